@@ -1,0 +1,135 @@
+/*
+ * CPU oracle for the fused tile kernel  Y = GELU_erf(A.B + bias).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU kernels are checked against.  It is single-threaded, has no blocking,
+ * no SIMD intrinsics and no BLAS, and shares no code, header, table or helper
+ * with the HIP library.  Only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg may call it; the product never does.
+ *
+ * What is computed (the kernel is the tile-level kernel that the paper's
+ * profile -> analyse -> transform -> evaluate loop of Sec. 3.3 / Algorithm 1
+ * treats as its input K; its arithmetic is fixed by the workload definition,
+ * not by the paper, which prints no formula for it):
+ *
+ *   z[m,n] = sum_{k=0}^{K-1} a[m,k] * b[k,n] + bias[n]
+ *   y[m,n] = GELU(z) = 1/2 * z * (1 + erf(z / sqrt 2))
+ *   s[m,n] = sum_k |a[m,k] * b[k,n]| + |bias[n]|      (for a-priori error bounds)
+ *
+ * a, b, bias are the exact real values of the bf16 bit patterns handed in.
+ * All arithmetic is IEEE double: a product of two bf16 values has at most 16
+ * significand bits and is exact in double, so only the running sum rounds.
+ * Layouts are row-major with leading dimensions in elements: A[M,K] (lda),
+ * B[K,N] (ldb), bias[N]; outputs are dense M x N doubles (ld = N).
+ *
+ * Every function here is pinned by tests that do not call back into this file
+ * to produce the expected value: exact rational brute force on tiny inputs,
+ * closed-form GELU values x*Phi(x), the identity GELU(x) - GELU(-x) = x,
+ * identity / zero / ones / rank-1 operands, exact power-of-two scaling,
+ * integer-valued operands, and numpy's float64 matmul.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+#include <stdlib.h>
+
+/* bf16 is the upper half of an IEEE binary32: widen by appending 16 zero bits. */
+double tfo_bf16_to_double(uint16_t bits)
+{
+    uint32_t w = (uint32_t)bits << 16;
+    float f;
+    memcpy(&f, &w, sizeof f);
+    return (double)f;
+}
+
+/* Exact-erf GELU, x * Phi(x).  For negative x the factor (1 + erf) cancels, so
+ * the same quantity is written with erfc:  1 + erf(t) = erfc(-t). */
+double tfo_gelu(double z)
+{
+    const double inv_sqrt2 = 0.70710678118654752440;
+    if (z < 0.0)
+        return 0.5 * z * erfc(-z * inv_sqrt2);
+    return 0.5 * z * (1.0 + erf(z * inv_sqrt2));
+}
+
+/*
+ * Full problem.  Any of Y, Z, S may be NULL (not wanted).
+ * Returns 0, or -1 on a bad argument, -2 if the row buffers cannot be allocated.
+ * Loop order is i, k, j with one row of accumulators: still the plain triple
+ * loop, each z[m,n] is summed in increasing k.
+ */
+int tfo_gemm_bias_gelu(int M, int N, int K,
+                       const uint16_t *A, long lda,
+                       const uint16_t *B, long ldb,
+                       const uint16_t *bias,
+                       double *Y, double *Z, double *S)
+{
+    if (M < 0 || N < 0 || K < 0) return -1;
+    if (M == 0 || N == 0) return 0;
+    if ((K > 0 && (!A || !B)) || !bias) return -1;
+    if (lda < K || ldb < N) return -1;
+
+    double *acc = (double *)malloc(sizeof(double) * (size_t)N);
+    double *abs_acc = (double *)malloc(sizeof(double) * (size_t)N);
+    if (!acc || !abs_acc) { free(acc); free(abs_acc); return -2; }
+
+    for (int m = 0; m < M; ++m) {
+        for (int n = 0; n < N; ++n) { acc[n] = 0.0; abs_acc[n] = 0.0; }
+        for (int k = 0; k < K; ++k) {
+            const double a = tfo_bf16_to_double(A[(size_t)m * (size_t)lda + (size_t)k]);
+            const uint16_t *brow = B + (size_t)k * (size_t)ldb;
+            for (int n = 0; n < N; ++n) {
+                const double p = a * tfo_bf16_to_double(brow[n]);
+                acc[n] += p;
+                abs_acc[n] += fabs(p);
+            }
+        }
+        for (int n = 0; n < N; ++n) {
+            const double bv = tfo_bf16_to_double(bias[n]);
+            const double z = acc[n] + bv;
+            const size_t o = (size_t)m * (size_t)N + (size_t)n;
+            if (Z) Z[o] = z;
+            if (Y) Y[o] = tfo_gelu(z);
+            if (S) S[o] = abs_acc[n] + fabs(bv);
+        }
+    }
+    free(acc);
+    free(abs_acc);
+    return 0;
+}
+
+/*
+ * Selected outputs only: for each t < count, the element (rows[t], cols[t]),
+ * written out as the dot product of one row of A with one column of B.
+ * Used where the whole problem is too large to evaluate on the host.
+ */
+int tfo_gemm_bias_gelu_at(int M, int N, int K,
+                          const uint16_t *A, long lda,
+                          const uint16_t *B, long ldb,
+                          const uint16_t *bias,
+                          long count, const int *rows, const int *cols,
+                          double *y, double *z, double *s)
+{
+    if (M < 0 || N < 0 || K < 0 || count < 0) return -1;
+    if (count > 0 && (!rows || !cols || !bias)) return -1;
+    if (K > 0 && count > 0 && (!A || !B)) return -1;
+    if (lda < K || ldb < N) return -1;
+    for (long t = 0; t < count; ++t) {
+        const int m = rows[t], n = cols[t];
+        if (m < 0 || m >= M || n < 0 || n >= N) return -1;
+        double acc = 0.0, abs_acc = 0.0;
+        for (int k = 0; k < K; ++k) {
+            const double p = tfo_bf16_to_double(A[(size_t)m * (size_t)lda + (size_t)k]) *
+                             tfo_bf16_to_double(B[(size_t)k * (size_t)ldb + (size_t)n]);
+            acc += p;
+            abs_acc += fabs(p);
+        }
+        const double bv = tfo_bf16_to_double(bias[n]);
+        const double zz = acc + bv;
+        if (z) z[t] = zz;
+        if (y) y[t] = tfo_gelu(zz);
+        if (s) s[t] = abs_acc + fabs(bv);
+    }
+    return 0;
+}
