@@ -1,0 +1,243 @@
+/*
+ * tf.h -- C boundary of libtf_gfx950.so
+ *
+ * A family of hand-written gfx950 (MI355X) kernels for the tile kernel
+ *
+ *      Y = GELU_erf(A . B + bias)          A[M,K], B[K,N], bias[N], Y[M,N], bf16, fp32 accumulate
+ *
+ * and the profiling-guided variant loop of the paper (Sec. 3.3, Algorithm 1) over that
+ * family.  The paper's objects map as follows:
+ *   hardware profile H ............ tf_hw            (tf_hw_query)
+ *   kernel K, candidates K' ....... tf_variant_desc  (tf_variant_enumerate; id 0 is the baseline kernel)
+ *   BuildRun(K') .................. tf_variant_run   (a non-OK status is the paper's "res = fail")
+ *   Profile(K') -> R' ............. tf_variant_profile (Sec. 3.4 "Profiling": warm-up + timed iterations
+ *                                   bracketed by events and a synchronisation)
+ *   Arbiter, RefineHint, Proposal . tf_arbiter, tf_refine_hint, tf_proposal (host only, no GPU needed)
+ *   the whole loop ................ tf_tune
+ *
+ * Conventions
+ *   - C linkage, no exceptions cross the boundary; functions return a tf_status
+ *     (0 = ok, negative = error; nothing is launched on error) unless stated otherwise.
+ *     tf_last_error() gives a thread-local message for the last failure.
+ *   - "device pointer" = address in the memory of the GPU the problem was created for; the
+ *     caller owns every buffer and the stream.  "host pointer" = ordinary process memory.
+ *   - bf16 tensors are raw uint16_t bit patterns, row-major, leading dimensions in elements.
+ *   - A kernel launch is asynchronous on the given stream; tf_variant_profile and tf_tune
+ *     synchronise that stream before they return.
+ *   - There is no CPU fallback: without a GPU every launching call fails with TF_E_LAUNCH.
+ */
+#ifndef TF_H_
+#define TF_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TF_OK = 0,
+  TF_E_INVALID = -1,      /* bad argument (null pointer, negative size, unknown id ...) */
+  TF_E_UNSUPPORTED = -2,  /* the variant cannot run this problem (shape, alignment, LDS, workspace) */
+  TF_E_LAUNCH = -3,       /* HIP reported an error (no device, launch failure ...) */
+  TF_E_NOMEM = -4,        /* host or device allocation failed */
+  TF_E_RANGE = -5,        /* output capacity too small */
+  TF_E_PROFILER = -6      /* counter file missing or not parseable */
+} tf_status;
+
+typedef enum {
+  TF_EPI_BIAS_GELU_ERF = 0, /* Y (bf16) = round_nearest_even(GELU_erf(A.B + bias))                  */
+  TF_EPI_NONE_F32 = 1       /* Y (float) = A.B + bias, the fp32 pre-activation; used by exactness tests */
+} tf_epilogue;
+
+typedef enum {
+  TF_KIND_NAIVE = 0,        /* one thread per output element, scalar FMA loop: the baseline kernel K */
+  TF_KIND_MFMA_DIRECT = 1,  /* one wave per 32x32 tile, MFMA operands loaded straight from memory     */
+  TF_KIND_MFMA_LDS = 2      /* LDS-staged, multi-buffered, swizzled MFMA tile kernel                  */
+} tf_kind;
+
+/* Bottleneck classes produced by tf_refine_hint (Sec. 3.3 "Targeted-Refinement-Hint":
+ * profiler deltas become a direction for the next proposal). */
+typedef enum {
+  TF_BN_UNKNOWN = 0,
+  TF_BN_UNDERFILLED = 1,   /* fewer work-groups than compute units, or a badly quantised last wave  */
+  TF_BN_HBM = 2,           /* memory traffic near the HBM roof on a shape below the ridge point      */
+  TF_BN_MFMA = 3,          /* matrix pipes busy: nothing left but quantisation                       */
+  TF_BN_LDS_CONFLICT = 4,  /* LDS bank conflicts above the threshold                                  */
+  TF_BN_OCCUPANCY = 5,     /* resident waves limited by registers / LDS                               */
+  TF_BN_LATENCY = 6        /* nothing saturated: stalls on staging, needs deeper buffering            */
+} tf_bottleneck;
+
+typedef enum { TF_DEC_CONTINUE = 0, TF_DEC_ACCEPT = 1, TF_DEC_FINISH = 2 } tf_decision;
+
+/* The problem: shapes and strides of one call of the tile kernel. */
+typedef struct {
+  int32_t M, N, K;
+  int64_t lda, ldb, ldy;   /* leading dimensions in elements; lda >= K, ldb >= N, ldy >= N */
+  int32_t epi;             /* tf_epilogue */
+  int32_t device;          /* HIP device ordinal */
+} tf_problem_desc;
+
+/* One member of the kernel family: the paper's "tiling/block shapes, num_warps, vectorization
+ * width, memory layout, prefetching, loop splitting" axes (Sec. 3.3, Initialization-and-Proposal). */
+typedef struct {
+  int32_t id;              /* index for tf_variant_run; 0 is always the naive baseline */
+  int32_t kind;            /* tf_kind */
+  int32_t bm, bn, bk;      /* macro tile */
+  int32_t waves_m, waves_n;/* wave grid inside the work-group (64-lane waves) */
+  int32_t stages;          /* LDS buffers in the ring */
+  int32_t split_k;         /* K slices reduced in fp32, in slice order, by the last slice to arrive */
+  int32_t direct_to_lds;   /* 1: global_load_lds staging; 0: via registers (allows a ragged K tail) */
+  int32_t xcd_swizzle;     /* 1: work-group ids renumbered so that neighbouring tiles share an XCD L2 */
+  int32_t group_m;         /* tile rows per group in the tile order */
+  int32_t threads;         /* work-group size */
+  int32_t lds_bytes;       /* LDS per work-group */
+  int32_t grid;            /* work-groups launched for this problem */
+  int64_t workspace_bytes; /* device workspace tf_variant_run needs (0 if none) */
+  char name[64];
+} tf_variant_desc;
+
+/* The profiler report R of the paper for one variant on one problem. */
+typedef struct {
+  int32_t variant_id;
+  int32_t status;                /* tf_status of the run; timing fields are valid only for TF_OK */
+  int32_t warmup, iters, launches_per_iter;
+  double t_min_us, t_med_us, t_mean_us, t_max_us;   /* per launch */
+  double tflops, gbytes_per_s;   /* from the algorithmic flops 2MNK and bytes 2(MK + KN + MN + N) */
+  double pct_mfma_peak, pct_hbm_peak;
+  double arithmetic_intensity;   /* algorithmic flop per byte of the problem */
+  int32_t grid, waves_per_simd;  /* launch size; resident waves per SIMD allowed by registers and LDS */
+  int32_t vgprs, agprs, sgprs, spill_bytes, lds_bytes;
+  double occupancy_pct;          /* waves_per_simd / 8 */
+  double grid_fill;              /* grid / (compute units * resident work-groups per CU), tail included */
+  int32_t have_counters;         /* 1 once tf_report_set_counters has filled the next five fields */
+  double mfma_busy_pct, lds_bank_conflict_pct, hbm_read_gbs, hbm_write_gbs, l2_hit_pct;
+  int32_t bottleneck;            /* tf_bottleneck, filled by tf_refine_hint / tf_tune */
+  int32_t parity_ok;             /* set by the caller's correctness gate; tf_tune takes it from its callback */
+} tf_report;
+
+/* Hardware profile H. */
+typedef struct {
+  char name[64];
+  int32_t cus, simds_per_cu, wave_size, xcds;
+  int32_t lds_bytes_per_cu, vgprs_per_simd_lane, max_waves_per_simd;
+  int64_t l2_bytes, hbm_bytes;
+  double clock_mhz, hbm_gbs_peak, bf16_tflops_peak;
+} tf_hw;
+
+/* Arbiter thresholds (the paper's Theta; it names the criteria, the values are this library's). */
+typedef struct {
+  double first_accept_speedup;  /* a candidate replaces the baseline only at >= this speedup (1.05) */
+  double later_accept_gain;     /* ... and a previously accepted best at >= this (1.02)              */
+  double robust_spread;         /* reject timings whose (median - min) / median exceeds this (0.10) */
+  int32_t patience;             /* finish after this many consecutive rounds without an accept (4)  */
+  int32_t max_rounds;           /* hard cap on optimisation rounds (8)                               */
+} tf_theta;
+
+typedef struct tf_problem tf_problem;   /* opaque; created and destroyed by the library */
+
+/* Fills *out with the library defaults for Theta. */
+void tf_theta_default(tf_theta* out);
+
+/* H of device `device` (host pointer out). */
+tf_status tf_hw_query(int32_t device, tf_hw* out);
+/* Same structure without touching a GPU: the published MI355X figures. */
+void tf_hw_nominal(tf_hw* out);
+
+/* Validates desc (host pointer) and creates the problem. M, N, K >= 0. */
+tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem** out);
+void tf_problem_destroy(tf_problem* p);
+
+/* Lists the variants that can run this problem (shape, alignment and LDS limits checked).
+ * out may be NULL to ask for the count. Returns the count (>= 1), or a negative tf_status;
+ * TF_E_RANGE if cap is too small. Needs no GPU. */
+int32_t tf_variant_enumerate(const tf_problem* p, tf_variant_desc* out, int32_t cap);
+
+/* BuildRun: launches variant `variant_id` on `hip_stream` (a hipStream_t, may be NULL for the
+ * default stream). A, B, bias, Y: device pointers (Y: bf16 or float per desc.epi).
+ * workspace: device pointer of at least the variant's workspace_bytes, or NULL to let the
+ * library use a buffer it allocates once per problem and keeps until tf_problem_destroy.
+ * The first use of a workspace is preceded by one fill kernel that zeroes its counters; the
+ * kernels leave the counters zero. Calls that share a workspace must not overlap. */
+tf_status tf_variant_run(tf_problem* p, int32_t variant_id, const void* A, const void* B,
+                         const void* bias, void* Y, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
+/* Profile: `warmup` untimed iterations, then `iters` timed ones; each iteration brackets
+ * `launches_per_iter` back-to-back launches (0 = pick so that an iteration lasts >= ~1 ms)
+ * between two events on the stream and synchronises. Fills *out (host pointer), including the
+ * static resource figures. Synchronous. */
+tf_status tf_variant_profile(tf_problem* p, int32_t variant_id, const void* A, const void* B,
+                             const void* bias, void* Y, void* workspace, size_t workspace_bytes,
+                             void* hip_stream, int32_t warmup, int32_t iters,
+                             int32_t launches_per_iter, tf_report* out);
+
+/* Reads a rocprofv3 counter CSV (columns Kernel_Name, Counter_Name, Counter_Value) and fills the
+ * counter fields of *r from the rows whose kernel name contains `kernel_substr`. */
+tf_status tf_report_set_counters(tf_report* r, const tf_hw* hw, const char* csv_path,
+                                 const char* kernel_substr);
+
+/* ---- the loop's host logic: pure functions, callable without a GPU ---------------------- */
+
+/* Performance-Arbiter: decision for candidate report `cand` against best-so-far `best`.
+ * best_is_baseline != 0 while nothing has been accepted yet; stall_rounds = consecutive
+ * rounds without an accept before this one; round = 1-based index of this round. */
+int32_t tf_arbiter(const tf_report* cand, const tf_report* best, const tf_theta* theta,
+                   int32_t best_is_baseline, int32_t stall_rounds, int32_t round);
+
+/* Targeted-Refinement-Hint: classifies the bottleneck of `cand` (tf_bottleneck). `prev` may be
+ * NULL. */
+int32_t tf_refine_hint(const tf_report* prev, const tf_report* cand, const tf_hw* hw);
+
+/* Proposal: id of the next candidate among family[0..n), none of which has tried[id] != 0,
+ * given the current kernel `base_id` and its bottleneck class; -1 when the family is
+ * exhausted. prob gives the shape. */
+int32_t tf_proposal(const tf_problem_desc* prob, const tf_hw* hw, const tf_variant_desc* family,
+                    int32_t n, const uint8_t* tried, int32_t base_id, int32_t bottleneck);
+
+/* Proposal given the family's predicted times (predicted_us[i] for family[i]): among the
+ * untried tile kernels that move in the direction the bottleneck asks for, relative to
+ * family[base_id], the one with the smallest predicted time; if none qualifies (or the base is
+ * not a tile kernel, or the class is TF_BN_UNKNOWN) the untried variant with the smallest
+ * predicted time; -1 if every variant has been tried. Ties go to the lower id. */
+int32_t tf_proposal_from(const tf_hw* hw, const tf_variant_desc* family, const double* predicted_us,
+                         int32_t n, const uint8_t* tried, int32_t base_id, int32_t bottleneck);
+
+/* Static cost model behind tf_proposal: predicted time in microseconds of variant v on the
+ * problem, from tile shape, wave quantisation and the measured LDS / load-path rates. */
+double tf_predict_us(const tf_problem_desc* prob, const tf_hw* hw, const tf_variant_desc* v);
+/* Work-groups of v that fit on one compute unit (registers and LDS), 1..8. */
+int32_t tf_resident_wgs(const tf_hw* hw, const tf_variant_desc* v);
+/* v->grid / (rounds * cus * resident work-groups): 1.0 when the last round is full. */
+double tf_grid_fill(const tf_hw* hw, const tf_variant_desc* v);
+
+/* Algorithm 1 over pre-made reports: reports[i] is what Profile would return for family[i]
+ * (reports[0] the baseline). Same outputs as tf_tune; needs no GPU. */
+tf_status tf_tune_replay(const tf_problem_desc* prob, const tf_hw* hw, const tf_variant_desc* family,
+                         const tf_report* reports, int32_t n, const tf_theta* theta,
+                         int32_t* best_variant, tf_report* best, tf_report* round_log,
+                         int32_t log_cap, int32_t* n_log);
+
+/* Correctness gate used by tf_tune after each BuildRun (the paper verifies functional
+ * equivalence of every candidate before its time counts). Returns non-zero if Y is accepted. */
+typedef int32_t (*tf_parity_fn)(void* user, int32_t variant_id);
+
+/* Algorithm 1. Profiles the baseline (variant 0), then runs at most theta->max_rounds rounds of
+ * Proposal -> BuildRun -> parity gate -> Profile -> Arbiter -> RefineHint. round_log (host
+ * pointer, capacity log_cap >= 1 + max_rounds) receives the baseline report followed by one
+ * report per round; *n_log their number. *best_variant / *best get K* and R*. parity may be
+ * NULL (every candidate is then taken as correct). */
+tf_status tf_tune(tf_problem* p, const void* A, const void* B, const void* bias, void* Y,
+                  void* workspace, size_t workspace_bytes, void* hip_stream,
+                  const tf_theta* theta, tf_parity_fn parity, void* parity_user,
+                  int32_t* best_variant, tf_report* best, tf_report* round_log, int32_t log_cap,
+                  int32_t* n_log);
+
+const char* tf_last_error(void);
+const char* tf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TF_H_ */

@@ -1,0 +1,585 @@
+// The C boundary: problem objects, variant enumeration, BuildRun, Profile, counter ingest
+// and the GPU-driven instance of the variant loop.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <string>
+#include <vector>
+
+#include "tf_device.h"
+#include "tf_loop.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+tf_status fail(tf_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+#define TF_HIP(call)                                                                      \
+  do {                                                                                    \
+    hipError_t e_ = (call);                                                               \
+    if (e_ != hipSuccess) return fail(TF_E_LAUNCH, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+struct VariantImpl {
+  int lds_index;   // index into tf::lds_kernel_table(), -1 for the unstaged kernels
+  int ktiles_per_split;
+  int tiles_m, tiles_n;
+  size_t counter_bytes;   // leading part of the workspace
+};
+
+}  // namespace
+
+struct tf_problem {
+  tf_problem_desc desc;
+  tf_hw hw;
+  bool have_hw;
+  std::vector<tf_variant_desc> family;
+  std::vector<VariantImpl> impl;
+  void* own_ws;
+  size_t own_ws_bytes;
+  void* zeroed_ws;        // workspace whose counters are known to be zero
+  size_t zeroed_bytes;
+  std::vector<char> attr_done;   // per LDS kernel: dynamic-LDS attribute set on this device
+};
+
+namespace {
+
+long cdivl(long a, long b) { return (a + b - 1) / b; }
+
+// ---------------------------------------------------------------- family
+void add_variant(tf_problem* p, const tf_variant_desc& v, const VariantImpl& im) {
+  tf_variant_desc d = v;
+  d.id = (int32_t)p->family.size();
+  p->family.push_back(d);
+  p->impl.push_back(im);
+}
+
+void build_family(tf_problem* p) {
+  const tf_problem_desc& d = p->desc;
+  p->family.clear();
+  p->impl.clear();
+  {
+    tf_variant_desc v;
+    memset(&v, 0, sizeof(v));
+    v.kind = TF_KIND_NAIVE; v.bm = 4; v.bn = 64; v.bk = 1; v.waves_m = 4; v.waves_n = 1; v.stages = 0;
+    v.split_k = 1; v.threads = 256; v.group_m = 1;
+    v.grid = (int32_t)(cdivl(d.N, 64) * cdivl(d.M, 4));
+    snprintf(v.name, sizeof(v.name), "naive_1elem_per_thread");
+    add_variant(p, v, VariantImpl{-1, 0, 0, 0, 0});
+  }
+  if (d.M > 0 && d.N > 0) {
+    tf_variant_desc v;
+    memset(&v, 0, sizeof(v));
+    v.kind = TF_KIND_MFMA_DIRECT; v.bm = 32; v.bn = 32; v.bk = 16; v.waves_m = 1; v.waves_n = 1;
+    v.split_k = 1; v.threads = 64; v.group_m = 1;
+    v.grid = (int32_t)(cdivl(d.N, 32) * cdivl(d.M, 32));
+    snprintf(v.name, sizeof(v.name), "mfma32_direct_1wave");
+    add_variant(p, v, VariantImpl{-1, 0, 0, 0, 0});
+  }
+  // LDS-staged tile kernels: 16-byte chunks must not straddle a row end, and tile-relative
+  // byte offsets are kept in 32 bits.
+  const bool aligned = d.M > 0 && d.N >= 8 && d.K >= 8 && d.K % 8 == 0 && d.N % 8 == 0 && d.lda % 8 == 0 &&
+                       d.ldb % 8 == 0 && d.ldy % 8 == 0 &&
+                       (double)d.M * (double)d.lda * 2.0 < 4294967296.0 &&
+                       (double)d.K * (double)d.ldb * 2.0 < 4294967296.0;
+  if (!aligned) return;
+  const int cus = p->hw.cus > 0 ? p->hw.cus : 256;
+  const tf::LdsKernelInfo* tab = tf::lds_kernel_table();
+  const long ktiles = cdivl(d.K, 64);
+  for (int i = 0; i < tf::lds_kernel_count(); ++i) {
+    const tf::LdsKernelInfo& k = tab[i];
+    if (k.direct_to_lds && d.K % 64 != 0) continue;        // no zero fill on the direct path
+    if (k.bm > 32 && k.bm / 2 >= d.M) continue;            // tile more than twice the problem
+    if (k.bn > 64 && k.bn / 2 >= d.N) continue;
+    if (k.lds_bytes > p->hw.lds_bytes_per_cu) continue;
+    const long tm = cdivl(d.M, k.bm), tn = cdivl(d.N, k.bn);
+    if (tm * tn > 0x7fffffffL / 16) continue;
+    static const int splits[] = {1, 2, 4, 8, 16};
+    for (int s : splits) {
+      if (s > 1 && (ktiles / s < 4 || tm * tn >= 2L * cus)) continue;
+      const long per = cdivl(ktiles, s);
+      if (s > 1 && per * (s - 1) >= ktiles) continue;      // would leave an empty slice
+      tf_variant_desc v;
+      memset(&v, 0, sizeof(v));
+      v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n;
+      v.stages = k.stages; v.split_k = s; v.direct_to_lds = k.direct_to_lds; v.xcd_swizzle = 1;
+      v.group_m = (int32_t)std::min<long>(tm, 8);
+      v.threads = k.threads; v.lds_bytes = k.lds_bytes;
+      v.grid = (int32_t)(tm * tn * s);
+      VariantImpl im;
+      im.lds_index = i; im.ktiles_per_split = (int)per; im.tiles_m = (int)tm; im.tiles_n = (int)tn;
+      im.counter_bytes = s > 1 ? (size_t)((tm * tn * 4 + 255) / 256 * 256) : 0;
+      v.workspace_bytes = s > 1 ? (int64_t)(im.counter_bytes + (size_t)s * d.M * d.N * 4) : 0;
+      snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d_s%d_%s_sk%d", k.bm, k.bn, k.bk, k.waves_m, k.waves_n,
+               k.stages, k.direct_to_lds ? "direct" : "regs", s);
+      add_variant(p, v, im);
+    }
+  }
+}
+
+// ---------------------------------------------------------------- launch
+tf_status check_ptrs(const tf_problem* p, const tf_variant_desc& v, const void* A, const void* B, const void* bias,
+                     void* Y) {
+  const tf_problem_desc& d = p->desc;
+  if (d.M == 0 || d.N == 0) return TF_OK;
+  if (!Y || !bias) return fail(TF_E_INVALID, "null Y or bias pointer");
+  if (d.K > 0 && (!A || !B)) return fail(TF_E_INVALID, "null A or B pointer");
+  if (v.kind == TF_KIND_MFMA_LDS) {
+    if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)Y) & 15u || ((uintptr_t)bias & 7u))
+      return fail(TF_E_UNSUPPORTED, "variant %s needs 16-byte aligned A, B, Y and 8-byte aligned bias", v.name);
+  }
+  return TF_OK;
+}
+
+tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const void* bias, void* Y, void* ws,
+                    size_t ws_bytes, hipStream_t stream) {
+  const tf_problem_desc& d = p->desc;
+  const tf_variant_desc& v = p->family[id];
+  const VariantImpl& im = p->impl[id];
+  tf_status st = check_ptrs(p, v, A, B, bias, Y);
+  if (st != TF_OK) return st;
+  if (d.M == 0 || d.N == 0) return TF_OK;   // nothing to compute
+  tf::GemmParams g;
+  memset(&g, 0, sizeof(g));
+  g.A = (const uint16_t*)A; g.B = (const uint16_t*)B; g.bias = (const uint16_t*)bias; g.Y = Y;
+  g.M = d.M; g.N = d.N; g.K = d.K; g.lda = d.lda; g.ldb = d.ldb; g.ldy = d.ldy;
+  g.epi = d.epi; g.split_k = v.split_k; g.group_m = v.group_m > 0 ? v.group_m : 1; g.xcd_swizzle = v.xcd_swizzle;
+  if (v.kind == TF_KIND_NAIVE) {
+    if (cdivl(d.M, 4) > 65535) return fail(TF_E_UNSUPPORTED, "naive variant: M too large for the grid");
+    tf::launch_naive(g, stream);
+  } else if (v.kind == TF_KIND_MFMA_DIRECT) {
+    if (cdivl(d.M, 32) > 65535) return fail(TF_E_UNSUPPORTED, "mfma_direct variant: M too large for the grid");
+    tf::launch_mfma_direct(g, stream);
+  } else {
+    const tf::LdsKernelInfo& k = tf::lds_kernel_table()[im.lds_index];
+    g.tiles_m = im.tiles_m; g.tiles_n = im.tiles_n; g.ktiles_per_split = im.ktiles_per_split;
+    if (v.split_k > 1) {
+      if (!ws) {
+        if (p->own_ws_bytes < (size_t)v.workspace_bytes) {
+          if (p->own_ws) { (void)hipFree(p->own_ws); p->own_ws = nullptr; p->own_ws_bytes = 0; }
+          size_t need = 0;
+          for (const tf_variant_desc& f : p->family) need = std::max(need, (size_t)f.workspace_bytes);
+          if (hipMalloc(&p->own_ws, need) != hipSuccess) {
+            p->own_ws = nullptr;
+            return fail(TF_E_NOMEM, "cannot allocate %zu bytes of split-K workspace", need);
+          }
+          p->own_ws_bytes = need;
+        }
+        ws = p->own_ws; ws_bytes = p->own_ws_bytes;
+      }
+      if (ws_bytes < (size_t)v.workspace_bytes)
+        return fail(TF_E_UNSUPPORTED, "workspace of %zu bytes, variant %s needs %lld", ws_bytes, v.name,
+                    (long long)v.workspace_bytes);
+      if ((uintptr_t)ws & 255u) return fail(TF_E_UNSUPPORTED, "workspace must be 256-byte aligned");
+      if (p->zeroed_ws != ws || p->zeroed_bytes < im.counter_bytes) {
+        // the counters of a workspace seen for the first time may hold anything
+        size_t maxc = 0;
+        for (const VariantImpl& o : p->impl) maxc = std::max(maxc, o.counter_bytes);
+        maxc = std::min(maxc, ws_bytes);
+        tf::launch_fill_u32((unsigned*)ws, maxc / 4, 0u, stream);
+        p->zeroed_ws = ws; p->zeroed_bytes = maxc;
+      }
+      g.counters = (unsigned*)ws;
+      g.ws = (float*)((char*)ws + im.counter_bytes);
+    }
+    if (!p->attr_done[im.lds_index]) {
+      TF_HIP(hipFuncSetAttribute(k.func, hipFuncAttributeMaxDynamicSharedMemorySize, k.lds_bytes));
+      p->attr_done[im.lds_index] = 1;
+    }
+    k.launch(g, dim3((unsigned)v.grid), stream);
+  }
+  TF_HIP(hipGetLastError());
+  return TF_OK;
+}
+
+// ---------------------------------------------------------------- static resource figures
+void fill_static(tf_problem* p, int id, tf_report* r) {
+  const tf_variant_desc& v = p->family[id];
+  const void* func = nullptr;
+  int dyn = 0;
+  if (v.kind == TF_KIND_NAIVE) func = tf::naive_func();
+  else if (v.kind == TF_KIND_MFMA_DIRECT) func = tf::mfma_direct_func();
+  else { func = tf::lds_kernel_table()[p->impl[id].lds_index].func; dyn = v.lds_bytes; }
+  hipFuncAttributes a;
+  memset(&a, 0, sizeof(a));
+  if (hipFuncGetAttributes(&a, func) == hipSuccess) {
+    r->vgprs = a.numRegs;
+    r->spill_bytes = (int32_t)a.localSizeBytes;
+    r->lds_bytes = (int32_t)a.sharedSizeBytes + dyn;
+  }
+  int blocks = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, func, v.threads, dyn) != hipSuccess || blocks < 1) blocks = 1;
+  const int waves = blocks * (v.threads / 64);
+  int wps = (waves + p->hw.simds_per_cu - 1) / p->hw.simds_per_cu;
+  if (wps > p->hw.max_waves_per_simd) wps = p->hw.max_waves_per_simd;
+  r->waves_per_simd = wps;
+  r->occupancy_pct = 100.0 * wps / p->hw.max_waves_per_simd;
+  const long slots = (long)p->hw.cus * blocks;
+  r->grid = v.grid;
+  r->grid_fill = v.grid > 0 ? (double)v.grid / (double)(cdivl(v.grid, slots) * slots) : 0.0;
+}
+
+// ---------------------------------------------------------------- built-in parity gate
+// A candidate is accepted only if its output matches the baseline kernel's output on the
+// same inputs (the paper checks functional equivalence of every variant before timing it).
+template <typename T>
+__global__ void compare_kernel(const T* y, const T* ref, size_t rows, int n, long ldy, unsigned* bad) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * (size_t)n) return;
+  const size_t m = i / n, c = i % n;
+  float a, b;
+  if (sizeof(T) == 2) {
+    a = tf::bf16_bits_to_f32((uint16_t)y[m * ldy + c]);
+    b = tf::bf16_bits_to_f32((uint16_t)ref[m * ldy + c]);
+  } else {
+    a = (float)y[m * ldy + c];
+    b = (float)ref[m * ldy + c];
+  }
+  const bool ok = fabsf(a - b) <= 1e-2f * (1.0f + fabsf(b));   // also false for NaN
+  if (!ok) atomicAdd(bad, 1u);
+}
+
+struct TuneCtx {
+  tf_problem* p;
+  const void *A, *B, *bias;
+  void* Y;
+  void* ws;
+  size_t ws_bytes;
+  hipStream_t stream;
+  tf_parity_fn parity;
+  void* parity_user;
+  void* yref;        // baseline output
+  unsigned* bad;     // device counter
+  size_t ybytes;
+};
+
+tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, const void* bias, void* Y, void* ws,
+                       size_t ws_bytes, hipStream_t stream, int warmup, int iters, int lpi, tf_report* out);
+
+tf_status tune_profile(void* user, int32_t id, tf_report* out) {
+  TuneCtx* c = (TuneCtx*)user;
+  tf_problem* p = c->p;
+  memset(out, 0, sizeof(*out));
+  out->variant_id = id;
+  tf_status st = do_launch(p, id, c->A, c->B, c->bias, c->Y, c->ws, c->ws_bytes, c->stream);
+  if (st != TF_OK) { out->status = st; return TF_OK; }   // BuildRun failed: recorded, the loop goes on
+  TF_HIP(hipStreamSynchronize(c->stream));
+  int ok = 1;
+  if (c->parity) ok = c->parity(c->parity_user, id) != 0;
+  else if (id == 0) { TF_HIP(hipMemcpyAsync(c->yref, c->Y, c->ybytes, hipMemcpyDeviceToDevice, c->stream)); }
+  else if (p->desc.M > 0 && p->desc.N > 0) {
+    tf::launch_fill_u32(c->bad, 1, 0u, c->stream);
+    const size_t total = (size_t)p->desc.M * p->desc.N;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    if (p->desc.epi == TF_EPI_NONE_F32)
+      hipLaunchKernelGGL(compare_kernel<float>, dim3(blocks), dim3(256), 0, c->stream, (const float*)c->Y,
+                         (const float*)c->yref, (size_t)p->desc.M, p->desc.N, (long)p->desc.ldy, c->bad);
+    else
+      hipLaunchKernelGGL(compare_kernel<uint16_t>, dim3(blocks), dim3(256), 0, c->stream, (const uint16_t*)c->Y,
+                         (const uint16_t*)c->yref, (size_t)p->desc.M, p->desc.N, (long)p->desc.ldy, c->bad);
+    unsigned bad = 0;
+    TF_HIP(hipMemcpyAsync(&bad, c->bad, 4, hipMemcpyDeviceToHost, c->stream));
+    TF_HIP(hipStreamSynchronize(c->stream));
+    ok = bad == 0;
+  }
+  st = profile_impl(p, id, c->A, c->B, c->bias, c->Y, c->ws, c->ws_bytes, c->stream, 3, 5, 0, out);
+  if (st != TF_OK) { out->status = st; return TF_OK; }
+  out->parity_ok = ok;
+  return TF_OK;
+}
+
+double median(std::vector<double> v) {
+  std::sort(v.begin(), v.end());
+  const size_t n = v.size();
+  return n % 2 ? v[n / 2] : 0.5 * (v[n / 2 - 1] + v[n / 2]);
+}
+
+tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, const void* bias, void* Y, void* ws,
+                       size_t ws_bytes, hipStream_t stream, int warmup, int iters, int lpi, tf_report* out) {
+  memset(out, 0, sizeof(*out));
+  out->variant_id = id;
+  if (warmup < 0 || iters < 1 || lpi < 0) return fail(TF_E_INVALID, "warmup >= 0, iters >= 1, launches_per_iter >= 0");
+  hipEvent_t e0, e1;
+  TF_HIP(hipEventCreate(&e0));
+  TF_HIP(hipEventCreate(&e1));
+  tf_status st = TF_OK;
+  auto timed = [&](int launches, double* us) -> tf_status {
+    if (hipEventRecord(e0, stream) != hipSuccess) return fail(TF_E_LAUNCH, "hipEventRecord failed");
+    for (int l = 0; l < launches; ++l) {
+      tf_status s2 = do_launch(p, id, A, B, bias, Y, ws, ws_bytes, stream);
+      if (s2 != TF_OK) return s2;
+    }
+    if (hipEventRecord(e1, stream) != hipSuccess) return fail(TF_E_LAUNCH, "hipEventRecord failed");
+    if (hipEventSynchronize(e1) != hipSuccess) return fail(TF_E_LAUNCH, "hipEventSynchronize failed");
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return fail(TF_E_LAUNCH, "hipEventElapsedTime failed");
+    *us = 1e3 * ms / launches;
+    return TF_OK;
+  };
+  double t = 0.0;
+  for (int w = 0; w < warmup && st == TF_OK; ++w) st = timed(1, &t);
+  if (st == TF_OK && lpi == 0) {
+    st = timed(1, &t);
+    // batches of about a millisecond, so that one launch's overhead does not dominate short kernels
+    lpi = t > 0.0 ? (int)ceil(1000.0 / t) : 1000;
+    lpi = std::max(1, std::min(lpi, 2000));
+  }
+  std::vector<double> ts;
+  for (int i = 0; i < iters && st == TF_OK; ++i) {
+    st = timed(lpi, &t);
+    if (st == TF_OK) ts.push_back(t);
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  out->status = st;
+  if (st != TF_OK) return st;
+  out->warmup = warmup; out->iters = iters; out->launches_per_iter = lpi;
+  out->t_min_us = *std::min_element(ts.begin(), ts.end());
+  out->t_max_us = *std::max_element(ts.begin(), ts.end());
+  out->t_med_us = median(ts);
+  double sum = 0.0;
+  for (double x : ts) sum += x;
+  out->t_mean_us = sum / ts.size();
+  const tf_problem_desc& d = p->desc;
+  const double flops = 2.0 * d.M * (double)d.N * d.K;
+  const double bytes = 2.0 * ((double)d.M * d.K + (double)d.K * d.N + (double)d.M * d.N + d.N);
+  out->arithmetic_intensity = bytes > 0 ? flops / bytes : 0.0;
+  if (out->t_med_us > 0.0) {
+    out->tflops = flops / out->t_med_us * 1e-6;
+    out->gbytes_per_s = bytes / out->t_med_us * 1e-3;
+    out->pct_mfma_peak = 100.0 * out->tflops / p->hw.bf16_tflops_peak;
+    out->pct_hbm_peak = 100.0 * out->gbytes_per_s / p->hw.hbm_gbs_peak;
+  }
+  fill_static(p, id, out);
+  out->parity_ok = 0;
+  out->bottleneck = tf_refine_hint(nullptr, out, &p->hw);
+  return TF_OK;
+}
+
+// ---------------------------------------------------------------- CSV
+std::vector<std::string> split_csv(const std::string& line) {
+  std::vector<std::string> out;
+  std::string cur;
+  bool q = false;
+  for (size_t i = 0; i < line.size(); ++i) {
+    const char ch = line[i];
+    if (q) {
+      if (ch == '"') { if (i + 1 < line.size() && line[i + 1] == '"') { cur += '"'; ++i; } else q = false; }
+      else cur += ch;
+    } else if (ch == '"') q = true;
+    else if (ch == ',') { out.push_back(cur); cur.clear(); }
+    else if (ch != '\r' && ch != '\n') cur += ch;
+  }
+  out.push_back(cur);
+  return out;
+}
+
+}  // namespace
+
+// =================================================================== exported functions
+extern "C" const char* tf_last_error(void) { return g_err; }
+extern "C" const char* tf_version(void) { return "tf-gfx950 0.1"; }
+
+extern "C" tf_status tf_hw_query(int32_t device, tf_hw* out) {
+  if (!out) return fail(TF_E_INVALID, "null out");
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) return fail(TF_E_LAUNCH, "no HIP device");
+  if (device < 0 || device >= n) return fail(TF_E_INVALID, "device %d out of range (%d devices)", device, n);
+  hipDeviceProp_t pr;
+  TF_HIP(hipGetDeviceProperties(&pr, device));
+  tf_hw_nominal(out);
+  memset(out->name, 0, sizeof(out->name));
+  snprintf(out->name, sizeof(out->name), "%s %s", pr.name, pr.gcnArchName);
+  out->cus = pr.multiProcessorCount;
+  out->wave_size = pr.warpSize;
+  out->lds_bytes_per_cu = (int32_t)pr.sharedMemPerMultiprocessor;
+  out->l2_bytes = pr.l2CacheSize;
+  out->hbm_bytes = (int64_t)pr.totalGlobalMem;
+  out->clock_mhz = pr.clockRate / 1000.0;
+  // peaks: the published figures scaled to what the device reports
+  out->bf16_tflops_peak = out->cus * 4096.0 * out->clock_mhz * 1e6 / 1e12;
+  out->hbm_gbs_peak = 8000.0;
+  return TF_OK;
+}
+
+extern "C" tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem** out) {
+  if (!desc || !out) return fail(TF_E_INVALID, "null argument");
+  *out = nullptr;
+  if (desc->M < 0 || desc->N < 0 || desc->K < 0) return fail(TF_E_INVALID, "negative dimension");
+  if (desc->lda < desc->K || desc->ldb < desc->N || desc->ldy < desc->N)
+    return fail(TF_E_INVALID, "leading dimension smaller than the row length");
+  if (desc->epi != TF_EPI_BIAS_GELU_ERF && desc->epi != TF_EPI_NONE_F32) return fail(TF_E_INVALID, "unknown epilogue %d", desc->epi);
+  tf_problem* p = new (std::nothrow) tf_problem();
+  if (!p) return fail(TF_E_NOMEM, "out of host memory");
+  p->desc = *desc;
+  p->own_ws = nullptr; p->own_ws_bytes = 0; p->zeroed_ws = nullptr; p->zeroed_bytes = 0;
+  // H: from the device when there is one, otherwise the published figures (enumeration and the
+  // host-side loop logic work without a GPU; launching does not)
+  p->have_hw = tf_hw_query(desc->device, &p->hw) == TF_OK;
+  if (!p->have_hw) { tf_hw_nominal(&p->hw); g_err[0] = 0; }
+  p->attr_done.assign(tf::lds_kernel_count(), 0);
+  build_family(p);
+  *out = p;
+  return TF_OK;
+}
+
+extern "C" void tf_problem_destroy(tf_problem* p) {
+  if (!p) return;
+  if (p->own_ws) (void)hipFree(p->own_ws);
+  delete p;
+}
+
+extern "C" int32_t tf_variant_enumerate(const tf_problem* p, tf_variant_desc* out, int32_t cap) {
+  if (!p) return fail(TF_E_INVALID, "null problem");
+  const int32_t n = (int32_t)p->family.size();
+  if (!out) return n;
+  if (cap < n) return fail(TF_E_RANGE, "capacity %d < %d variants", cap, n);
+  memcpy(out, p->family.data(), sizeof(tf_variant_desc) * n);
+  return n;
+}
+
+static tf_status prepare(tf_problem* p, int32_t id) {
+  if (!p) return fail(TF_E_INVALID, "null problem");
+  if (id < 0 || id >= (int32_t)p->family.size()) return fail(TF_E_INVALID, "variant id %d out of range", id);
+  if (!p->have_hw) {
+    p->have_hw = tf_hw_query(p->desc.device, &p->hw) == TF_OK;
+    if (!p->have_hw) return fail(TF_E_LAUNCH, "no usable HIP device %d: %s", p->desc.device, g_err);
+  }
+  TF_HIP(hipSetDevice(p->desc.device));
+  return TF_OK;
+}
+
+extern "C" tf_status tf_variant_run(tf_problem* p, int32_t id, const void* A, const void* B, const void* bias,
+                                    void* Y, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  tf_status st = prepare(p, id);
+  if (st != TF_OK) return st;
+  return do_launch(p, id, A, B, bias, Y, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+extern "C" tf_status tf_variant_profile(tf_problem* p, int32_t id, const void* A, const void* B, const void* bias,
+                                        void* Y, void* workspace, size_t workspace_bytes, void* hip_stream,
+                                        int32_t warmup, int32_t iters, int32_t launches_per_iter, tf_report* out) {
+  if (!out) return fail(TF_E_INVALID, "null report");
+  tf_status st = prepare(p, id);
+  if (st != TF_OK) return st;
+  return profile_impl(p, id, A, B, bias, Y, workspace, workspace_bytes, (hipStream_t)hip_stream, warmup, iters,
+                      launches_per_iter, out);
+}
+
+extern "C" tf_status tf_report_set_counters(tf_report* r, const tf_hw* hw, const char* csv_path,
+                                            const char* kernel_substr) {
+  if (!r || !hw || !csv_path || !kernel_substr) return fail(TF_E_INVALID, "null argument");
+  FILE* f = fopen(csv_path, "r");
+  if (!f) return fail(TF_E_PROFILER, "cannot open %s", csv_path);
+  std::vector<char> buf(1 << 16);
+  int c_name = -1, c_ctr = -1, c_val = -1, c_disp = -1, c_t0 = -1, c_t1 = -1;
+  bool header = true;
+  struct Acc { double sum = 0; std::vector<long> dispatches; };
+  std::vector<std::pair<std::string, Acc>> accs;
+  auto acc_of = [&](const std::string& n) -> Acc& {
+    for (auto& a : accs) if (a.first == n) return a.second;
+    accs.push_back({n, Acc()});
+    return accs.back().second;
+  };
+  std::vector<long> all_disp;
+  double dur_ns = 0.0; long dur_n = 0;
+  while (fgets(buf.data(), (int)buf.size(), f)) {
+    std::vector<std::string> cols = split_csv(buf.data());
+    if (header) {
+      for (size_t i = 0; i < cols.size(); ++i) {
+        if (cols[i] == "Kernel_Name") c_name = (int)i;
+        else if (cols[i] == "Counter_Name") c_ctr = (int)i;
+        else if (cols[i] == "Counter_Value") c_val = (int)i;
+        else if (cols[i] == "Dispatch_Id") c_disp = (int)i;
+        else if (cols[i] == "Start_Timestamp") c_t0 = (int)i;
+        else if (cols[i] == "End_Timestamp") c_t1 = (int)i;
+      }
+      header = false;
+      if (c_name < 0 || c_ctr < 0 || c_val < 0) { fclose(f); return fail(TF_E_PROFILER, "%s: missing Kernel_Name / Counter_Name / Counter_Value column", csv_path); }
+      continue;
+    }
+    const int need = std::max(c_name, std::max(c_ctr, c_val));
+    if ((int)cols.size() <= need) continue;
+    if (cols[c_name].find(kernel_substr) == std::string::npos) continue;
+    Acc& a = acc_of(cols[c_ctr]);
+    a.sum += atof(cols[c_val].c_str());
+    const long disp = c_disp >= 0 && (int)cols.size() > c_disp ? atol(cols[c_disp].c_str()) : (long)a.dispatches.size();
+    if (std::find(a.dispatches.begin(), a.dispatches.end(), disp) == a.dispatches.end()) {
+      a.dispatches.push_back(disp);
+      if (std::find(all_disp.begin(), all_disp.end(), disp) == all_disp.end()) {
+        all_disp.push_back(disp);
+        if (c_t0 >= 0 && c_t1 >= 0 && (int)cols.size() > std::max(c_t0, c_t1)) {
+          const double t0 = atof(cols[c_t0].c_str()), t1 = atof(cols[c_t1].c_str());
+          if (t1 > t0) { dur_ns += t1 - t0; ++dur_n; }
+        }
+      }
+    }
+  }
+  fclose(f);
+  if (accs.empty()) return fail(TF_E_PROFILER, "%s: no row for a kernel containing '%s'", csv_path, kernel_substr);
+  auto mean = [&](const char* n, double* v) -> bool {
+    for (auto& a : accs) if (a.first == n && !a.second.dispatches.empty()) { *v = a.second.sum / a.second.dispatches.size(); return true; }
+    return false;
+  };
+  // per-dispatch duration: the profiled one if the file has timestamps, else the report's own median
+  const double dur_us = dur_n > 0 ? dur_ns / dur_n * 1e-3 : r->t_med_us;
+  double a = 0, b = 0;
+  int got = 0;
+  if (mean("SQ_VALU_MFMA_BUSY_CYCLES", &a) && mean("SQ_BUSY_CU_CYCLES", &b) && b > 0) { r->mfma_busy_pct = 100.0 * a / b; ++got; }
+  else if (mean("SQ_VALU_MFMA_BUSY_CYCLES", &a) && mean("GRBM_GUI_ACTIVE", &b) && b > 0) {
+    // busy cycles are summed over the SIMD-quads of all CUs; GRBM_GUI_ACTIVE is wall cycles
+    r->mfma_busy_pct = 100.0 * a / (b * hw->cus * hw->simds_per_cu); ++got;
+  }
+  if (mean("SQ_LDS_BANK_CONFLICT", &a) && (mean("SQ_LDS_IDX_ACTIVE", &b) || mean("SQ_ACTIVE_INST_LDS", &b)) && b > 0) {
+    r->lds_bank_conflict_pct = 100.0 * a / b; ++got;
+  }
+  if (mean("FETCH_SIZE", &a) && dur_us > 0) { r->hbm_read_gbs = a * 1024.0 / dur_us * 1e-3; ++got; }
+  if (mean("WRITE_SIZE", &a) && dur_us > 0) { r->hbm_write_gbs = a * 1024.0 / dur_us * 1e-3; ++got; }
+  if (mean("TCC_HIT_sum", &a) && mean("TCC_MISS_sum", &b) && a + b > 0) { r->l2_hit_pct = 100.0 * a / (a + b); ++got; }
+  if (!got) return fail(TF_E_PROFILER, "%s: none of the known counters present", csv_path);
+  r->have_counters = 1;
+  r->bottleneck = tf_refine_hint(nullptr, r, hw);
+  return TF_OK;
+}
+
+extern "C" tf_status tf_tune(tf_problem* p, const void* A, const void* B, const void* bias, void* Y, void* workspace,
+                             size_t workspace_bytes, void* hip_stream, const tf_theta* theta, tf_parity_fn parity,
+                             void* parity_user, int32_t* best_variant, tf_report* best, tf_report* round_log,
+                             int32_t log_cap, int32_t* n_log) {
+  tf_status st = prepare(p, 0);
+  if (st != TF_OK) return st;
+  tf_theta th;
+  if (theta) th = *theta; else tf_theta_default(&th);
+  if (th.max_rounds < 1 || th.patience < 1) return fail(TF_E_INVALID, "max_rounds and patience must be >= 1");
+  TuneCtx c;
+  memset(&c, 0, sizeof(c));
+  c.p = p; c.A = A; c.B = B; c.bias = bias; c.Y = Y; c.ws = workspace; c.ws_bytes = workspace_bytes;
+  c.stream = (hipStream_t)hip_stream; c.parity = parity; c.parity_user = parity_user;
+  const size_t esz = p->desc.epi == TF_EPI_NONE_F32 ? 4 : 2;
+  c.ybytes = p->desc.M > 0 ? ((size_t)(p->desc.M - 1) * p->desc.ldy + p->desc.N) * esz : 0;
+  if (!parity) {
+    if (hipMalloc(&c.yref, std::max<size_t>(c.ybytes, 16)) != hipSuccess) return fail(TF_E_NOMEM, "cannot allocate the reference output");
+    if (hipMalloc((void**)&c.bad, 256) != hipSuccess) { (void)hipFree(c.yref); return fail(TF_E_NOMEM, "cannot allocate the mismatch counter"); }
+  }
+  st = tf::run_loop(&p->desc, &p->hw, p->family.data(), (int32_t)p->family.size(), &th, tune_profile, &c, best_variant,
+                    best, round_log, log_cap, n_log);
+  if (c.yref) (void)hipFree(c.yref);
+  if (c.bad) (void)hipFree(c.bad);
+  if (st == TF_OK && *best_variant >= 0) {
+    // leave Y holding the output of the selected kernel
+    tf_status s2 = do_launch(p, *best_variant, A, B, bias, Y, workspace, workspace_bytes, c.stream);
+    if (s2 != TF_OK) return s2;
+    TF_HIP(hipStreamSynchronize(c.stream));
+  }
+  return st;
+}

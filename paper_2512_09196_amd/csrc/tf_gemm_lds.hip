@@ -1,0 +1,421 @@
+// LDS-staged bf16 MFMA GEMM with fused bias + GELU(erf) epilogue for gfx950.
+//
+// One work-group computes one BM x BN tile of Y (or one K slice of it). Per K step of
+// BK = 64 it stages an A tile [BM][64] and a B tile [64][BN] in LDS, multi-buffered, and
+// each of the WM x WN waves accumulates a (BM/WM) x (BN/WN) sub-tile with
+// v_mfma_f32_32x32x16_bf16 in fp32.
+//
+// LDS layouts (chosen from measured bank behaviour: 64 banks x 4 B, b128 reads are
+// conflict free when 16 consecutive lanes cover 16 distinct 16-byte slots of a 256-byte line):
+//   A tile: row-major, 128 B per row, eight 16-byte chunks per row; chunk c of row r is
+//           stored in slot c ^ ((r >> 1) & 7). MFMA A operands are ds_read_b128.
+//   B tile: row-major as in memory ([k][n], n contiguous), BN*2 bytes per row, split in
+//           64-byte pieces; piece j of row k is stored in slot j ^ f(k) so that four
+//           consecutive k rows fall in four different bank groups. MFMA B operands, which
+//           need 8 consecutive k per lane, are read with the transposing
+//           ds_read_b64_tr_b16 (two per operand), so B is never transposed by ALU code.
+// Both tiles are written either by global_load_lds_dwordx4 (memory -> LDS without passing
+// through registers; the lane -> slot map is fixed by hardware, the swizzle is applied to
+// the global address instead) or by 16-byte global loads into registers followed by
+// ds_write_b128, which allows zero fill of a ragged K tail.
+#include "tf_device.h"
+
+namespace tf {
+
+template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool DIRECT_>
+struct LdsCfg {
+  static constexpr int BM = BM_, BN = BN_, BK = 64, WM = WM_, WN = WN_, STAGES = STAGES_;
+  static constexpr bool DIRECT = DIRECT_;
+  static constexpr int NWAVES = WM * WN, THREADS = NWAVES * 64;
+  static constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
+  static constexpr int TM = WTM / 32, TN = WTN / 32;       // 32x32 MFMA blocks per wave
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BK * BN * 2;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+  static constexpr int A_INSTR = A_BYTES / 1024;           // wave-wide 1 KB transfers per tile
+  static constexpr int B_INSTR = B_BYTES / 1024;
+  static constexpr int A_PER_WAVE = A_INSTR / NWAVES, B_PER_WAVE = B_INSTR / NWAVES;
+  static constexpr int B_ROW_BYTES = BN * 2;
+  static constexpr int B_ROWS_PER_INSTR = 1024 / B_ROW_BYTES;
+  static constexpr int B_SLOTS_PER_ROW = B_ROW_BYTES / 16;  // 16-byte slots per B row
+  static constexpr int B_PIECES = B_ROW_BYTES / 64;         // 64-byte pieces per B row
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 blocks");
+  static_assert(A_INSTR % NWAVES == 0 && B_INSTR % NWAVES == 0, "tile loads must divide over the waves");
+  static_assert(BN == 64 || BN == 128 || BN == 256, "B row must be 128, 256 or 512 bytes");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
+};
+
+// Slot permutation of the 64-byte pieces of B row k (see header).
+template <int PIECES>
+__device__ __forceinline__ int b_swz(int k) {
+  if (PIECES >= 4) return k & 3;
+  if (PIECES == 2) return (k >> 1) & 1;
+  return 0;
+}
+
+template <class C>
+struct TileLoader {
+  // Per-lane, per-transfer source offsets (in elements, relative to the tile's first k) and
+  // validity. Computed once; the K step only moves the base pointers.
+  // (byte offsets from the tile's first k; 32 bits: the host rejects tensors of 4 GiB or more)
+  unsigned a_src[C::A_PER_WAVE];
+  unsigned b_src[C::B_PER_WAVE];
+  int a_k[C::A_PER_WAVE];        // k offset (elements) of the lane's chunk inside the tile
+  int b_k[C::B_PER_WAVE];        // k row of the lane inside the tile
+  bool b_ok[C::B_PER_WAVE];      // column chunk inside N
+  bool a_ok[C::A_PER_WAVE];      // row inside M
+
+  __device__ __forceinline__ void init(const GemmParams& p, int m0, int n0, int wave, int lane) {
+#pragma unroll
+    for (int q = 0; q < C::A_PER_WAVE; ++q) {
+      const int ia = wave + C::NWAVES * q;
+      const int row = 8 * ia + (lane >> 3);
+      const int slot = lane & 7;
+      const int c = slot ^ ((row >> 1) & 7);
+      int m = m0 + row;
+      a_ok[q] = m < p.M;
+      if (m >= p.M) m = p.M - 1;
+      a_src[q] = ((unsigned)m * (unsigned)p.lda + 8u * c) * 2u;
+      a_k[q] = 8 * c;
+    }
+#pragma unroll
+    for (int q = 0; q < C::B_PER_WAVE; ++q) {
+      const int ib = wave + C::NWAVES * q;
+      constexpr int LPR = 64 / C::B_ROWS_PER_INSTR;          // lanes per row
+      const int krow = C::B_ROWS_PER_INSTR * ib + lane / LPR;
+      const int s16 = lane % LPR;
+      const int piece = (s16 >> 2) ^ b_swz<C::B_PIECES>(krow);
+      int n = n0 + 32 * piece + 8 * (s16 & 3);
+      b_ok[q] = n < p.N;
+      if (n >= p.N) n = 0;
+      b_src[q] = ((unsigned)krow * (unsigned)p.ldb + (unsigned)n) * 2u;
+      b_k[q] = krow;
+    }
+  }
+
+  // memory -> LDS without registers. Requires every k of the tile to be < K.
+  __device__ __forceinline__ void issue_direct(const uint16_t* Ak, const uint16_t* Bk, char* stage, int wave) const {
+#pragma unroll
+    for (int q = 0; q < C::A_PER_WAVE; ++q) {
+      const int ia = wave + C::NWAVES * q;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)((const char*)Ak + a_src[q]),
+                                       (__attribute__((address_space(3))) void*)(stage + ia * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int q = 0; q < C::B_PER_WAVE; ++q) {
+      const int ib = wave + C::NWAVES * q;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)((const char*)Bk + b_src[q]),
+                                       (__attribute__((address_space(3))) void*)(stage + C::A_BYTES + ib * 1024), 16, 0, 0);
+    }
+  }
+
+  // memory -> registers, zero where k >= K (ragged tail) or outside M / N.
+  __device__ __forceinline__ void load_regs(const uint16_t* Ak, const uint16_t* Bk, int k0, int K,
+                                            u32x4 (&ra)[C::A_PER_WAVE], u32x4 (&rb)[C::B_PER_WAVE]) const {
+#pragma unroll
+    for (int q = 0; q < C::A_PER_WAVE; ++q) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (a_ok[q] && k0 + a_k[q] < K) v = *(const u32x4*)((const char*)Ak + a_src[q]);
+      ra[q] = v;
+    }
+#pragma unroll
+    for (int q = 0; q < C::B_PER_WAVE; ++q) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (b_ok[q] && k0 + b_k[q] < K) v = *(const u32x4*)((const char*)Bk + b_src[q]);
+      rb[q] = v;
+    }
+  }
+  __device__ __forceinline__ void store_regs(char* stage, int wave, int lane,
+                                             const u32x4 (&ra)[C::A_PER_WAVE], const u32x4 (&rb)[C::B_PER_WAVE]) const {
+#pragma unroll
+    for (int q = 0; q < C::A_PER_WAVE; ++q) {
+      const int ia = wave + C::NWAVES * q;
+      *(u32x4*)(stage + ia * 1024 + lane * 16) = ra[q];
+    }
+#pragma unroll
+    for (int q = 0; q < C::B_PER_WAVE; ++q) {
+      const int ib = wave + C::NWAVES * q;
+      *(u32x4*)(stage + C::A_BYTES + ib * 1024 + lane * 16) = rb[q];
+    }
+  }
+};
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
+// vmcnt = bits [3:0] and [15:14], expcnt [6:4] and lgkmcnt [11:8] left at "no wait").
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// Split-K: one slice's partial tile -> workspace (fp32, [slice][M][N]).
+template <class C, bool FULL>
+__device__ __forceinline__ void store_partial(const f32x16 (&acc)[C::TM][C::TN], float* wsk, const GemmParams& p,
+                                              int wm0, int wn0) {
+#pragma unroll
+  for (int i = 0; i < C::TM; ++i) {
+    const int m = wm0 + 32 * i;
+#pragma unroll
+    for (int t = 0; t < C::TN; ++t)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = wn0 + 32 * t + 8 * q;
+        if (FULL || (m < p.M && n < p.N)) {
+          const f32x4 v = {acc[i][t][4 * q], acc[i][t][4 * q + 1], acc[i][t][4 * q + 2], acc[i][t][4 * q + 3]};
+          *(f32x4*)(wsk + (size_t)m * p.N + n) = v;
+        }
+      }
+  }
+}
+
+// Split-K: sum of all slices, always in slice order 0, 1, ... so the result does not depend on
+// which slice arrived last.
+template <class C, bool FULL>
+__device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0) {
+  const size_t slice = (size_t)p.M * p.N;
+#pragma unroll
+  for (int i = 0; i < C::TM; ++i) {
+    const int m = wm0 + 32 * i;
+#pragma unroll
+    for (int t = 0; t < C::TN; ++t)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = wn0 + 32 * t + 8 * q;
+        f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (FULL || (m < p.M && n < p.N)) {
+          const float* src = p.ws + (size_t)m * p.N + n;
+          for (int sidx = 0; sidx < p.split_k; ++sidx) sum += *(const f32x4*)(src + (size_t)sidx * slice);
+        }
+        acc[i][t][4 * q] = sum[0]; acc[i][t][4 * q + 1] = sum[1];
+        acc[i][t][4 * q + 2] = sum[2]; acc[i][t][4 * q + 3] = sum[3];
+      }
+  }
+}
+
+template <class C, bool FULL, int EPI>
+__device__ __forceinline__ void epilogue(const f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0) {
+#pragma unroll
+  for (int t = 0; t < C::TN; ++t) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int n = wn0 + 32 * t + 8 * q;
+      const bool n_ok = FULL || n < p.N;
+      u32x2 braw = {0u, 0u};
+      if (n_ok) braw = *(const u32x2*)(p.bias + n);
+      const float b0 = __builtin_bit_cast(float, braw[0] << 16), b1 = __builtin_bit_cast(float, braw[0] & 0xffff0000u);
+      const float b2 = __builtin_bit_cast(float, braw[1] << 16), b3 = __builtin_bit_cast(float, braw[1] & 0xffff0000u);
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i) {
+        const int m = wm0 + 32 * i;
+        if (FULL || (n_ok && m < p.M)) {
+          const float z0 = acc[i][t][4 * q] + b0, z1 = acc[i][t][4 * q + 1] + b1;
+          const float z2 = acc[i][t][4 * q + 2] + b2, z3 = acc[i][t][4 * q + 3] + b3;
+          if (EPI == TF_EPI_NONE_F32) {
+            const f32x4 v = {z0, z1, z2, z3};
+            *(f32x4*)((float*)p.Y + (size_t)m * p.ldy + n) = v;
+          } else {
+            u32x2 o;
+            o[0] = pack_bf16x2(gelu_erf(z0), gelu_erf(z1));
+            o[1] = pack_bf16x2(gelu_erf(z2), gelu_erf(z3));
+            *(u32x2*)((uint16_t*)p.Y + (size_t)m * p.ldy + n) = o;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <class C>
+__global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave / C::WN, wave_n = wave % C::WN;
+
+  const TileCoord tc = map_tile(p, blockIdx.x);
+  const int m0 = tc.tm * C::BM, n0 = tc.tn * C::BN;
+  const int ktiles_total = (p.K + C::BK - 1) / C::BK;
+  const int kt_begin = tc.ks * p.ktiles_per_split;
+  int kt_end = kt_begin + p.ktiles_per_split;
+  if (kt_end > ktiles_total) kt_end = ktiles_total;
+  const int nkt = kt_end - kt_begin;   // may be <= 0 for a trailing empty slice: contributes zeros
+
+  // ---- LDS read offsets of this lane (bytes inside a stage)
+  int a_off[4];
+  {
+    const int r = wave_m * C::WTM + (lane & 31);
+    const int g = lane >> 5;
+    const int sw = (r >> 1) & 7;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) a_off[kk] = r * 128 + (((2 * kk + g) ^ sw) << 4);
+  }
+  int b_off[C::TN];
+  {
+    const int b = lane >> 4, s = lane & 15;
+    const int krow = 8 * (b >> 1) + (s >> 2);                 // + 16 kk + 4 h
+    const int within = (16 * (b & 1) + 4 * (s & 3)) * 2;      // bytes inside the 64-byte piece
+#pragma unroll
+    for (int t = 0; t < C::TN; ++t) {
+      const int j = (wave_n * C::WTN) / 32 + t;
+      const int piece = j ^ b_swz<C::B_PIECES>(krow);
+      b_off[t] = C::A_BYTES + krow * C::B_ROW_BYTES + piece * 64 + within;
+    }
+  }
+
+  f32x16 acc[C::TM][C::TN];
+#pragma unroll
+  for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+    for (int t = 0; t < C::TN; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][t][r] = 0.0f;
+
+  TileLoader<C> ld;
+  ld.init(p, m0, n0, wave, lane);
+  const uint16_t* Ak = p.A + (long)kt_begin * C::BK;
+  const uint16_t* Bk = p.B + (long)kt_begin * C::BK * p.ldb;
+  const long b_step = (long)C::BK * p.ldb;
+
+  auto compute = [&](const char* stage) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 af[C::TM], bfr[C::TN];
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i)
+        af[i] = *(const bf16x8*)(stage + a_off[kk] + i * 32 * 128);
+#pragma unroll
+      for (int t = 0; t < C::TN; ++t) {
+        const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + 4 * C::B_ROW_BYTES));
+        const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        bfr[t] = __builtin_bit_cast(bf16x8, v);
+      }
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int t = 0; t < C::TN; ++t)
+          acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[t], af[i], acc[i][t], 0, 0, 0);
+    }
+  };
+
+  if constexpr (C::DIRECT) {
+    // Ring of STAGES buffers; tiles 0 .. STAGES-2 are in flight before the loop.
+    constexpr int PER_TILE = C::A_PER_WAVE + C::B_PER_WAVE;   // transfers per wave per tile
+#pragma unroll
+    for (int s = 0; s < C::STAGES - 1; ++s) {
+      if (s < nkt) ld.issue_direct(Ak + (long)s * C::BK, Bk + (long)s * b_step, smem + s * C::STAGE_BYTES, wave);
+    }
+    int stage = 0;
+    for (int kt = 0; kt < nkt; ++kt) {
+      // tile kt has landed once at most the transfers of the tiles issued after it remain
+      const int later = (nkt - 1 - kt) < (C::STAGES - 2) ? (nkt - 1 - kt) : (C::STAGES - 2);
+      if (later <= 0) wait_vmcnt<0>();
+      else if (later == 1) wait_vmcnt<PER_TILE < 64 ? PER_TILE : 0>();
+      else wait_vmcnt<2 * PER_TILE < 64 ? 2 * PER_TILE : 0>();
+      __syncthreads();   // everyone's part of tile kt is in LDS; everyone is done with the buffer refilled below
+      const int nxt = kt + C::STAGES - 1;
+      if (nxt < nkt) {
+        int ws = stage + C::STAGES - 1;
+        if (ws >= C::STAGES) ws -= C::STAGES;
+        ld.issue_direct(Ak + (long)nxt * C::BK, Bk + (long)nxt * b_step, smem + ws * C::STAGE_BYTES, wave);
+      }
+      compute(smem + stage * C::STAGE_BYTES);
+      if (++stage == C::STAGES) stage = 0;
+    }
+  } else {
+    // Register-staged double buffering: loads of tile kt+1 are in flight during the MFMAs of tile kt.
+    static_assert(C::DIRECT || C::STAGES == 2, "register staging uses two buffers");
+    u32x4 ra[C::A_PER_WAVE], rb[C::B_PER_WAVE];
+    const int kbase = kt_begin * C::BK;
+    if (nkt > 0) {
+      ld.load_regs(Ak, Bk, kbase, p.K, ra, rb);
+      ld.store_regs(smem, wave, lane, ra, rb);
+    }
+    for (int kt = 0; kt < nkt; ++kt) {
+      __syncthreads();
+      const bool more = kt + 1 < nkt;
+      if (more) ld.load_regs(Ak + (long)(kt + 1) * C::BK, Bk + (long)(kt + 1) * b_step, kbase + (kt + 1) * C::BK, p.K, ra, rb);
+      compute(smem + (kt & 1) * C::STAGE_BYTES);
+      if (more) ld.store_regs(smem + ((kt + 1) & 1) * C::STAGE_BYTES, wave, lane, ra, rb);
+    }
+  }
+
+  // ---- accumulator layout. The MFMA is issued with the B fragment as its first operand and
+  // the A fragment as its second, so each 32x32 block is held transposed: lane l, register r
+  // holds  m = block_m + (l & 31),  n = block_n + 8 (r / 4) + 4 (l / 32) + (r % 4).
+  // A lane therefore owns runs of four consecutive n, which pack into one 8-byte (bf16) or
+  // 16-byte (fp32) store without any cross-lane exchange.
+  const int lane_m = lane & 31, lane_g = lane >> 5;
+  const int wm0 = m0 + wave_m * C::WTM + lane_m;              // + 32 i
+  const int wn0 = n0 + wave_n * C::WTN + 4 * lane_g;          // + 32 t + 8 q
+  const bool full = (m0 + C::BM <= p.M) && (n0 + C::BN <= p.N);
+
+  if (p.split_k > 1) {
+    // publish the partial tile; the last slice to arrive sums all slices in slice order
+    const size_t slice = (size_t)p.M * p.N;
+    float* wsk = p.ws + (size_t)tc.ks * slice;
+    if (full) store_partial<C, true>(acc, wsk, p, wm0, wn0);
+    else store_partial<C, false>(acc, wsk, p, wm0, wn0);
+    __threadfence();
+    __syncthreads();
+    __shared__ unsigned ticket;
+    unsigned* ctr = p.counters + (tc.tm * p.tiles_n + tc.tn);
+    if (tid == 0) ticket = atomicAdd(ctr, 1u);
+    __syncthreads();
+    if (ticket != (unsigned)(p.split_k - 1)) return;
+    if (tid == 0) *ctr = 0u;          // ready for the next launch
+    __threadfence();
+    if (full) sum_partials<C, true>(acc, p, wm0, wn0);
+    else sum_partials<C, false>(acc, p, wm0, wn0);
+  }
+
+  // ---- epilogue: + bias, GELU, round to bf16 (or raw fp32 pre-activation)
+  if (p.epi == TF_EPI_NONE_F32) {
+    if (full) epilogue<C, true, TF_EPI_NONE_F32>(acc, p, wm0, wn0);
+    else epilogue<C, false, TF_EPI_NONE_F32>(acc, p, wm0, wn0);
+  } else {
+    if (full) epilogue<C, true, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0);
+    else epilogue<C, false, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0);
+  }
+}
+
+template <class C>
+static void launch_lds(const GemmParams& p, dim3 grid, hipStream_t stream) {
+  hipLaunchKernelGGL(tf_gemm_lds_kernel<C>, grid, dim3(C::THREADS), C::LDS_BYTES, stream, p);
+}
+
+template <class C>
+static LdsKernelInfo make_info() {
+  LdsKernelInfo k;
+  k.bm = C::BM; k.bn = C::BN; k.bk = C::BK; k.waves_m = C::WM; k.waves_n = C::WN;
+  k.stages = C::STAGES; k.direct_to_lds = C::DIRECT ? 1 : 0;
+  k.threads = C::THREADS; k.lds_bytes = C::LDS_BYTES;
+  k.func = (const void*)tf_gemm_lds_kernel<C>;
+  k.launch = launch_lds<C>;
+  return k;
+}
+
+//                         BM   BN  WM WN ST  direct
+using K256x256_d2 = LdsCfg<256, 256, 2, 2, 2, true>;
+using K256x128_d2 = LdsCfg<256, 128, 2, 2, 2, true>;
+using K128x256_d2 = LdsCfg<128, 256, 2, 2, 2, true>;
+using K128x128_d2 = LdsCfg<128, 128, 2, 2, 2, true>;
+using K128x128_d3 = LdsCfg<128, 128, 2, 2, 3, true>;
+using K128x128_r2 = LdsCfg<128, 128, 2, 2, 2, false>;
+using K64x64_r2   = LdsCfg< 64,  64, 2, 2, 2, false>;
+using K64x64_d3   = LdsCfg< 64,  64, 2, 2, 3, true>;
+using K32x128_d3  = LdsCfg< 32, 128, 1, 4, 3, true>;
+using K32x64_d4   = LdsCfg< 32,  64, 1, 2, 4, true>;
+using K32x128_r2  = LdsCfg< 32, 128, 1, 4, 2, false>;
+
+static LdsKernelInfo g_table[] = {
+    make_info<K256x256_d2>(), make_info<K256x128_d2>(), make_info<K128x256_d2>(),
+    make_info<K128x128_d2>(), make_info<K128x128_d3>(), make_info<K128x128_r2>(),
+    make_info<K64x64_r2>(),   make_info<K64x64_d3>(),   make_info<K32x128_d3>(),
+    make_info<K32x64_d4>(),   make_info<K32x128_r2>(),
+};
+
+int lds_kernel_count() { return (int)(sizeof(g_table) / sizeof(g_table[0])); }
+const LdsKernelInfo* lds_kernel_table() { return g_table; }
+
+}  // namespace tf

@@ -1,0 +1,44 @@
+// Internal declarations shared by the translation units of libtf_gfx950.so.
+// Not part of the public boundary (that is include/tf.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "tf.h"
+
+namespace tf {
+
+// Arguments of every GEMM kernel of the family. All pointers are device pointers.
+struct GemmParams {
+  const uint16_t* A;      // [M, lda] bf16 bits, row-major
+  const uint16_t* B;      // [K, ldb] bf16 bits, row-major
+  const uint16_t* bias;   // [N] bf16 bits
+  void* Y;                // [M, ldy]: bf16 bits (TF_EPI_BIAS_GELU_ERF) or float (TF_EPI_NONE_F32)
+  float* ws;              // split-K partial sums [split_k][M][N] (unused when split_k == 1)
+  unsigned* counters;     // one arrival counter per output tile, zero between launches
+  int M, N, K;
+  long lda, ldb, ldy;     // in elements
+  int tiles_m, tiles_n;
+  int split_k;            // number of K slices
+  int ktiles_per_split;   // K tiles (of BK) per slice; the last slice may be shorter
+  int epi;                // tf_epilogue
+  int group_m;            // tile rows per L2 group in the tile order (>= 1)
+  int xcd_swizzle;        // 1: remap work-group ids so that neighbouring tiles share an XCD
+};
+
+// One compiled kernel of the LDS-staged MFMA family.
+struct LdsKernelInfo {
+  int bm, bn, bk, waves_m, waves_n, stages, direct_to_lds;
+  int threads, lds_bytes;
+  const void* func;       // kernel symbol, for hipFuncGetAttributes / occupancy queries
+  void (*launch)(const GemmParams&, dim3 grid, hipStream_t);
+};
+int lds_kernel_count();
+const LdsKernelInfo* lds_kernel_table();
+
+void launch_naive(const GemmParams&, hipStream_t);
+void launch_mfma_direct(const GemmParams&, hipStream_t);
+const void* naive_func();
+const void* mfma_direct_func();
+void launch_fill_u32(unsigned* p, size_t n, unsigned v, hipStream_t);
+
+}  // namespace tf

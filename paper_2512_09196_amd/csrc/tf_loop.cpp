@@ -1,0 +1,260 @@
+// Host logic of the profiling-guided variant loop (paper Sec. 3.3, Algorithm 1).
+// Pure functions of reports and descriptors: nothing here touches the GPU, so the loop can
+// be tested on synthetic reports.
+//
+// The paper names the roles (Proposal, BuildRun, Profile, Arbiter, RefineHint), the
+// Arbiter's criteria (speedup, robustness, resource limits, diminishing returns), two
+// example hints (memory stalls -> tiling/staging, low occupancy -> register pressure), the
+// 1.05x success bar (Sec. 4.2) and the cap of 8 rounds; it gives no threshold values and its
+// Proposal / RefineHint are an LLM. Here both are rules over a finite kernel family.
+#include <math.h>
+#include <string.h>
+
+#include "tf_loop.h"
+
+extern "C" void tf_theta_default(tf_theta* t) {
+  if (!t) return;
+  t->first_accept_speedup = 1.05;  // the paper's success bar against the baseline kernel
+  t->later_accept_gain = 1.02;     // a new best must beat the old best by more than timing noise
+  t->robust_spread = 0.10;
+  t->patience = 4;   // Case Study 3 runs four consecutive non-improving rounds before it stops
+  t->max_rounds = 8;
+}
+
+extern "C" void tf_hw_nominal(tf_hw* h) {
+  if (!h) return;
+  memset(h, 0, sizeof(*h));
+  strncpy(h->name, "AMD Instinct MI355X (published figures)", sizeof(h->name) - 1);
+  h->cus = 256; h->simds_per_cu = 4; h->wave_size = 64; h->xcds = 8;
+  h->lds_bytes_per_cu = 160 * 1024; h->vgprs_per_simd_lane = 512; h->max_waves_per_simd = 8;
+  h->l2_bytes = 4ll << 20; h->hbm_bytes = 288ll << 30;
+  h->clock_mhz = 2400.0; h->hbm_gbs_peak = 8000.0;
+  h->bf16_tflops_peak = 256 * 4096.0 * 2400.0e6 / 1e12;   // 2516.6
+}
+
+// ------------------------------------------------------------------ Arbiter
+extern "C" int32_t tf_arbiter(const tf_report* cand, const tf_report* best, const tf_theta* th,
+                              int32_t best_is_baseline, int32_t stall_rounds, int32_t round) {
+  if (!cand || !best || !th) return TF_DEC_FINISH;
+  const bool usable = cand->status == TF_OK && cand->parity_ok != 0 && cand->t_med_us > 0.0 &&
+                      best->t_med_us > 0.0;
+  if (usable) {
+    const double spread = (cand->t_med_us - cand->t_min_us) / cand->t_med_us;
+    const double need = best_is_baseline ? th->first_accept_speedup : th->later_accept_gain;
+    if (spread <= th->robust_spread && best->t_med_us / cand->t_med_us >= need) return TF_DEC_ACCEPT;
+  }
+  if (stall_rounds + 1 >= th->patience) return TF_DEC_FINISH;   // diminishing returns
+  if (round >= th->max_rounds) return TF_DEC_FINISH;
+  return TF_DEC_CONTINUE;
+}
+
+// ------------------------------------------------------------------ RefineHint
+static int classify(const tf_report* r, const tf_hw* hw) {
+  const double ridge = hw->bf16_tflops_peak * 1e3 / hw->hbm_gbs_peak;   // flop per byte
+  const double mfma = r->have_counters ? r->mfma_busy_pct : r->pct_mfma_peak;
+  const double hbm = r->have_counters ? 100.0 * (r->hbm_read_gbs + r->hbm_write_gbs) / hw->hbm_gbs_peak
+                                      : r->pct_hbm_peak;
+  if (r->grid_fill < 0.75) return TF_BN_UNDERFILLED;
+  if (r->arithmetic_intensity < ridge && hbm >= 60.0) return TF_BN_HBM;
+  if (mfma >= 70.0) return TF_BN_MFMA;
+  if (r->have_counters && r->lds_bank_conflict_pct > 5.0) return TF_BN_LDS_CONFLICT;
+  if (r->occupancy_pct < 25.0 && mfma < 50.0 && hbm < 50.0) return TF_BN_OCCUPANCY;
+  return TF_BN_LATENCY;
+}
+
+extern "C" int32_t tf_refine_hint(const tf_report* prev, const tf_report* cand, const tf_hw* hw) {
+  if (!cand || !hw) return TF_BN_UNKNOWN;
+  if (cand->status != TF_OK || cand->t_med_us <= 0.0) return TF_BN_UNKNOWN;
+  int c = classify(cand, hw);
+  // The delta against the previous report: when the last step made things slower and the
+  // diagnosis did not change, the remedy for that diagnosis has just failed; swap between the
+  // two "nothing is saturated" diagnoses so the next proposal goes the other way (the
+  // tile-size versus resident-work-groups trade-off of Case Study 3).
+  if (prev && prev->status == TF_OK && prev->t_med_us > 0.0 && cand->t_med_us > 1.02 * prev->t_med_us &&
+      classify(prev, hw) == c) {
+    if (c == TF_BN_OCCUPANCY) c = TF_BN_LATENCY;
+    else if (c == TF_BN_LATENCY) c = TF_BN_OCCUPANCY;
+  }
+  return c;
+}
+
+// ------------------------------------------------------------------ static cost model
+static inline long cdiv(long a, long b) { return (a + b - 1) / b; }
+
+extern "C" int32_t tf_resident_wgs(const tf_hw* hw, const tf_variant_desc* v) {
+  if (v->kind != TF_KIND_MFMA_LDS) return 8;
+  const int acc_regs = (v->bm / v->waves_m) * (v->bn / v->waves_n) / 64;
+  const int regs = acc_regs + 96;                      // fragments, staging, addresses
+  int wps = hw->vgprs_per_simd_lane / regs;
+  if (wps < 1) wps = 1;
+  if (wps > hw->max_waves_per_simd) wps = hw->max_waves_per_simd;
+  const int wg_waves = v->waves_m * v->waves_n;
+  int by_regs = wps * hw->simds_per_cu / wg_waves;
+  if (by_regs < 1) by_regs = 1;
+  int by_lds = v->lds_bytes > 0 ? hw->lds_bytes_per_cu / v->lds_bytes : 8;
+  if (by_lds < 1) by_lds = 1;
+  int r = by_regs < by_lds ? by_regs : by_lds;
+  return r > 8 ? 8 : r;
+}
+
+extern "C" double tf_grid_fill(const tf_hw* hw, const tf_variant_desc* v) {
+  const long slots = (long)hw->cus * tf_resident_wgs(hw, v);
+  if (v->grid <= 0) return 0.0;
+  return (double)v->grid / (double)(cdiv(v->grid, slots) * slots);
+}
+
+extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, const tf_variant_desc* v) {
+  const double flops = 2.0 * pr->M * (double)pr->N * pr->K;
+  const double bytes = 2.0 * ((double)pr->M * pr->K + (double)pr->K * pr->N + (double)pr->M * pr->N + pr->N);
+  const double hbm_us = bytes / (hw->hbm_gbs_peak * 1e3);
+  if (v->kind == TF_KIND_NAIVE) return fmax(flops / (0.004 * hw->bf16_tflops_peak * 1e6), hbm_us) + 2.0;
+  if (v->kind == TF_KIND_MFMA_DIRECT) return fmax(flops / (0.02 * hw->bf16_tflops_peak * 1e6), hbm_us) + 2.0;
+  const int resident = tf_resident_wgs(hw, v);
+  const long slots = (long)hw->cus * resident;
+  const long rounds = cdiv(v->grid, slots);
+  const long ktiles = cdiv(cdiv(pr->K, 64), v->split_k);
+  const int wg_waves = v->waves_m * v->waves_n;
+  // cycles one CU spends on one K tile of one work-group
+  const double mfma = v->bm * (double)v->bn / 32.0;              // 128 bm bn flop at 4096 flop/clk
+  const double stage_bytes = (v->bm + v->bn) * 128.0;
+  const double lds_w = stage_bytes / 64.0;                       // measured LDS write rate, B/clk
+  const double lds_r = wg_waves * ((v->bm / v->waves_m) + (v->bn / v->waves_n)) * 128.0 / 224.0;
+  const double ta = stage_bytes / 64.0;                          // global -> CU, B/clk
+  double ktile = fmax(mfma, fmax(lds_w + lds_r, ta));
+  if (!v->direct_to_lds) ktile *= 1.10;                          // VALU/VGPR traffic of register staging
+  const double exposed = 400.0 / (resident * (v->stages - 1));   // barrier + staging latency not hidden
+  const double epi = v->bm * (double)v->bn / 4.0;                // 16 VALU ops per element, 64 lanes/clk
+  const double splitk = v->split_k > 1 ? v->bm * (double)v->bn * (1.0 + v->split_k) / 32.0 : 0.0;
+  // a round gives every CU up to `resident` work-groups, which share its pipes; the last
+  // round may be thinner
+  double cycles = 0.0;
+  long left = v->grid;
+  for (long r = 0; r < rounds; ++r) {
+    const long now = left < slots ? left : slots;
+    const long per_cu = cdiv(now, hw->cus);
+    cycles += per_cu * (ktiles * ktile + epi + splitk) + ktiles * exposed + 2500.0;
+    left -= now;
+  }
+  double us = cycles / hw->clock_mhz;
+  const double ws_us = v->split_k > 1 ? 2.0 * v->split_k * 4.0 * pr->M * (double)pr->N / (hw->hbm_gbs_peak * 1e3) : 0.0;
+  return fmax(us, hbm_us + ws_us) + 2.0;
+}
+
+// ------------------------------------------------------------------ Proposal
+static bool matches_hint(int bn, const tf_hw* hw, const tf_variant_desc* b, const tf_variant_desc* v) {
+  const double fill_b = tf_grid_fill(hw, b), fill_v = tf_grid_fill(hw, v);
+  const long area_b = (long)b->bm * b->bn, area_v = (long)v->bm * v->bn;
+  switch (bn) {
+    case TF_BN_UNDERFILLED:   // more, smaller units of work
+      return fill_v > fill_b + 1e-9;
+    case TF_BN_HBM:           // more bytes in flight
+      return v->stages > b->stages || v->split_k > b->split_k || (v->direct_to_lds && !b->direct_to_lds) ||
+             v->grid > b->grid;
+    case TF_BN_MFMA:          // only quantisation and LDS traffic per MFMA are left
+      return area_v >= area_b && fill_v >= fill_b - 1e-9;
+    case TF_BN_LDS_CONFLICT:  // other staging path or other tile shape
+      return v->direct_to_lds != b->direct_to_lds || v->bn != b->bn;
+    case TF_BN_OCCUPANCY:     // fewer registers / less LDS per work-group
+      return area_v < area_b || (area_v == area_b && v->lds_bytes < b->lds_bytes);
+    case TF_BN_LATENCY:       // deeper staging, or bigger tiles to amortise it
+      return v->stages > b->stages || (v->direct_to_lds && !b->direct_to_lds) || area_v > area_b;
+    default:
+      return true;
+  }
+}
+
+extern "C" int32_t tf_proposal_from(const tf_hw* hw, const tf_variant_desc* family, const double* predicted_us,
+                                    int32_t n, const uint8_t* tried, int32_t base_id, int32_t bottleneck) {
+  if (!hw || !family || !predicted_us || !tried || n <= 0) return -1;
+  const tf_variant_desc* base = (base_id >= 0 && base_id < n) ? &family[base_id] : nullptr;
+  const bool use_hint = base && base->kind == TF_KIND_MFMA_LDS && bottleneck != TF_BN_UNKNOWN;
+  int best = -1, best_any = -1;
+  for (int i = 0; i < n; ++i) {
+    if (tried[i]) continue;
+    if (best_any < 0 || predicted_us[i] < predicted_us[best_any]) best_any = i;
+    if (use_hint && family[i].kind == TF_KIND_MFMA_LDS && matches_hint(bottleneck, hw, base, &family[i])) {
+      if (best < 0 || predicted_us[i] < predicted_us[best]) best = i;
+    }
+  }
+  return best >= 0 ? best : best_any;
+}
+
+extern "C" int32_t tf_proposal(const tf_problem_desc* prob, const tf_hw* hw, const tf_variant_desc* family,
+                               int32_t n, const uint8_t* tried, int32_t base_id, int32_t bottleneck) {
+  if (!prob || !hw || !family || !tried || n <= 0) return -1;
+  double* pred = new double[n];
+  for (int i = 0; i < n; ++i) pred[i] = tf_predict_us(prob, hw, &family[i]);
+  const int r = tf_proposal_from(hw, family, pred, n, tried, base_id, bottleneck);
+  delete[] pred;
+  return r;
+}
+
+// ------------------------------------------------------------------ Algorithm 1
+namespace tf {
+
+tf_status run_loop(const tf_problem_desc* prob, const tf_hw* hw, const tf_variant_desc* family, int32_t n,
+                   const tf_theta* theta, profile_fn profile, void* user, int32_t* best_variant, tf_report* best,
+                   tf_report* round_log, int32_t log_cap, int32_t* n_log) {
+  if (!prob || !hw || !family || n <= 0 || !theta || !profile || !best_variant || !best || !round_log || !n_log)
+    return TF_E_INVALID;
+  if (log_cap < 1 + theta->max_rounds) return TF_E_RANGE;
+  uint8_t* tried = new uint8_t[n]();
+  // K* <- K, R* <- R : the baseline kernel is variant 0
+  tf_report R;
+  tf_status st = profile(user, 0, &R);
+  if (st != TF_OK || R.status != TF_OK) { delete[] tried; return st != TF_OK ? st : (tf_status)R.status; }
+  R.bottleneck = tf_refine_hint(nullptr, &R, hw);
+  tried[0] = 1;
+  int nl = 0;
+  round_log[nl++] = R;
+  tf_report Rstar = R;
+  int kstar = 0, kcur = 0, bottleneck = TF_BN_UNKNOWN;   // first proposal: the static one-shot pick
+  int stall = 0;
+  for (int round = 1; round <= theta->max_rounds; ++round) {
+    const int cand = tf_proposal(prob, hw, family, n, tried, kcur, bottleneck);
+    if (cand < 0) break;                          // family exhausted
+    tried[cand] = 1;
+    tf_report Rc;
+    st = profile(user, cand, &Rc);                // BuildRun + parity gate + Profile
+    if (st != TF_OK) { Rc.status = st; Rc.variant_id = cand; }
+    Rc.bottleneck = tf_refine_hint(&R, &Rc, hw);
+    round_log[nl++] = Rc;
+    const int dec = tf_arbiter(&Rc, &Rstar, theta, kstar == 0, stall, round);
+    if (dec == TF_DEC_ACCEPT) { kstar = cand; Rstar = Rc; stall = 0; }
+    else ++stall;
+    if (dec == TF_DEC_FINISH) break;
+    // K <- RefineHint(K, R, R'): an accepted candidate becomes the kernel the next proposal
+    // starts from; otherwise the next proposal starts again from K*. Either way the newest
+    // valid diagnosis gives the direction.
+    kcur = (dec == TF_DEC_ACCEPT) ? cand : kstar;
+    bottleneck = (Rc.status == TF_OK && Rc.t_med_us > 0.0) ? Rc.bottleneck : Rstar.bottleneck;
+    R = Rc;
+  }
+  *best_variant = kstar;
+  *best = Rstar;
+  *n_log = nl;
+  delete[] tried;
+  return TF_OK;
+}
+
+}  // namespace tf
+
+// Algorithm 1 over pre-made reports (reports[i] is what Profile would return for variant i):
+// the loop without a GPU, for tests and for replaying recorded profiles.
+struct SimCtx { const tf_report* reports; int n; };
+static tf_status sim_profile(void* user, int32_t id, tf_report* out) {
+  const SimCtx* c = (const SimCtx*)user;
+  if (id < 0 || id >= c->n) return TF_E_INVALID;
+  *out = c->reports[id];
+  out->variant_id = id;
+  return TF_OK;
+}
+
+extern "C" tf_status tf_tune_replay(const tf_problem_desc* prob, const tf_hw* hw, const tf_variant_desc* family,
+                                    const tf_report* reports, int32_t n, const tf_theta* theta,
+                                    int32_t* best_variant, tf_report* best, tf_report* round_log,
+                                    int32_t log_cap, int32_t* n_log) {
+  if (!reports) return TF_E_INVALID;
+  SimCtx c{reports, n};
+  return tf::run_loop(prob, hw, family, n, theta, sim_profile, &c, best_variant, best, round_log, log_cap, n_log);
+}

@@ -1,0 +1,130 @@
+"""Parity at the full sizes of the five workloads, in the launch configuration the benchmark
+times: sampled outputs against the oracle (one dot product each), all variants against each
+other on the whole output, and the GPU-driven variant loop."""
+import numpy as np
+import pytest
+
+from oracle import gemm_oracle as orc
+from paper_2512_09196_amd import tf
+from paper_2512_09196_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+_cache = {}
+
+
+def inputs(name):
+    if name not in _cache:
+        _cache.clear()                      # one full-size workload in host memory at a time
+        _cache[name] = wl.make_inputs(wl.WORKLOADS[name])
+    return _cache[name]
+
+
+def sample_positions(M, N, n_random=1500, seed=0):
+    rng = np.random.default_rng(seed)
+    edges_m = sorted({m for m in (0, 1, 31, 32, 127, 128, 255, 256, M // 2, M - 2, M - 1) if 0 <= m < M})
+    edges_n = sorted({n for n in (0, 7, 8, 63, 64, 127, 128, 255, 256, N // 2, N - 9, N - 8, N - 1) if 0 <= n < N})
+    rows = [m for m in edges_m for _ in edges_n] + list(rng.integers(0, M, n_random))
+    cols = [n for _ in edges_m for n in edges_n] + list(rng.integers(0, N, n_random))
+    return np.array(rows, np.int32), np.array(cols, np.int32)
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_full_size_sampled_parity_and_variant_agreement(name):
+    torch = gu.torch_mod()
+    w = wl.WORKLOADS[name]
+    A, B, bias = inputs(name)
+    rows, cols = sample_positions(w.M, w.N, seed=w.seed)
+    y, z, s = orc.gemm_bias_gelu_at(A, B, bias, rows, cols)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    r_t = torch.from_numpy(rows.astype(np.int64)).cuda()
+    c_t = torch.from_numpy(cols.astype(np.int64)).cuda()
+    for epi, f32 in ((tf.TF_EPI_BIAS_GELU_ERF, False), (tf.TF_EPI_NONE_F32, True)):
+        Y = torch.empty((w.M, w.N), dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
+        ref = None
+        with tf.Problem(w.M, w.N, w.K, epi=epi) as prob:
+            vs = prob.variants()
+            # the slow unstaged kernels only once per workload (bf16 epilogue), every tile kernel always
+            todo = [v for v in vs if v.kind == tf.TF_KIND_MFMA_LDS or not f32]
+            assert len(todo) >= 3
+            for v in todo:
+                print(name, "epi", epi, v.name.decode(), flush=True)
+                Y.fill_(float("nan"))
+                prob.run(v.id, dA, dB, dbias, Y)
+                torch.cuda.synchronize()
+                Yf = Y.float()
+                assert not torch.isnan(Yf).any().item(), v.name.decode() + " left NaN / unwritten elements"
+                got = Yf[r_t, c_t].double().cpu().numpy()
+                if f32:
+                    assert np.all(np.abs(got - z) <= gu.preact_bound(z, s, w.K)), v.name.decode()
+                else:
+                    assert gu.official_ok(got, y), v.name.decode()
+                    assert np.all(np.abs(got - y) <= gu.strict_bound(y, z, s, w.K)), v.name.decode()
+                if ref is None:
+                    ref = Yf.clone()
+                else:
+                    # two correct kernels differ by summation order only: far inside the official bar,
+                    # and (bf16 output) by at most one rounding step of the larger value
+                    d = (Yf - ref).abs()
+                    lim = 1e-2 * (1.0 + ref.abs())
+                    assert bool((d <= lim).all().item()), v.name.decode()
+                del Yf
+        del Y, ref
+
+
+def test_tune_on_gpu_c1_and_c2():
+    torch = gu.torch_mod()
+    for name in ("C1", "C2"):
+        w = wl.WORKLOADS[name]
+        A, B, bias = inputs(name)
+        dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+        Y = torch.empty((w.M, w.N), dtype=torch.bfloat16, device="cuda")
+        rows, cols = sample_positions(w.M, w.N, n_random=300, seed=1)
+        y, z, s = orc.gemm_bias_gelu_at(A, B, bias, rows, cols)
+        r_t, c_t = torch.from_numpy(rows.astype(np.int64)).cuda(), torch.from_numpy(cols.astype(np.int64)).cuda()
+        checked = []
+
+        def gate(vid):
+            got = Y.float()[r_t, c_t].double().cpu().numpy()
+            checked.append(vid)
+            return bool(np.all(np.abs(got - y) <= gu.strict_bound(y, z, s, w.K)))
+
+        with tf.Problem(w.M, w.N, w.K) as prob:
+            for parity in (None, gate):
+                best, rep, log = prob.tune(dA, dB, dbias, Y, parity=parity)
+                print(name, "tune ->", prob.variants()[best].name.decode(), "%.2f us" % rep.t_med_us,
+                      "rounds", len(log) - 1, flush=True)
+                assert log[0].variant_id == 0 and 1 <= len(log) - 1 <= 8
+                assert len({r.variant_id for r in log}) == len(log)
+                assert best != 0, "no variant beat the naive kernel"
+                assert rep.parity_ok == 1 and rep.status == 0
+                assert log[0].t_med_us / rep.t_med_us >= 1.05
+                assert rep.t_med_us <= min(r.t_med_us for r in log if r.status == 0 and r.parity_ok) * 1.0001
+                # Y holds the selected kernel's output
+                got = Y.float()[r_t, c_t].double().cpu().numpy()
+                assert np.all(np.abs(got - y) <= gu.strict_bound(y, z, s, w.K))
+            assert checked and checked[0] == 0
+
+
+def test_profile_report_fields():
+    torch = gu.torch_mod()
+    w = wl.WORKLOADS["C2"]
+    A, B, bias = inputs("C2")
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    Y = torch.empty((w.M, w.N), dtype=torch.bfloat16, device="cuda")
+    hw = tf.hw_query(0)
+    assert hw.cus == 256 and hw.wave_size == 64 and hw.lds_bytes_per_cu == 160 * 1024
+    with tf.Problem(w.M, w.N, w.K) as prob:
+        v = [v for v in prob.variants() if v.kind == tf.TF_KIND_MFMA_LDS and v.bm == 128 and v.bn == 128][0]
+        r = prob.profile(v.id, dA, dB, dbias, Y, warmup=3, iters=5)
+        assert r.status == 0 and r.warmup == 3 and r.iters == 5 and r.launches_per_iter >= 1
+        assert 0 < r.t_min_us <= r.t_med_us <= r.t_max_us and r.t_min_us <= r.t_mean_us <= r.t_max_us
+        assert r.tflops == pytest.approx(w.flops / r.t_med_us * 1e-6, rel=1e-9)
+        assert r.gbytes_per_s == pytest.approx(w.algorithmic_bytes / r.t_med_us * 1e-3, rel=1e-9)
+        assert r.pct_mfma_peak == pytest.approx(100 * r.tflops / hw.bf16_tflops_peak, rel=1e-9)
+        assert r.arithmetic_intensity == pytest.approx(w.flops / w.algorithmic_bytes, rel=1e-9)
+        assert r.grid == v.grid and 1 <= r.waves_per_simd <= 8 and r.vgprs > 0 and r.lds_bytes >= v.lds_bytes
+        assert 0 < r.grid_fill <= 1.0 and r.spill_bytes == 0
+        assert r.tflops > 100.0       # an MFMA kernel on this shape is far above any VALU rate

@@ -1,0 +1,213 @@
+"""Parity of the HIP kernels with the CPU oracle, element by element, through the C boundary.
+
+Tolerances:
+  official  |gpu - oracle| <= 1e-2 (1 + |oracle|)                      (the stated bar)
+  strict    the a-priori bound of a correct fp32-accumulating kernel   (gpu_util.strict_bound)
+  exact     bit equality of the fp32 pre-activation on integer-valued operands
+"""
+import numpy as np
+import pytest
+
+from oracle import gemm_oracle as orc
+from paper_2512_09196_amd import tf
+from paper_2512_09196_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def variants_by_kind(prob):
+    return prob.variants()
+
+
+def check_all_variants(M, N, K, A, B, bias, lda=None, ldb=None, ldy=None, only=None):
+    """Every variant enumerated for the shape against the oracle, with both epilogues."""
+    y, z, s = orc.gemm_bias_gelu(A, B, bias)
+    dA = gu.to_dev(A if lda is None else gu.strided(A, lda))
+    dB = gu.to_dev(B if ldb is None else gu.strided(B, ldb))
+    dbias = gu.to_dev(bias)
+    ran = []
+    for epi, f32 in ((tf.TF_EPI_BIAS_GELU_ERF, False), (tf.TF_EPI_NONE_F32, True)):
+        out = gu.OutBuf(M, N, ldy=ldy, f32=f32)
+        with tf.Problem(M, N, K, lda=lda, ldb=ldb, ldy=ldy, epi=epi) as prob:
+            for v in prob.variants():
+                if only is not None and not only(v):
+                    continue
+                name = v.name.decode()
+                print("case", (M, N, K), "epi", epi, "variant", name, flush=True)
+                got, intact, _ = gu.run_variant(prob, v.id, dA, dB, dbias, out)
+                assert intact, "%s wrote outside Y" % name
+                assert not np.isnan(got).any(), "%s left elements unwritten" % name
+                if f32:
+                    err = np.abs(got - z)
+                    assert np.all(err <= gu.preact_bound(z, s, K)), "%s pre-activation off by %g" % (name, err.max())
+                else:
+                    assert gu.official_ok(got, y), name
+                    err = np.abs(got - y)
+                    bound = gu.strict_bound(y, z, s, K)
+                    assert np.all(err <= bound), "%s: worst excess %g" % (name, (err - bound).max())
+                ran.append(name)
+    return ran
+
+
+def test_c1_every_variant():
+    w = wl.WORKLOADS["C1"]
+    A, B, bias = wl.make_inputs(w)
+    ran = check_all_variants(w.M, w.N, w.K, A, B, bias)
+    assert any(n.startswith("lds_") for n in ran) and "naive_1elem_per_thread" in ran and "mfma32_direct_1wave" in ran
+
+
+@pytest.mark.parametrize("shape", [(300, 520, 448), (130, 264, 192), (33, 72, 64), (257, 136, 1024)])
+def test_ragged_tiles_direct_and_register_staging(shape):
+    # several tiles in M and N with a ragged last tile; K a multiple of 64
+    M, N, K = shape
+    A, B, bias = wl.make_custom(M, N, K, seed=sum(shape))
+    ran = check_all_variants(M, N, K, A, B, bias)
+    assert any("direct" in n for n in ran) and any("regs" in n for n in ran)
+
+
+@pytest.mark.parametrize("shape", [(200, 136, 72), (70, 80, 200), (64, 64, 8)])
+def test_ragged_k_tail_is_zero_filled(shape):
+    M, N, K = shape
+    A, B, bias = wl.make_custom(M, N, K, seed=7 + K, a_dist=("normal", 1.0), b_dist=("normal", 0.3))
+    ran = check_all_variants(M, N, K, A, B, bias)
+    assert any("regs" in n for n in ran) and not any("direct" in n and n.startswith("lds") for n in ran)
+
+
+@pytest.mark.parametrize("shape", [(17, 19, 23), (1, 1, 1), (5, 3, 100), (40, 33, 7)])
+def test_unaligned_shapes_run_on_the_unstaged_kernels(shape):
+    M, N, K = shape
+    A, B, bias = wl.make_custom(M, N, K, seed=99 + M)
+    ran = check_all_variants(M, N, K, A, B, bias)
+    assert ran.count("naive_1elem_per_thread") == 2 and ran.count("mfma32_direct_1wave") == 2
+    assert not any(n.startswith("lds") for n in ran)
+
+
+def test_split_k_variants():
+    M, N, K = 128, 256, 4096
+    A, B, bias = wl.make_custom(M, N, K, seed=5)
+    ran = check_all_variants(M, N, K, A, B, bias, only=lambda v: v.kind == tf.TF_KIND_MFMA_LDS)
+    assert any("_sk2" in n for n in ran) and any("_sk8" in n or "_sk16" in n for n in ran)
+
+
+def test_skinny_decode_shape_small():
+    M, N, K = 16, 512, 2048
+    A, B, bias = wl.make_custom(M, N, K, seed=3, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                                bias_dist=("normal", 0.01))
+    ran = check_all_variants(M, N, K, A, B, bias)
+    assert any(n.startswith("lds_32x") for n in ran)
+
+
+def test_leading_dimensions_and_padding_columns():
+    M, N, K = 150, 200, 320
+    A, B, bias = wl.make_custom(M, N, K, seed=17)
+    check_all_variants(M, N, K, A, B, bias, lda=K + 24, ldb=N + 8, ldy=N + 16)
+
+
+def test_degenerate_sizes():
+    torch = gu.torch_mod()
+    # K = 0: Y = GELU(bias) on every row
+    bias = wl.normal_bf16(1, 2, (24,), 1.0)
+    with tf.Problem(6, 24, 0) as prob:
+        out = gu.OutBuf(6, 24)
+        for v in prob.variants():
+            got, intact, _ = gu.run_variant(prob, v.id, 0, 0, gu.to_dev(bias), out)
+            want = np.array([orc.gelu(float(b)) for b in wl.bf16_bits_to_f32(bias)])
+            assert intact and np.all(np.abs(got - want[None, :]) <= 2.0 ** -8 * np.abs(want) + 1e-6)
+    # M = 0 and N = 0: nothing is launched, nothing is written
+    for (M, N) in ((0, 16), (16, 0)):
+        with tf.Problem(M, N, 64) as prob:
+            out = gu.OutBuf(M, max(N, 8))
+            prob.run(0, 0, 0, 0, out.ptr)
+            torch.cuda.synchronize()
+            assert out.host()[1]
+    # GELU(0) = 0: all-zero operands give an all-zero (+0) output
+    Z = np.zeros((64, 64), np.uint16)
+    with tf.Problem(64, 64, 64) as prob:
+        out = gu.OutBuf(64, 64)
+        for v in prob.variants():
+            _, intact, raw = gu.run_variant(prob, v.id, gu.to_dev(Z), gu.to_dev(Z), gu.to_dev(np.zeros(64, np.uint16)), out)
+            assert intact and np.all(raw == 0)
+
+
+def test_integer_operands_are_bit_exact_in_every_variant():
+    # |a|,|b| <= 2, K = 1024: every partial sum is an integer below 2^24, so fp32 accumulation is
+    # exact in any order -- tile edges, K slices, MFMA lane maps and swizzles all have to be right
+    for (M, N, K) in ((192, 320, 1024), (130, 264, 4096), (32, 128, 2048)):
+        A = wl.small_int_bf16(41, 0, (M, K))
+        B = wl.small_int_bf16(41, 1, (K, N))
+        bias = wl.small_int_bf16(41, 2, (N,), -3, 3)
+        _, z, _ = orc.gemm_bias_gelu(A, B, bias)
+        zf = z.astype(np.float32)
+        assert np.array_equal(zf.astype(np.float64), z)
+        dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+        out = gu.OutBuf(M, N, f32=True)
+        with tf.Problem(M, N, K, epi=tf.TF_EPI_NONE_F32) as prob:
+            vs = prob.variants()
+            assert any(v.split_k > 1 for v in vs)
+            for v in vs:
+                print("exact", (M, N, K), v.name.decode(), flush=True)
+                _, intact, raw = gu.run_variant(prob, v.id, dA, dB, dbias, out)
+                assert intact
+                assert np.array_equal(raw, zf), v.name.decode()
+
+
+def test_identity_and_structured_operands():
+    K = N = 128
+    _, B, bias = wl.make_custom(K, N, K, seed=23, b_dist=("normal", 1.0))
+    A = wl.f64_to_bf16_bits(np.eye(K))
+    y, z, s = orc.gemm_bias_gelu(A, B, bias)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    out = gu.OutBuf(K, N, f32=True)
+    with tf.Problem(K, N, K, epi=tf.TF_EPI_NONE_F32) as prob:
+        for v in prob.variants():
+            _, intact, raw = gu.run_variant(prob, v.id, dA, dB, dbias, out)
+            # A = I: z = b + bias, one fp32 addition of two bf16 values
+            want = (wl.bf16_bits_to_f32(B) + wl.bf16_bits_to_f32(bias)[None, :]).astype(np.float32)
+            assert intact and np.array_equal(raw, want), v.name.decode()
+
+
+def test_split_k_is_deterministic_and_counters_self_clean():
+    M, N, K = 128, 128, 8192
+    A, B, bias = wl.make_custom(M, N, K, seed=31)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    out = gu.OutBuf(M, N, f32=True)
+    with tf.Problem(M, N, K, epi=tf.TF_EPI_NONE_F32) as prob:
+        sk = [v for v in prob.variants() if v.split_k >= 4]
+        assert sk
+        for v in sk[:4]:
+            first = None
+            for rep in range(4):
+                _, intact, raw = gu.run_variant(prob, v.id, dA, dB, dbias, out)
+                assert intact
+                if first is None:
+                    first = raw
+                assert np.array_equal(raw, first), "run %d of %s differs" % (rep, v.name.decode())
+
+
+def test_caller_workspace_and_errors():
+    torch = gu.torch_mod()
+    M, N, K = 128, 128, 2048
+    A, B, bias = wl.make_custom(M, N, K, seed=37)
+    y, z, s = orc.gemm_bias_gelu(A, B, bias)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    out = gu.OutBuf(M, N)
+    with tf.Problem(M, N, K) as prob:
+        v = [v for v in prob.variants() if v.split_k > 1][0]
+        ws = torch.full((v.workspace_bytes // 4 + 64,), -1, dtype=torch.int32, device="cuda")   # dirty on purpose
+        got, intact, _ = gu.run_variant(prob, v.id, dA, dB, dbias, out, workspace=ws, workspace_bytes=ws.numel() * 4)
+        assert intact and np.all(np.abs(got - y) <= gu.strict_bound(y, z, s, K))
+        got2, _, _ = gu.run_variant(prob, v.id, dA, dB, dbias, out, workspace=ws, workspace_bytes=ws.numel() * 4)
+        assert np.array_equal(got, got2)
+        with pytest.raises(tf.TfError) as e:
+            prob.run(v.id, dA, dB, dbias, out.ptr, workspace=ws, workspace_bytes=1024)
+        assert e.value.status == tf.TF_E_UNSUPPORTED
+        with pytest.raises(tf.TfError) as e:
+            prob.run(len(prob.variants()), dA, dB, dbias, out.ptr)
+        assert e.value.status == tf.TF_E_INVALID
+        lds = [v for v in prob.variants() if v.kind == tf.TF_KIND_MFMA_LDS][0]
+        with pytest.raises(tf.TfError) as e:
+            prob.run(lds.id, dA.data_ptr() + 2, dB, dbias, out.ptr)      # misaligned A
+        assert e.value.status == tf.TF_E_UNSUPPORTED
+        torch.cuda.synchronize()

@@ -1,0 +1,164 @@
+"""The library's host-side loop logic (tf_arbiter, tf_refine_hint, tf_proposal_from,
+tf_tune_replay) against the plain-Python loop oracle on synthetic reports, plus sanity of
+the static cost model. No GPU involved."""
+import os
+import random
+
+import pytest
+
+from oracle import loop_oracle as lo
+from paper_2512_09196_amd import tf
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "case_study3_rounds.txt")
+REPORT_KEYS = ["status", "parity_ok", "t_med_us", "t_min_us", "grid_fill", "arithmetic_intensity", "pct_mfma_peak",
+               "pct_hbm_peak", "occupancy_pct", "have_counters", "mfma_busy_pct", "hbm_read_gbs", "hbm_write_gbs",
+               "lds_bank_conflict_pct"]
+VARIANT_KEYS = ["kind", "bm", "bn", "stages", "split_k", "direct_to_lds", "lds_bytes", "grid"]
+
+
+def c_report(d):
+    r = tf.Report()
+    for k in REPORT_KEYS:
+        setattr(r, k, d[k])
+    return r
+
+
+def c_variant(d, i):
+    v = tf.VariantDesc()
+    for k in VARIANT_KEYS:
+        setattr(v, k, d[k])
+    v.id = i
+    v.bk = 64
+    v.waves_m = v.waves_n = 2
+    v.threads = 256
+    return v
+
+
+def hw_dict(h):
+    return dict(bf16_tflops_peak=h.bf16_tflops_peak, hbm_gbs_peak=h.hbm_gbs_peak)
+
+
+def rand_report(rng):
+    t = rng.uniform(5, 500)
+    return dict(status=rng.choice([0, 0, 0, 0, -2, -3]), parity_ok=rng.choice([1, 1, 1, 0]), t_med_us=t,
+                t_min_us=t * rng.choice([0.99, 0.97, 0.8]), grid_fill=rng.uniform(0.1, 1.0),
+                arithmetic_intensity=rng.choice([16.0, 85.0, 500.0, 1700.0]), pct_mfma_peak=rng.uniform(0, 95),
+                pct_hbm_peak=rng.uniform(0, 95), occupancy_pct=rng.choice([12.5, 25.0, 37.5, 50.0]),
+                have_counters=rng.randint(0, 1), mfma_busy_pct=rng.uniform(0, 100), hbm_read_gbs=rng.uniform(0, 6000),
+                hbm_write_gbs=rng.uniform(0, 2000), lds_bank_conflict_pct=rng.uniform(0, 12))
+
+
+def rand_variant(rng, kind=None):
+    bm, bn = rng.choice([32, 64, 128, 256]), rng.choice([64, 128, 256])
+    st = rng.choice([2, 3, 4])
+    return dict(kind=rng.choice([1, 2, 2, 2]) if kind is None else kind, bm=bm, bn=bn, stages=st,
+                split_k=rng.choice([1, 2, 4, 8]), direct_to_lds=rng.randint(0, 1), lds_bytes=st * (bm + bn) * 128,
+                grid=rng.choice([16, 64, 128, 256, 688, 1024, 2752]))
+
+
+def test_arbiter_and_hint_match_oracle_on_random_reports():
+    rng = random.Random(11)
+    hw = tf.hw_nominal()
+    th_c = tf.theta_default()
+    th = dict(first_accept_speedup=th_c.first_accept_speedup, later_accept_gain=th_c.later_accept_gain,
+              robust_spread=th_c.robust_spread, patience=th_c.patience, max_rounds=th_c.max_rounds)
+    assert th == lo.DEFAULT_THETA
+    seen_dec, seen_cls = set(), set()
+    for _ in range(3000):
+        a, b, pv = rand_report(rng), rand_report(rng), rand_report(rng)
+        b["status"], b["parity_ok"] = 0, 1
+        base, stall, rnd = rng.randint(0, 1), rng.randint(0, 4), rng.randint(1, 8)
+        want = lo.arbiter(a, b, th, bool(base), stall, rnd)
+        got = tf.arbiter(c_report(a), c_report(b), th_c, bool(base), stall, rnd)
+        assert got == want
+        seen_dec.add(got)
+        prev = None if rng.random() < 0.3 else pv
+        want = lo.refine_hint(prev, a, hw_dict(hw))
+        got = tf.refine_hint(c_report(prev) if prev else None, c_report(a), hw)
+        assert got == want
+        seen_cls.add(got)
+    assert seen_dec == {0, 1, 2} and seen_cls == set(range(7))
+
+
+def test_proposal_matches_oracle_on_random_families():
+    rng = random.Random(12)
+    hw = tf.hw_nominal()
+    for _ in range(400):
+        n = rng.randint(1, 25)
+        fam = [rand_variant(rng, kind=0)] + [rand_variant(rng) for _ in range(n - 1)]
+        cfam = [c_variant(d, i) for i, d in enumerate(fam)]
+        pred = [rng.choice([10.0, 20.0, 30.0, rng.uniform(1, 100)]) for _ in range(n)]
+        fill = [tf.grid_fill(hw, v) for v in cfam]
+        tried = [rng.random() < 0.4 for _ in range(n)]
+        for hint in range(7):
+            base = rng.randrange(n)
+            assert tf.proposal_from(hw, cfam, pred, tried, base, hint) == lo.proposal(fam, pred, fill, tried, base, hint)
+
+
+def test_tune_replay_matches_oracle_loop():
+    rng = random.Random(13)
+    hw = tf.hw_nominal()
+    th = tf.theta_default()
+    desc = tf.ProblemDesc(2048, 2048, 2048, 2048, 2048, 2048, 0, 0)
+    for _ in range(150):
+        n = rng.randint(1, 30)
+        fam = [rand_variant(rng, kind=0)] + [rand_variant(rng) for _ in range(n - 1)]
+        reps = [rand_report(rng) for _ in range(n)]
+        reps[0]["status"], reps[0]["parity_ok"] = 0, 1
+        cfam = [c_variant(d, i) for i, d in enumerate(fam)]
+        pred = [tf.predict_us(desc, hw, v) for v in cfam]
+        fill = [tf.grid_fill(hw, v) for v in cfam]
+        k_star, r_star, log = lo.optimize(fam, pred, fill, lambda i: reps[i], hw_dict(hw))
+        bv, best, clog = tf.tune_replay(desc, hw, cfam, [c_report(r) for r in reps], th)
+        assert bv == k_star
+        assert best.t_med_us == r_star["t_med_us"]
+        assert [r.variant_id for r in clog] == [r["variant_id"] for r in log]
+        assert [r.bottleneck for r in clog] == [r["bottleneck"] for r in log]
+        assert len(clog) <= 9
+
+
+def test_case_study3_replay_through_the_library():
+    rows = [l.split() for l in open(GOLDEN) if l.strip() and not l.startswith("#")]
+    hw, th = tf.hw_nominal(), tf.theta_default()
+    desc = tf.ProblemDesc(1024, 1024, 1024, 1024, 1024, 1024, 0, 0)
+    reps = []
+    for f in rows:
+        d = rand_report(random.Random(0))
+        d.update(status=0, parity_ok=1, t_med_us=float(f[1]) * 1e3, t_min_us=float(f[1]) * 990.0, grid_fill=1.0,
+                 have_counters=0, pct_mfma_peak=float(f[5]), pct_hbm_peak=float(f[4]), occupancy_pct=float(f[6]),
+                 arithmetic_intensity=1000.0)
+        reps.append(c_report(d))
+    fam = [c_variant(dict(kind=0, bm=4, bn=64, stages=0, split_k=1, direct_to_lds=0, lds_bytes=0, grid=4096), 0)]
+    fam += [c_variant(dict(kind=2, bm=128, bn=128, stages=2, split_k=1, direct_to_lds=1, lds_bytes=65536, grid=64), i)
+            for i in range(1, 5)]
+    bv, best, log = tf.tune_replay(desc, hw, fam, reps, th)
+    assert bv == 0 and best.t_med_us == pytest.approx(9690.0)
+    assert len(log) == 5     # baseline + four rounds: the fourth miss in a row ends the loop
+    assert sorted(r.variant_id for r in log) == [0, 1, 2, 3, 4]
+
+
+def test_cost_model_orders_the_obvious_cases():
+    hw = tf.hw_nominal()
+    with tf.Problem(4096, 11008, 4096) as p:
+        vs = p.variants()
+        pred = {v.name.decode(): tf.predict_us(p.desc, hw, v) for v in vs}
+    assert pred["naive_1elem_per_thread"] > pred["mfma32_direct_1wave"] > min(pred.values())
+    best = min(pred, key=pred.get)
+    assert best.startswith("lds_256x256"), best          # big tiles win on the large compute-bound shape
+    assert 146.0 < pred[best] < 400.0                     # never below the MFMA roof
+    with tf.Problem(16, 8192, 8192) as p:
+        vs = p.variants()
+        pr = [tf.predict_us(p.desc, hw, v) for v in vs]
+        best = vs[pr.index(min(pr))]
+    assert best.kind == tf.TF_KIND_MFMA_LDS and best.split_k > 1      # the skinny shape needs K slices to fill the chip
+    assert min(pr) >= 16.8                                # never below the HBM roof
+    # resident work-groups: 256x256 tiles use the whole register file and most of the LDS;
+    # 64x64 tiles are limited by LDS only (three 16 KB stages -> 3, two -> 4 by registers)
+    with tf.Problem(2048, 2048, 2048) as p:
+        for v in p.variants():
+            if v.kind == tf.TF_KIND_MFMA_LDS and v.bm == 256 and v.bn == 256:
+                assert tf.resident_wgs(hw, v) == 1
+            if v.kind == tf.TF_KIND_MFMA_LDS and v.bm == 64 and v.bn == 64:
+                assert tf.resident_wgs(hw, v) == (3 if v.stages == 3 else 4)
+            f = tf.grid_fill(hw, v)
+            assert 0.0 < f <= 1.0
