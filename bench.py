@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the tile kernel Y = GELU_erf(A.B + bias) on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--variant NAME] [--no-cpu]
+
+One step = one launch of the kernel the variant loop selected, over one batch of synthetic
+input that is already resident in HBM; batches rotate over enough buffer sets to exceed the
+256 MB Infinity Cache, so operands are not served from cache left by the previous step.
+The variant loop (Algorithm 1 of the paper: baseline profile, up to 8 rounds of proposal,
+run, parity gate, profile, arbiter) runs once before the timed region; its result, its
+round log and the tuned-vs-naive speedup are reported in the same JSON line.
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_PEAK_TFLOPS = 256 * 4096 * 2.4e9 / 1e12     # 2516.6: 256 CUs x 4096 flop/clk x 2.4 GHz, dense
+HBM_PEAK_GBS = 8000.0
+MALL_BYTES = 256 << 20
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, A, B, bias, budget_s=12.0):
+    """The oracle as it stands, single thread, on the first rows of the same workload."""
+    from oracle import gemm_oracle as orc
+    probe_rows = max(1, min(w.M, int(2e7 // max(1, w.N * w.K)) or 1))
+    t0 = time.perf_counter()
+    orc.gemm_bias_gelu(A[:probe_rows], B, bias)
+    dt = time.perf_counter() - t0
+    rows = int(max(probe_rows, min(w.M, probe_rows * budget_s / max(dt, 1e-6))))
+    t0 = time.perf_counter()
+    orc.gemm_bias_gelu(A[:rows], B, bias)
+    dt = time.perf_counter() - t0
+    flops = 2.0 * rows * w.N * w.K
+    return {"value": flops / dt * 1e-12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d of %d rows of %s (%.2f GMAC) in %.2f s" % (rows, w.M, w.name, flops / 2e9, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--variant", default=None, help="time this variant instead of the loop's choice")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-tune", action="store_true", help="skip the loop (needs --variant)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)." % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2512_09196_amd import tf
+    from paper_2512_09196_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; there is no CPU path.")
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    log("generating %s (M=%d N=%d K=%d, seed %d)" % (w.name, w.M, w.N, w.K, w.seed))
+    A, B, bias = wl.make_inputs(w)
+    set_bytes = w.algorithmic_bytes
+    nbuf = max(2, min(24, -(-2 * MALL_BYTES // set_bytes)))
+    log("buffer sets: %d x %.1f MB" % (nbuf, set_bytes / 1e6))
+    dA = [torch.from_numpy(A.view(np.int16)).cuda() for _ in range(nbuf)]
+    dB = [torch.from_numpy(B.view(np.int16)).cuda() for _ in range(nbuf)]
+    db = [torch.from_numpy(bias.view(np.int16)).cuda() for _ in range(nbuf)]
+    dY = [torch.empty((w.M, w.N), dtype=torch.bfloat16, device="cuda") for _ in range(nbuf)]
+    stream = torch.cuda.current_stream()
+
+    prob = tf.Problem(w.M, w.N, w.K)
+    variants = prob.variants()
+    names = [v.name.decode() for v in variants]
+    tune = None
+    if not args.no_tune:
+        t0 = time.perf_counter()
+        best, rep, rlog = prob.tune(dA[0], dB[0], db[0], dY[0], stream=stream)
+        tune_s = time.perf_counter() - t0
+        rounds = [{"variant": names[r.variant_id], "t_med_us": round(r.t_med_us, 3), "status": r.status,
+                   "parity_ok": r.parity_ok, "bottleneck": tf.BOTTLENECK_NAMES[r.bottleneck],
+                   "pct_mfma_peak": round(r.pct_mfma_peak, 2), "pct_hbm_peak": round(r.pct_hbm_peak, 2)} for r in rlog]
+        for r in rounds:
+            log("  loop:", r)
+        tune = {"selected": names[best], "rounds": len(rlog) - 1, "wall_s": round(tune_s, 3),
+                "naive_us": round(rlog[0].t_med_us, 3), "tuned_us": round(rep.t_med_us, 3),
+                "tuned_vs_naive": round(rlog[0].t_med_us / rep.t_med_us, 2),
+                "one_shot_pick": rounds[1]["variant"] if len(rounds) > 1 else None,
+                "one_shot_us": rounds[1]["t_med_us"] if len(rounds) > 1 else None, "log": rounds}
+        vid = best
+    if args.variant is not None:
+        if args.variant not in names:
+            log("unknown variant %s; have: %s" % (args.variant, ", ".join(names)))
+            sys.exit(2)
+        vid = names.index(args.variant)
+    elif args.no_tune:
+        log("--no-tune needs --variant")
+        sys.exit(2)
+    v = variants[vid]
+    log("timing variant", names[vid])
+
+    # marshal the arguments once: the timed loop is nothing but tf_variant_run calls
+    import ctypes
+    run = tf.lib().tf_variant_run
+    sp = ctypes.c_void_p(stream.cuda_stream)
+    argsets = [(prob._h, vid, ctypes.c_void_p(dA[j].data_ptr()), ctypes.c_void_p(dB[j].data_ptr()),
+                ctypes.c_void_p(db[j].data_ptr()), ctypes.c_void_p(dY[j].data_ptr()), None, 0, sp)
+               for j in range(nbuf)]
+    prob.run(vid, dA[0], dB[0], db[0], dY[0], stream=stream)    # first use: workspace, attributes, errors raised
+
+    def step(i):
+        if run(*argsets[i % nbuf]) != 0:
+            raise RuntimeError(tf.lib().tf_last_error().decode())
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(args.steps):
+        step(i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall_ms / args.steps
+    kern_us = ev_ms * 1e3 / args.steps          # average launch duration on the launch stream
+    tflops = w.flops / (ms_per_step * 1e-3) * 1e-12
+    if w.bound == "hbm":
+        roof = {"bound": "hbm", "achieved": w.algorithmic_bytes / (kern_us * 1e-6) * 1e-9, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": w.flops / (kern_us * 1e-6) * 1e-12, "peak": BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = names[vid]
+    roof["avg_launch_us"] = kern_us
+
+    out = {
+        "metric": "GEMM+epilogue TFLOP/s (bf16 GELU_erf(A.B+bias), fp32 accumulate)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: M=%d N=%d K=%d bf16, seed %d" % (w.name, w.M, w.N, w.K, w.seed),
+                   "variant": names[vid], "grid": v.grid, "split_k": v.split_k, "buffer_sets": nbuf},
+        "pct_bf16_mfma_peak": 100.0 * tflops / BF16_PEAK_TFLOPS,
+        "hbm_gbs_algorithmic": w.algorithmic_bytes / (ms_per_step * 1e-3) * 1e-9,
+        "roofline": roof,
+        "tune": tune,
+    }
+    if not args.no_cpu:
+        log("timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(w, A, B, bias)
+    else:
+        out["cpu_baseline"] = None
+    prob.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

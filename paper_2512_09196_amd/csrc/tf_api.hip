@@ -125,6 +125,16 @@ void build_family(tf_problem* p) {
       add_variant(p, v, im);
     }
   }
+  // One counter area for the whole family, so that the partial sums of one variant never
+  // land on the counters of another: [counters | partial sums].
+  size_t maxc = 0;
+  for (const VariantImpl& o : p->impl) maxc = std::max(maxc, o.counter_bytes);
+  for (size_t i = 0; i < p->impl.size(); ++i) {
+    if (p->family[i].split_k > 1) {
+      p->impl[i].counter_bytes = maxc;
+      p->family[i].workspace_bytes = (int64_t)(maxc + (size_t)p->family[i].split_k * d.M * d.N * 4);
+    }
+  }
 }
 
 // ---------------------------------------------------------------- launch
@@ -402,7 +412,9 @@ extern "C" tf_status tf_hw_query(int32_t device, tf_hw* out) {
   snprintf(out->name, sizeof(out->name), "%s %s", pr.name, pr.gcnArchName);
   out->cus = pr.multiProcessorCount;
   out->wave_size = pr.warpSize;
-  out->lds_bytes_per_cu = (int32_t)pr.sharedMemPerMultiprocessor;
+  // LDS of one CU = the most one work-group may allocate (the per-multiprocessor field of the
+  // runtime reports a chip-wide total on this device)
+  out->lds_bytes_per_cu = (int32_t)pr.sharedMemPerBlock;
   out->l2_bytes = pr.l2CacheSize;
   out->hbm_bytes = (int64_t)pr.totalGlobalMem;
   out->clock_mhz = pr.clockRate / 1000.0;

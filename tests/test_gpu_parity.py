@@ -186,6 +186,24 @@ def test_split_k_is_deterministic_and_counters_self_clean():
                 assert np.array_equal(raw, first), "run %d of %s differs" % (rep, v.name.decode())
 
 
+def test_split_k_variants_with_different_tile_counts_share_one_workspace():
+    # tile shapes with 4, 8, 16 and 64 output tiles take turns on the problem's workspace:
+    # the partial sums of one must never land on the arrival counters of another
+    M, N, K = 512, 512, 2048
+    A, B, bias = wl.make_custom(M, N, K, seed=43)
+    y, z, s = orc.gemm_bias_gelu(A, B, bias)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    out = gu.OutBuf(M, N)
+    with tf.Problem(M, N, K) as prob:
+        sk = [v for v in prob.variants() if v.split_k > 1]
+        assert len({(v.bm, v.bn) for v in sk}) >= 3
+        for order in (sk, sk[::-1], sk[::3] + sk[1::3] + sk[2::3]):
+            for v in order:
+                got, intact, _ = gu.run_variant(prob, v.id, dA, dB, dbias, out)
+                assert intact and not np.isnan(got).any(), v.name.decode()
+                assert np.all(np.abs(got - y) <= gu.strict_bound(y, z, s, K)), v.name.decode()
+
+
 def test_caller_workspace_and_errors():
     torch = gu.torch_mod()
     M, N, K = 128, 128, 2048
