@@ -94,18 +94,26 @@ struct TileLoader {
   }
 
   // memory -> LDS without registers. Requires every k of the tile to be < K.
-  __device__ __forceinline__ void issue_direct(const uint16_t* Ak, const uint16_t* Bk, char* stage, int wave) const {
+  // Written as inline assembly: M0 carries the wave-uniform LDS destination, each lane lands
+  // at M0 + 16 * lane, the source is an SGPR base plus this lane's 32-bit byte offset. The
+  // transfers are counted by vmcnt; the kernel waits for them explicitly before the barrier
+  // that publishes a tile, so the compiler needs no knowledge of them (given the builtin, it
+  // would make every later LDS read wait for all transfers in flight, including the tiles
+  // prefetched for later steps). Nothing else in these kernels uses M0.
+  __device__ __forceinline__ static void gload_lds16(unsigned lds_addr, unsigned voff, const void* sbase) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+  }
+  __device__ __forceinline__ void issue_direct(const uint16_t* Ak, const uint16_t* Bk, unsigned stage_lds, int wave) const {
 #pragma unroll
     for (int q = 0; q < C::A_PER_WAVE; ++q) {
       const int ia = wave + C::NWAVES * q;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)((const char*)Ak + a_src[q]),
-                                       (__attribute__((address_space(3))) void*)(stage + ia * 1024), 16, 0, 0);
+      gload_lds16(__builtin_amdgcn_readfirstlane(stage_lds + ia * 1024), a_src[q], Ak);
     }
 #pragma unroll
     for (int q = 0; q < C::B_PER_WAVE; ++q) {
       const int ib = wave + C::NWAVES * q;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)((const char*)Bk + b_src[q]),
-                                       (__attribute__((address_space(3))) void*)(stage + C::A_BYTES + ib * 1024), 16, 0, 0);
+      gload_lds16(__builtin_amdgcn_readfirstlane(stage_lds + C::A_BYTES + ib * 1024), b_src[q], Bk);
     }
   }
 
@@ -142,6 +150,15 @@ struct TileLoader {
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
 // vmcnt = bits [3:0] and [15:14], expcnt [6:4] and lgkmcnt [11:8] left at "no wait").
+// Work-group barrier for the direct-to-LDS pipeline: this wave's LDS reads have returned
+// (lgkmcnt 0), then s_barrier. Unlike __syncthreads() it does not wait for vector-memory
+// operations, so tiles prefetched for later steps stay in flight across it; the caller waits
+// for the tile it is about to publish with wait_vmcnt<> first. The asm memory clobber keeps
+// the compiler from moving LDS accesses across it.
+__device__ __forceinline__ void barrier_lds() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
@@ -275,68 +292,135 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   const uint16_t* Bk = p.B + (long)kt_begin * C::BK * p.ldb;
   const long b_step = (long)C::BK * p.ldb;
 
-  auto compute = [&](const char* stage) {
+  // ---- main loop, software pipelined by hand (one wave per SIMD has nobody to hide behind):
+  //  * fragments are double buffered in registers: the LDS reads of k16-step kk+1 are issued
+  //    before the MFMAs of step kk;
+  //  * the loop is rotated: the barrier that hands over the next tile, the global loads of the
+  //    tile after it and the first fragment reads of the next tile are all issued BEFORE the
+  //    last 16-wide step of the current tile, whose MFMAs cover their latency.
+  bf16x8 af[2][C::TM], bfr[2][C::TN];
+  auto read_frags = [&](const char* stage, int kk, int set) {
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 af[C::TM], bfr[C::TN];
+    for (int i = 0; i < C::TM; ++i)
+      af[set][i] = *(const bf16x8*)(stage + a_off[kk] + i * 32 * 128);
 #pragma unroll
-      for (int i = 0; i < C::TM; ++i)
-        af[i] = *(const bf16x8*)(stage + a_off[kk] + i * 32 * 128);
+    for (int t = 0; t < C::TN; ++t) {
+      const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + 4 * C::B_ROW_BYTES));
+      const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      bfr[set][t] = __builtin_bit_cast(bf16x8, v);
+    }
+  };
+  auto mfma_step = [&](int set) {
 #pragma unroll
-      for (int t = 0; t < C::TN; ++t) {
-        const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + 4 * C::B_ROW_BYTES));
-        const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        bfr[t] = __builtin_bit_cast(bf16x8, v);
-      }
+    for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-      for (int i = 0; i < C::TM; ++i)
+      for (int t = 0; t < C::TN; ++t)
+        acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][t], af[set][i], acc[i][t], 0, 0, 0);
+  };
+  // scheduling hint for one pipelined step: alternate one MFMA with one LDS read until the
+  // reads are all issued, so that the matrix pipe never waits for the whole batch of reads
+  constexpr int N_DS = C::TM + 2 * C::TN, N_MFMA = C::TM * C::TN;
+  auto interleave_hint = [&]() {
 #pragma unroll
-        for (int t = 0; t < C::TN; ++t)
-          acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[t], af[i], acc[i][t], 0, 0, 0);
+    for (int x = 0; x < (N_DS < N_MFMA ? N_DS : N_MFMA); ++x) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one DS read
     }
   };
 
+  // The last tile is peeled off the loop, so the loop body has no branch inside and is
+  // scheduled as one block. Prefetches that would run past the last tile re-fetch the last
+  // tile instead (into a buffer nobody reads any more): the number of transfers in flight is
+  // then the same in every iteration and the vmcnt waits are constants.
+  const int last = nkt - 1;
   if constexpr (C::DIRECT) {
-    // Ring of STAGES buffers; tiles 0 .. STAGES-2 are in flight before the loop.
+    constexpr int D = C::STAGES - 1;                            // tiles in flight ahead of the one computed
     constexpr int PER_TILE = C::A_PER_WAVE + C::B_PER_WAVE;   // transfers per wave per tile
+    static_assert((D - 1) * PER_TILE < 64, "vmcnt range");
+    const unsigned lds0 = (unsigned)(size_t)smem;
+    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * C::BK; };
+    auto tile_b = [&](int t) { return Bk + (long)(t < last ? t : last) * b_step; };
+    if (nkt > 0) {
 #pragma unroll
-    for (int s = 0; s < C::STAGES - 1; ++s) {
-      if (s < nkt) ld.issue_direct(Ak + (long)s * C::BK, Bk + (long)s * b_step, smem + s * C::STAGE_BYTES, wave);
-    }
-    int stage = 0;
-    for (int kt = 0; kt < nkt; ++kt) {
-      // tile kt has landed once at most the transfers of the tiles issued after it remain
-      const int later = (nkt - 1 - kt) < (C::STAGES - 2) ? (nkt - 1 - kt) : (C::STAGES - 2);
-      if (later <= 0) wait_vmcnt<0>();
-      else if (later == 1) wait_vmcnt<PER_TILE < 64 ? PER_TILE : 0>();
-      else wait_vmcnt<2 * PER_TILE < 64 ? 2 * PER_TILE : 0>();
-      __syncthreads();   // everyone's part of tile kt is in LDS; everyone is done with the buffer refilled below
-      const int nxt = kt + C::STAGES - 1;
-      if (nxt < nkt) {
-        int ws = stage + C::STAGES - 1;
-        if (ws >= C::STAGES) ws -= C::STAGES;
-        ld.issue_direct(Ak + (long)nxt * C::BK, Bk + (long)nxt * b_step, smem + ws * C::STAGE_BYTES, wave);
+      for (int s = 0; s < D; ++s) ld.issue_direct(tile_a(s), tile_b(s), lds0 + s * C::STAGE_BYTES, wave);
+      wait_vmcnt<(D - 1) * PER_TILE>();      // tile 0 has landed, D-1 younger tiles may still fly
+      barrier_lds();  
+      ld.issue_direct(tile_a(D), tile_b(D), lds0 + D * C::STAGE_BYTES, wave);
+      read_frags(smem, 0, 0);
+      int stage = 0;
+      for (int kt = 0; kt < last; ++kt) {
+        const char* cur = smem + stage * C::STAGE_BYTES;
+        int nstage = stage + 1;
+        if (nstage == C::STAGES) nstage = 0;
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+          read_frags(cur, kk + 1, (kk + 1) & 1);
+          mfma_step(kk & 1);
+          interleave_hint();
+        }
+        wait_vmcnt<(D - 1) * PER_TILE>();    // tile kt+1 has landed
+        barrier_lds();                       // ... for every wave, and every wave is done reading tile kt
+        ld.issue_direct(tile_a(kt + 1 + D), tile_b(kt + 1 + D), lds0 + stage * C::STAGE_BYTES, wave);
+        read_frags(smem + nstage * C::STAGE_BYTES, 0, 0);
+        mfma_step(1);                        // k16-step 3 of tile kt covers the latencies above
+        interleave_hint();
+        stage = nstage;
       }
-      compute(smem + stage * C::STAGE_BYTES);
-      if (++stage == C::STAGES) stage = 0;
+      {
+        const char* cur = smem + stage * C::STAGE_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+          read_frags(cur, kk + 1, (kk + 1) & 1);
+          mfma_step(kk & 1);
+          interleave_hint();
+        }
+        mfma_step(1);
+      }
+      wait_vmcnt<0>();                       // the redundant prefetches must not outlive their LDS
     }
   } else {
-    // Register-staged double buffering: loads of tile kt+1 are in flight during the MFMAs of tile kt.
+    // Register-staged double buffering: the global loads of tile kt+1 fly during tile kt and are
+    // written to the other LDS buffer before the hand-over barrier.
     static_assert(C::DIRECT || C::STAGES == 2, "register staging uses two buffers");
     u32x4 ra[C::A_PER_WAVE], rb[C::B_PER_WAVE];
     const int kbase = kt_begin * C::BK;
+    auto load_tile = [&](int t) {
+      const int tt = t < last ? t : last;
+      ld.load_regs(Ak + (long)tt * C::BK, Bk + (long)tt * b_step, kbase + tt * C::BK, p.K, ra, rb);
+    };
     if (nkt > 0) {
-      ld.load_regs(Ak, Bk, kbase, p.K, ra, rb);
+      load_tile(0);
       ld.store_regs(smem, wave, lane, ra, rb);
-    }
-    for (int kt = 0; kt < nkt; ++kt) {
       __syncthreads();
-      const bool more = kt + 1 < nkt;
-      if (more) ld.load_regs(Ak + (long)(kt + 1) * C::BK, Bk + (long)(kt + 1) * b_step, kbase + (kt + 1) * C::BK, p.K, ra, rb);
-      compute(smem + (kt & 1) * C::STAGE_BYTES);
-      if (more) ld.store_regs(smem + ((kt + 1) & 1) * C::STAGE_BYTES, wave, lane, ra, rb);
+      load_tile(1);
+      read_frags(smem, 0, 0);
+      for (int kt = 0; kt < last; ++kt) {
+        const char* cur = smem + (kt & 1) * C::STAGE_BYTES;
+        char* nxt = smem + ((kt + 1) & 1) * C::STAGE_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+          read_frags(cur, kk + 1, (kk + 1) & 1);
+          mfma_step(kk & 1);
+          interleave_hint();
+        }
+        ld.store_regs(nxt, wave, lane, ra, rb);   // buffer last read in iteration kt-1, released by its barrier
+        __syncthreads();
+        load_tile(kt + 2);
+        read_frags(nxt, 0, 0);
+        mfma_step(1);
+      }
+      {
+        const char* cur = smem + (last & 1) * C::STAGE_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+          read_frags(cur, kk + 1, (kk + 1) & 1);
+          mfma_step(kk & 1);
+          interleave_hint();
+        }
+        mfma_step(1);
+      }
     }
   }
 
