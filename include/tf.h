@@ -87,7 +87,9 @@ typedef struct {
   int32_t bm, bn, bk;      /* macro tile */
   int32_t waves_m, waves_n;/* wave grid inside the work-group (64-lane waves) */
   int32_t stages;          /* LDS buffers in the ring */
-  int32_t split_k;         /* K slices reduced in fp32, in slice order, by the last slice to arrive */
+  int32_t split_k;         /* K slices, summed in fp32 in slice order (1 = no split) */
+  int32_t fused_reduce;    /* split_k > 1: 1 = the last slice to arrive reduces inside the GEMM kernel (one launch,
+                              arrival counters); 0 = a second kernel sums the slices and applies the epilogue */
   int32_t direct_to_lds;   /* 1: global_load_lds staging; 0: via registers (allows a ragged K tail) */
   int32_t xcd_swizzle;     /* 1: work-group ids renumbered so that neighbouring tiles share an XCD L2 */
   int32_t group_m;         /* tile rows per group in the tile order */

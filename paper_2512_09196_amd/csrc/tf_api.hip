@@ -109,20 +109,24 @@ void build_family(tf_problem* p) {
       if (s > 1 && (ktiles / s < 4 || tm * tn >= 2L * cus)) continue;
       const long per = cdivl(ktiles, s);
       if (s > 1 && per * (s - 1) >= ktiles) continue;      // would leave an empty slice
-      tf_variant_desc v;
-      memset(&v, 0, sizeof(v));
-      v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n;
-      v.stages = k.stages; v.split_k = s; v.direct_to_lds = k.direct_to_lds; v.xcd_swizzle = 1;
-      v.group_m = (int32_t)std::min<long>(tm, 8);
-      v.threads = k.threads; v.lds_bytes = k.lds_bytes;
-      v.grid = (int32_t)(tm * tn * s);
-      VariantImpl im;
-      im.lds_index = i; im.ktiles_per_split = (int)per; im.tiles_m = (int)tm; im.tiles_n = (int)tn;
-      im.counter_bytes = s > 1 ? (size_t)((tm * tn * 4 + 255) / 256 * 256) : 0;
-      v.workspace_bytes = s > 1 ? (int64_t)(im.counter_bytes + (size_t)s * d.M * d.N * 4) : 0;
-      snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d_s%d_%s_sk%d", k.bm, k.bn, k.bk, k.waves_m, k.waves_n,
-               k.stages, k.direct_to_lds ? "direct" : "regs", s);
-      add_variant(p, v, im);
+      for (int fused = 1; fused >= 0; --fused) {
+        if (s == 1 && fused == 0) continue;
+        tf_variant_desc v;
+        memset(&v, 0, sizeof(v));
+        v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n;
+        v.stages = k.stages; v.split_k = s; v.fused_reduce = (s > 1) ? fused : 0;
+        v.direct_to_lds = k.direct_to_lds; v.xcd_swizzle = 1;
+        v.group_m = (int32_t)std::min<long>(tm, 8);
+        v.threads = k.threads; v.lds_bytes = k.lds_bytes;
+        v.grid = (int32_t)(tm * tn * s);
+        VariantImpl im;
+        im.lds_index = i; im.ktiles_per_split = (int)per; im.tiles_m = (int)tm; im.tiles_n = (int)tn;
+        im.counter_bytes = s > 1 ? (size_t)((tm * tn * 4 + 255) / 256 * 256) : 0;
+        v.workspace_bytes = s > 1 ? (int64_t)(im.counter_bytes + (size_t)s * d.M * d.N * 4) : 0;
+        snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d_s%d_%s_sk%d%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n,
+                 k.stages, k.direct_to_lds ? "direct" : "regs", s, s > 1 ? (fused ? "f" : "r") : "");
+        add_variant(p, v, im);
+      }
     }
   }
   // One counter area for the whole family, so that the partial sums of one variant never
@@ -163,7 +167,7 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
   memset(&g, 0, sizeof(g));
   g.A = (const uint16_t*)A; g.B = (const uint16_t*)B; g.bias = (const uint16_t*)bias; g.Y = Y;
   g.M = d.M; g.N = d.N; g.K = d.K; g.lda = d.lda; g.ldb = d.ldb; g.ldy = d.ldy;
-  g.epi = d.epi; g.split_k = v.split_k; g.group_m = v.group_m > 0 ? v.group_m : 1; g.xcd_swizzle = v.xcd_swizzle;
+  g.epi = d.epi; g.split_k = v.split_k; g.fused_reduce = v.fused_reduce; g.group_m = v.group_m > 0 ? v.group_m : 1; g.xcd_swizzle = v.xcd_swizzle;
   if (v.kind == TF_KIND_NAIVE) {
     if (cdivl(d.M, 4) > 65535) return fail(TF_E_UNSUPPORTED, "naive variant: M too large for the grid");
     tf::launch_naive(g, stream);
@@ -207,6 +211,7 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
       p->attr_done[im.lds_index] = 1;
     }
     k.launch(g, dim3((unsigned)v.grid), stream);
+    if (v.split_k > 1 && !v.fused_reduce) tf::launch_splitk_reduce(g, stream);
   }
   TF_HIP(hipGetLastError());
   return TF_OK;

@@ -100,7 +100,14 @@ struct TileLoader {
   // that publishes a tile, so the compiler needs no knowledge of them (given the builtin, it
   // would make every later LDS read wait for all transfers in flight, including the tiles
   // prefetched for later steps). Nothing else in these kernels uses M0.
-  __device__ __forceinline__ static void gload_lds16(unsigned lds_addr, unsigned voff, const void* sbase) {
+  __device__ __forceinline__ static void gload_lds16(unsigned lds_addr, unsigned voff, const void* base) {
+    // the base is the same for every lane; say so, or it may be handed over in vector registers
+    const unsigned long long b = (unsigned long long)base;
+    // (the builtin returns a signed int: go through unsigned, or the low half sign-extends)
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
+    const unsigned long long sb = (unsigned long long)lo | ((unsigned long long)hi << 32);
+    const void* sbase = (const void*)sb;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
   }
@@ -165,8 +172,19 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
+// Four fp32 stored with device ("agent") scope: written through the L2 of this XCD, so a
+// work-group on another XCD (another L2) reads the new value from memory. Split-K uses it for
+// the partial sums instead of a device-wide fence, which would write back and invalidate the
+// whole L2 twice per work-group.
+__device__ __forceinline__ void store_through_f32x4(float* ptr, const f32x4 v) {
+  __hip_atomic_store(ptr + 0, v[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(ptr + 1, v[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(ptr + 2, v[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(ptr + 3, v[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Split-K: one slice's partial tile -> workspace (fp32, [slice][M][N]).
-template <class C, bool FULL>
+template <class C, bool FULL, bool THROUGH>
 __device__ __forceinline__ void store_partial(const f32x16 (&acc)[C::TM][C::TN], float* wsk, const GemmParams& p,
                                               int wm0, int wn0) {
 #pragma unroll
@@ -179,7 +197,8 @@ __device__ __forceinline__ void store_partial(const f32x16 (&acc)[C::TM][C::TN],
         const int n = wn0 + 32 * t + 8 * q;
         if (FULL || (m < p.M && n < p.N)) {
           const f32x4 v = {acc[i][t][4 * q], acc[i][t][4 * q + 1], acc[i][t][4 * q + 2], acc[i][t][4 * q + 3]};
-          *(f32x4*)(wsk + (size_t)m * p.N + n) = v;
+          if (THROUGH) store_through_f32x4(wsk + (size_t)m * p.N + n, v);
+          else *(f32x4*)(wsk + (size_t)m * p.N + n) = v;
         }
       }
   }
@@ -201,7 +220,17 @@ __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const 
         f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
         if (FULL || (m < p.M && n < p.N)) {
           const float* src = p.ws + (size_t)m * p.N + n;
-          for (int sidx = 0; sidx < p.split_k; ++sidx) sum += *(const f32x4*)(src + (size_t)sidx * slice);
+          for (int sidx = 0; sidx < p.split_k; ++sidx) {
+            // device-scope loads: served from memory, never from a line this XCD's L2 kept
+            // from an earlier launch
+            const float* q4 = src + (size_t)sidx * slice;
+            f32x4 v;
+            v[0] = __hip_atomic_load(q4 + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v[1] = __hip_atomic_load(q4 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v[2] = __hip_atomic_load(q4 + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v[3] = __hip_atomic_load(q4 + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sum += v;
+          }
         }
         acc[i][t][4 * q] = sum[0]; acc[i][t][4 * q + 1] = sum[1];
         acc[i][t][4 * q + 2] = sum[2]; acc[i][t][4 * q + 3] = sum[3];
@@ -438,9 +467,18 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     // publish the partial tile; the last slice to arrive sums all slices in slice order
     const size_t slice = (size_t)p.M * p.N;
     float* wsk = p.ws + (size_t)tc.ks * slice;
-    if (full) store_partial<C, true>(acc, wsk, p, wm0, wn0);
-    else store_partial<C, false>(acc, wsk, p, wm0, wn0);
-    __threadfence();
+    if (!p.fused_reduce) {
+      // two-kernel split-K: plain stores; a reduce kernel launched behind this one sums the
+      // slices in slice order and applies the epilogue (the kernel boundary orders the two)
+      if (full) store_partial<C, true, false>(acc, wsk, p, wm0, wn0);
+      else store_partial<C, false, false>(acc, wsk, p, wm0, wn0);
+      return;
+    }
+    if (full) store_partial<C, true, true>(acc, wsk, p, wm0, wn0);
+    else store_partial<C, false, true>(acc, wsk, p, wm0, wn0);
+    // every write-through store of this wave has been acknowledged before the wave reaches the
+    // barrier, so the ticket taken after it is ordered behind the whole work-group's partials
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     __shared__ unsigned ticket;
     unsigned* ctr = p.counters + (tc.tm * p.tiles_n + tc.tn);
@@ -448,7 +486,6 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     __syncthreads();
     if (ticket != (unsigned)(p.split_k - 1)) return;
     if (tid == 0) *ctr = 0u;          // ready for the next launch
-    __threadfence();
     if (full) sum_partials<C, true>(acc, p, wm0, wn0);
     else sum_partials<C, false>(acc, p, wm0, wn0);
   }

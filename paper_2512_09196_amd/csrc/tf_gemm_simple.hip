@@ -64,6 +64,40 @@ __global__ void tf_fill_u32_kernel(unsigned* p, size_t n, unsigned v) {
   if (i < n) p[i] = v;
 }
 
+// Second kernel of the two-kernel split-K: Y = epilogue(sum_s ws[s] + bias), slices summed in
+// slice order. One thread per four consecutive n (N is a multiple of 8 for every tile kernel).
+__global__ void __launch_bounds__(256) tf_splitk_reduce_kernel(const GemmParams p) {
+  const size_t quads_per_row = (size_t)p.N / 4;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)p.M * quads_per_row) return;
+  const size_t m = i / quads_per_row;
+  const int n = (int)(i % quads_per_row) * 4;
+  const size_t slice = (size_t)p.M * p.N;
+  const float* src = p.ws + m * p.N + n;
+  f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int s = 0; s < p.split_k; ++s) sum += *(const f32x4*)(src + (size_t)s * slice);
+  const u32x2 braw = *(const u32x2*)(p.bias + n);
+  const float z0 = sum[0] + __builtin_bit_cast(float, braw[0] << 16);
+  const float z1 = sum[1] + __builtin_bit_cast(float, braw[0] & 0xffff0000u);
+  const float z2 = sum[2] + __builtin_bit_cast(float, braw[1] << 16);
+  const float z3 = sum[3] + __builtin_bit_cast(float, braw[1] & 0xffff0000u);
+  if (p.epi == TF_EPI_NONE_F32) {
+    const f32x4 v = {z0, z1, z2, z3};
+    *(f32x4*)((float*)p.Y + m * p.ldy + n) = v;
+  } else {
+    u32x2 o;
+    o[0] = pack_bf16x2(gelu_erf(z0), gelu_erf(z1));
+    o[1] = pack_bf16x2(gelu_erf(z2), gelu_erf(z3));
+    *(u32x2*)((uint16_t*)p.Y + m * p.ldy + n) = o;
+  }
+}
+
+void launch_splitk_reduce(const GemmParams& p, hipStream_t s) {
+  const size_t quads = (size_t)p.M * (p.N / 4);
+  hipLaunchKernelGGL(tf_splitk_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, p);
+}
+const void* splitk_reduce_func() { return (const void*)tf_splitk_reduce_kernel; }
+
 void launch_naive(const GemmParams& p, hipStream_t s) {
   dim3 grid((p.N + 63) / 64, (p.M + 3) / 4);
   hipLaunchKernelGGL(tf_gemm_naive_kernel, grid, dim3(256), 0, s, p);

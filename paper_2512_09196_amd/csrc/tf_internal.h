@@ -19,6 +19,7 @@ struct GemmParams {
   long lda, ldb, ldy;     // in elements
   int tiles_m, tiles_n;
   int split_k;            // number of K slices
+  int fused_reduce;       // split-K: 1 = the last slice to arrive reduces inside the GEMM kernel; 0 = a second kernel does
   int ktiles_per_split;   // K tiles (of BK) per slice; the last slice may be shorter
   int epi;                // tf_epilogue
   int group_m;            // tile rows per L2 group in the tile order (>= 1)
@@ -40,5 +41,7 @@ void launch_mfma_direct(const GemmParams&, hipStream_t);
 const void* naive_func();
 const void* mfma_direct_func();
 void launch_fill_u32(unsigned* p, size_t n, unsigned v, hipStream_t);
+void launch_splitk_reduce(const GemmParams&, hipStream_t);   // sums ws slices in order, bias + epilogue -> Y
+const void* splitk_reduce_func();
 
 }  // namespace tf

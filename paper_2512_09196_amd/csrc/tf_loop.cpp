@@ -124,7 +124,15 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   if (!v->direct_to_lds) ktile *= 1.10;                          // VALU/VGPR traffic of register staging
   const double exposed = 400.0 / (resident * (v->stages - 1));   // barrier + staging latency not hidden
   const double epi = v->bm * (double)v->bn / 4.0;                // 16 VALU ops per element, 64 lanes/clk
-  const double splitk = v->split_k > 1 ? v->bm * (double)v->bn * (1.0 + v->split_k) / 32.0 : 0.0;
+  // split-K: every slice writes its fp32 partial tile (about 32 B/clk per CU). Fused, the last
+  // slice of a tile then reads all slices back alone with device-scope loads (about 16 B/clk),
+  // a serial tail; otherwise a second kernel streams the workspace once.
+  double splitk = 0.0, reduce_us = 0.0;
+  if (v->split_k > 1) {
+    splitk = v->bm * (double)v->bn * 4.0 / 32.0;
+    if (v->fused_reduce) splitk += v->bm * (double)v->bn * 4.0 * v->split_k / 16.0;
+    else reduce_us = 2.5 + (v->split_k + 0.5) * 4.0 * pr->M * (double)pr->N / (0.5 * hw->hbm_gbs_peak * 1e3);
+  }
   // a round gives every CU up to `resident` work-groups, which share its pipes; the last
   // round may be thinner
   double cycles = 0.0;
@@ -137,7 +145,7 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   }
   double us = cycles / hw->clock_mhz;
   const double ws_us = v->split_k > 1 ? 2.0 * v->split_k * 4.0 * pr->M * (double)pr->N / (hw->hbm_gbs_peak * 1e3) : 0.0;
-  return fmax(us, hbm_us + ws_us) + 2.0;
+  return fmax(us, hbm_us + ws_us) + 2.0 + reduce_us;
 }
 
 // ------------------------------------------------------------------ Proposal
