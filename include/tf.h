@@ -91,6 +91,8 @@ typedef struct {
   int32_t fused_reduce;    /* split_k > 1: 1 = the last slice to arrive reduces inside the GEMM kernel (one launch,
                               arrival counters); 0 = a second kernel sums the slices and applies the epilogue */
   int32_t direct_to_lds;   /* 1: global_load_lds staging; 0: via registers (allows a ragged K tail) */
+  int32_t a_bypass_lds;    /* 1: A fragments are loaded from memory straight into MFMA operand registers, only B is
+                              staged in LDS (one wave column per work-group) */
   int32_t xcd_swizzle;     /* 1: work-group ids renumbered so that neighbouring tiles share an XCD L2 */
   int32_t group_m;         /* tile rows per group in the tile order */
   int32_t threads;         /* work-group size */

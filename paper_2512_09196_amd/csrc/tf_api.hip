@@ -115,7 +115,7 @@ void build_family(tf_problem* p) {
         memset(&v, 0, sizeof(v));
         v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n;
         v.stages = k.stages; v.split_k = s; v.fused_reduce = (s > 1) ? fused : 0;
-        v.direct_to_lds = k.direct_to_lds; v.xcd_swizzle = 1;
+        v.direct_to_lds = k.direct_to_lds; v.a_bypass_lds = k.a_bypass_lds; v.xcd_swizzle = 1;
         v.group_m = (int32_t)std::min<long>(tm, 8);
         v.threads = k.threads; v.lds_bytes = k.lds_bytes;
         v.grid = (int32_t)(tm * tn * s);
@@ -124,7 +124,8 @@ void build_family(tf_problem* p) {
         im.counter_bytes = s > 1 ? (size_t)((tm * tn * 4 + 255) / 256 * 256) : 0;
         v.workspace_bytes = s > 1 ? (int64_t)(im.counter_bytes + (size_t)s * d.M * d.N * 4) : 0;
         snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d_s%d_%s_sk%d%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n,
-                 k.stages, k.direct_to_lds ? "direct" : "regs", s, s > 1 ? (fused ? "f" : "r") : "");
+                 k.stages, k.a_bypass_lds ? "areg" : (k.direct_to_lds ? "direct" : "regs"), s,
+                 s > 1 ? (fused ? "f" : "r") : "");
         add_variant(p, v, im);
       }
     }

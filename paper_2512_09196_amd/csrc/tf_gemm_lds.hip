@@ -22,14 +22,19 @@
 
 namespace tf {
 
-template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool DIRECT_>
+template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool DIRECT_, bool ABYPASS_ = false>
 struct LdsCfg {
   static constexpr int BM = BM_, BN = BN_, BK = 64, WM = WM_, WN = WN_, STAGES = STAGES_;
   static constexpr bool DIRECT = DIRECT_;
+  // ABYPASS: the A operand never enters LDS. Each wave loads its own A fragments from memory
+  // straight into registers (WN must be 1, so no two waves need the same A rows) and only B is
+  // staged. This halves the LDS write traffic, which is what bounds the two-operand scheme.
+  static constexpr bool ABYPASS = ABYPASS_;
   static constexpr int NWAVES = WM * WN, THREADS = NWAVES * 64;
   static constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
   static constexpr int TM = WTM / 32, TN = WTN / 32;       // 32x32 MFMA blocks per wave
-  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BK * BN * 2;
+  static constexpr int A_BYTES = ABYPASS ? 0 : BM * BK * 2, B_BYTES = BK * BN * 2;
+  static_assert(!ABYPASS || (WN == 1 && DIRECT && STAGES == 2), "A bypass: one wave column, direct B staging, two buffers");
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
   static constexpr int A_INSTR = A_BYTES / 1024;           // wave-wide 1 KB transfers per tile
@@ -58,12 +63,13 @@ struct TileLoader {
   // Per-lane, per-transfer source offsets (in elements, relative to the tile's first k) and
   // validity. Computed once; the K step only moves the base pointers.
   // (byte offsets from the tile's first k; 32 bits: the host rejects tensors of 4 GiB or more)
-  unsigned a_src[C::A_PER_WAVE];
+  static constexpr int NA = C::A_PER_WAVE > 0 ? C::A_PER_WAVE : 1;   // (no zero-length arrays)
+  unsigned a_src[NA];
   unsigned b_src[C::B_PER_WAVE];
-  int a_k[C::A_PER_WAVE];        // k offset (elements) of the lane's chunk inside the tile
+  int a_k[NA];                   // k offset (elements) of the lane's chunk inside the tile
   int b_k[C::B_PER_WAVE];        // k row of the lane inside the tile
   bool b_ok[C::B_PER_WAVE];      // column chunk inside N
-  bool a_ok[C::A_PER_WAVE];      // row inside M
+  bool a_ok[NA];                 // row inside M
 
   __device__ __forceinline__ void init(const GemmParams& p, int m0, int n0, int wave, int lane) {
 #pragma unroll
@@ -124,9 +130,29 @@ struct TileLoader {
     }
   }
 
+  __device__ __forceinline__ void issue_a_one(int q, const uint16_t* Ak, unsigned stage_lds, int wave) const {
+    const int ia = wave + C::NWAVES * q;
+    gload_lds16(__builtin_amdgcn_readfirstlane(stage_lds + ia * 1024), a_src[q < NA ? q : 0], Ak);
+  }
+  __device__ __forceinline__ void issue_b_one(int q, const uint16_t* Bk, unsigned stage_lds, int wave) const {
+    const int ib = wave + C::NWAVES * q;
+    gload_lds16(__builtin_amdgcn_readfirstlane(stage_lds + C::A_BYTES + ib * 1024), b_src[q], Bk);
+  }
+  __device__ __forceinline__ void issue_a_all(const uint16_t* Ak, unsigned stage_lds, int wave) const {
+#pragma unroll
+    for (int q = 0; q < C::A_PER_WAVE; ++q) issue_a_one(q, Ak, stage_lds, wave);
+  }
+  __device__ __forceinline__ void issue_b_direct(const uint16_t* Bk, unsigned stage_lds, int wave) const {
+#pragma unroll
+    for (int q = 0; q < C::B_PER_WAVE; ++q) {
+      const int ib = wave + C::NWAVES * q;
+      gload_lds16(__builtin_amdgcn_readfirstlane(stage_lds + C::A_BYTES + ib * 1024), b_src[q], Bk);
+    }
+  }
+
   // memory -> registers, zero where k >= K (ragged tail) or outside M / N.
   __device__ __forceinline__ void load_regs(const uint16_t* Ak, const uint16_t* Bk, int k0, int K,
-                                            u32x4 (&ra)[C::A_PER_WAVE], u32x4 (&rb)[C::B_PER_WAVE]) const {
+                                            u32x4 (&ra)[NA], u32x4 (&rb)[C::B_PER_WAVE]) const {
 #pragma unroll
     for (int q = 0; q < C::A_PER_WAVE; ++q) {
       u32x4 v = {0u, 0u, 0u, 0u};
@@ -141,7 +167,7 @@ struct TileLoader {
     }
   }
   __device__ __forceinline__ void store_regs(char* stage, int wave, int lane,
-                                             const u32x4 (&ra)[C::A_PER_WAVE], const u32x4 (&rb)[C::B_PER_WAVE]) const {
+                                             const u32x4 (&ra)[NA], const u32x4 (&rb)[C::B_PER_WAVE]) const {
 #pragma unroll
     for (int q = 0; q < C::A_PER_WAVE; ++q) {
       const int ia = wave + C::NWAVES * q;
@@ -364,43 +390,178 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   // tile instead (into a buffer nobody reads any more): the number of transfers in flight is
   // then the same in every iteration and the vmcnt waits are constants.
   const int last = nkt - 1;
-  if constexpr (C::DIRECT) {
+  if constexpr (C::ABYPASS) {
+    // A straight from memory into MFMA operand registers: lane l of a wave needs, for row block
+    // i and k16-step kk, the 16 bytes at row 32 i + (l & 31), k = 16 kk + 8 (l >> 5): one
+    // global_load_dwordx4. Two register sets alternate per tile (the loop is unrolled by two so
+    // both are addressed statically); the loads of tile kt+1 are issued at the top of tile kt.
+    // These loads are ordinary loads the compiler tracks; the B transfers are not, so every
+    // hand-over waits for vmcnt 0, which by then only covers loads issued a tile earlier.
+    const unsigned lds0 = (unsigned)(size_t)smem;
+    unsigned a_goff[C::TM];
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) {
+      int m = m0 + wave_m * C::WTM + 32 * i + (lane & 31);
+      if (m >= p.M) m = p.M - 1;
+      a_goff[i] = ((unsigned)m * (unsigned)p.lda + 8u * (lane >> 5)) * 2u;
+    }
+    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * C::BK; };
+    auto tile_b = [&](int t) { return Bk + (long)(t < last ? t : last) * b_step; };
+    auto load_a = [&](u32x4 (&dst)[C::TM][4], const uint16_t* base) {
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) dst[i][kk] = *(const u32x4*)((const char*)base + a_goff[i] + kk * 32);
+    };
+    auto read_b = [&](const char* stage, int kk, int set) {
+#pragma unroll
+      for (int t = 0; t < C::TN; ++t) {
+        const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + 4 * C::B_ROW_BYTES));
+        const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        bfr[set][t] = __builtin_bit_cast(bf16x8, v);
+      }
+    };
+    auto mfma_a = [&](const u32x4 (&as)[C::TM][4], int kk, int set) {
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int t = 0; t < C::TN; ++t)
+          acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][t], __builtin_bit_cast(bf16x8, as[i][kk]), acc[i][t], 0, 0, 0);
+    };
+    auto hint_b = [&]() {
+#pragma unroll
+      for (int x = 0; x < (2 * C::TN < C::TM * C::TN ? 2 * C::TN : C::TM * C::TN); ++x) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+    };
+    // one non-final tile t computed from register set `cur`, while `nxt` receives tile t+1
+    auto half = [&](const u32x4 (&cur)[C::TM][4], u32x4 (&nxt)[C::TM][4], int t) {
+      const char* sb = smem + (t & 1) * C::STAGE_BYTES;
+      load_a(nxt, tile_a(t + 1));
+      __builtin_amdgcn_sched_barrier(0);   // keep the loads up here: a whole tile of MFMAs covers their latency
+#pragma unroll
+      for (int kk = 0; kk < 3; ++kk) {
+        read_b(sb, kk + 1, (kk + 1) & 1);
+        mfma_a(cur, kk, kk & 1);
+        hint_b();
+      }
+      wait_vmcnt<0>();      // B tile t+1 (issued one tile ago) and A tile t+1 have arrived
+      barrier_lds();        // ... for every wave; every wave is done reading B tile t
+      ld.issue_b_direct(tile_b(t + 2), lds0 + (t & 1) * C::STAGE_BYTES, wave);
+      read_b(smem + ((t + 1) & 1) * C::STAGE_BYTES, 0, 0);
+      mfma_a(cur, 3, 1);
+      hint_b();
+    };
+    auto final_tile = [&](const u32x4 (&cur)[C::TM][4], int t) {
+      const char* sb = smem + (t & 1) * C::STAGE_BYTES;
+#pragma unroll
+      for (int kk = 0; kk < 3; ++kk) {
+        read_b(sb, kk + 1, (kk + 1) & 1);
+        mfma_a(cur, kk, kk & 1);
+        hint_b();
+      }
+      mfma_a(cur, 3, 1);
+    };
+    if (nkt > 0) {
+      u32x4 A0[C::TM][4], A1[C::TM][4];
+      ld.issue_b_direct(tile_b(0), lds0, wave);
+      load_a(A0, tile_a(0));
+      wait_vmcnt<0>();
+      barrier_lds();
+      ld.issue_b_direct(tile_b(1), lds0 + C::STAGE_BYTES, wave);
+      read_b(smem, 0, 0);
+      int kt = 0;
+      for (; kt + 2 <= last; kt += 2) {
+        half(A0, A1, kt);
+        half(A1, A0, kt + 1);
+      }
+      if (kt < last) {
+        half(A0, A1, kt);
+        final_tile(A1, last);
+      } else {
+        final_tile(A0, last);
+      }
+      wait_vmcnt<0>();
+    }
+  } else if constexpr (C::DIRECT) {
     constexpr int D = C::STAGES - 1;                            // tiles in flight ahead of the one computed
     constexpr int PER_TILE = C::A_PER_WAVE + C::B_PER_WAVE;   // transfers per wave per tile
     static_assert((D - 1) * PER_TILE < 64, "vmcnt range");
     const unsigned lds0 = (unsigned)(size_t)smem;
     auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * C::BK; };
     auto tile_b = [&](int t) { return Bk + (long)(t < last ? t : last) * b_step; };
+    // A wave issues in order: a burst of transfers right after the barrier would hold back the
+    // MFMAs behind it for as long as the load unit takes to accept the burst (the four waves of a
+    // CU share one, at about 16 cycles per transfer). So the transfers of a tile are dealt out
+    // one at a time between the fragment reads of two k16-steps: its A part during the last step
+    // of the tile whose buffer it takes over, its B part during the first step of the next tile.
+    // which: 1 = A part, 2 = B part; the fragment reads and the transfers keep this order, the
+    // MFMAs are spread between them by the scheduling hint.
+    auto read_frags_issue = [&](const char* stage, int kk, int set, int which, const uint16_t* src, unsigned dst_lds) {
+      constexpr int NR = C::TM + C::TN;                   // fragment reads (A: one b128, B: a tr pair)
+      const int nx = which == 1 ? C::A_PER_WAVE : C::B_PER_WAVE;
+#pragma unroll
+      for (int x = 0; x < (NR > 8 ? NR : 8); ++x) {
+        if (x < C::TM) af[set][x] = *(const bf16x8*)(stage + a_off[kk] + x * 32 * 128);
+        else if (x < NR) {
+          const int t = x - C::TM;
+          const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + 4 * C::B_ROW_BYTES));
+          const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          bfr[set][t] = __builtin_bit_cast(bf16x8, v);
+        }
+        if (x < nx) {
+          if (which == 1) ld.issue_a_one(x, src, dst_lds, wave);
+          else ld.issue_b_one(x, src, dst_lds, wave);
+        }
+      }
+    };
+    static_assert(C::A_PER_WAVE <= 8 && C::B_PER_WAVE <= 8, "transfers of one part fit between the reads of one step");
     if (nkt > 0) {
 #pragma unroll
       for (int s = 0; s < D; ++s) ld.issue_direct(tile_a(s), tile_b(s), lds0 + s * C::STAGE_BYTES, wave);
       wait_vmcnt<(D - 1) * PER_TILE>();      // tile 0 has landed, D-1 younger tiles may still fly
-      barrier_lds();  
-      ld.issue_direct(tile_a(D), tile_b(D), lds0 + D * C::STAGE_BYTES, wave);
+      barrier_lds();
+      // tile D: A part now, B part during the first step of tile 0 (as in the steady state)
+      ld.issue_a_all(tile_a(D), lds0 + D * C::STAGE_BYTES, wave);
       read_frags(smem, 0, 0);
       int stage = 0;
       for (int kt = 0; kt < last; ++kt) {
         const char* cur = smem + stage * C::STAGE_BYTES;
         int nstage = stage + 1;
         if (nstage == C::STAGES) nstage = 0;
+        int pstage = stage + D;               // buffer of tile kt + D (freed by the barrier before this tile)
+        if (pstage >= C::STAGES) pstage -= C::STAGES;
+        read_frags_issue(cur, 1, 1, 2, tile_b(kt + D), lds0 + pstage * C::STAGE_BYTES);
+        mfma_step(0);
+        interleave_hint();
 #pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
+        for (int kk = 1; kk < 3; ++kk) {
           read_frags(cur, kk + 1, (kk + 1) & 1);
           mfma_step(kk & 1);
           interleave_hint();
         }
         wait_vmcnt<(D - 1) * PER_TILE>();    // tile kt+1 has landed
         barrier_lds();                       // ... for every wave, and every wave is done reading tile kt
-        ld.issue_direct(tile_a(kt + 1 + D), tile_b(kt + 1 + D), lds0 + stage * C::STAGE_BYTES, wave);
-        read_frags(smem + nstage * C::STAGE_BYTES, 0, 0);
+        read_frags_issue(smem + nstage * C::STAGE_BYTES, 0, 0, 1, tile_a(kt + 1 + D), lds0 + stage * C::STAGE_BYTES);
         mfma_step(1);                        // k16-step 3 of tile kt covers the latencies above
         interleave_hint();
         stage = nstage;
       }
       {
         const char* cur = smem + stage * C::STAGE_BYTES;
+        int pstage = stage + D;
+        if (pstage >= C::STAGES) pstage -= C::STAGES;
+        // (the B part that completes the redundant A part issued at the last hand-over)
+        read_frags_issue(cur, 1, 1, 2, tile_b(last + D), lds0 + pstage * C::STAGE_BYTES);
+        mfma_step(0);
+        interleave_hint();
 #pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
+        for (int kk = 1; kk < 3; ++kk) {
           read_frags(cur, kk + 1, (kk + 1) & 1);
           mfma_step(kk & 1);
           interleave_hint();
@@ -413,7 +574,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     // Register-staged double buffering: the global loads of tile kt+1 fly during tile kt and are
     // written to the other LDS buffer before the hand-over barrier.
     static_assert(C::DIRECT || C::STAGES == 2, "register staging uses two buffers");
-    u32x4 ra[C::A_PER_WAVE], rb[C::B_PER_WAVE];
+    u32x4 ra[TileLoader<C>::NA], rb[C::B_PER_WAVE];
     const int kbase = kt_begin * C::BK;
     auto load_tile = [&](int t) {
       const int tt = t < last ? t : last;
@@ -509,7 +670,7 @@ template <class C>
 static LdsKernelInfo make_info() {
   LdsKernelInfo k;
   k.bm = C::BM; k.bn = C::BN; k.bk = C::BK; k.waves_m = C::WM; k.waves_n = C::WN;
-  k.stages = C::STAGES; k.direct_to_lds = C::DIRECT ? 1 : 0;
+  k.stages = C::STAGES; k.direct_to_lds = C::DIRECT ? 1 : 0; k.a_bypass_lds = C::ABYPASS ? 1 : 0;
   k.threads = C::THREADS; k.lds_bytes = C::LDS_BYTES;
   k.func = (const void*)tf_gemm_lds_kernel<C>;
   k.launch = launch_lds<C>;
@@ -528,12 +689,15 @@ using K64x64_d3   = LdsCfg< 64,  64, 2, 2, 3, true>;
 using K32x128_d3  = LdsCfg< 32, 128, 1, 4, 3, true>;
 using K32x64_d4   = LdsCfg< 32,  64, 1, 2, 4, true>;
 using K32x128_r2  = LdsCfg< 32, 128, 1, 4, 2, false>;
+using K256x256_ab = LdsCfg<256, 256, 4, 1, 2, true, true>;
+using K128x256_ab = LdsCfg<128, 256, 4, 1, 2, true, true>;
 
 static LdsKernelInfo g_table[] = {
     make_info<K256x256_d2>(), make_info<K256x128_d2>(), make_info<K128x256_d2>(),
     make_info<K128x128_d2>(), make_info<K128x128_d3>(), make_info<K128x128_r2>(),
     make_info<K64x64_r2>(),   make_info<K64x64_d3>(),   make_info<K32x128_d3>(),
-    make_info<K32x64_d4>(),   make_info<K32x128_r2>(),
+    make_info<K32x64_d4>(),   make_info<K32x128_r2>(),  make_info<K256x256_ab>(),
+    make_info<K128x256_ab>(),
 };
 
 int lds_kernel_count() { return (int)(sizeof(g_table) / sizeof(g_table[0])); }
