@@ -137,6 +137,11 @@ typedef struct {
   double robust_spread;         /* reject timings whose (median - min) / median exceeds this (0.10) */
   int32_t patience;             /* finish after this many consecutive rounds without an accept (4)  */
   int32_t max_rounds;           /* hard cap on optimisation rounds (8)                               */
+  int64_t cold_bytes;           /* Profile stage of tf_tune: > 0 = time every candidate on rotating copies of
+                                   A, B and Y that together exceed this many bytes, so that no launch finds
+                                   its operands in cache (as a kernel profiler that flushes caches between
+                                   replays would measure; default 512 MiB, twice the memory-side cache);
+                                   0 = time back-to-back launches on the caller's buffers               */
 } tf_theta;
 
 typedef struct tf_problem tf_problem;   /* opaque; created and destroyed by the library */

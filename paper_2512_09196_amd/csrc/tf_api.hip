@@ -265,6 +265,15 @@ __global__ void compare_kernel(const T* y, const T* ref, size_t rows, int n, lon
   if (!ok) atomicAdd(bad, 1u);
 }
 
+// Copies of the operands that the Profile stage cycles through, one set per launch, so that a
+// launch never finds A, B or Y in L2 or the memory-side cache. One allocation holds them all.
+struct Rotation {
+  void* base = nullptr;
+  std::vector<const void*> A, B;
+  std::vector<void*> Y;
+  mutable size_t next = 0;
+};
+
 struct TuneCtx {
   tf_problem* p;
   const void *A, *B, *bias;
@@ -277,10 +286,12 @@ struct TuneCtx {
   void* yref;        // baseline output
   unsigned* bad;     // device counter
   size_t ybytes;
+  const Rotation* rot;   // cold-cache operand copies for the Profile stage, or null
 };
 
 tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, const void* bias, void* Y, void* ws,
-                       size_t ws_bytes, hipStream_t stream, int warmup, int iters, int lpi, tf_report* out);
+                       size_t ws_bytes, hipStream_t stream, int warmup, int iters, int lpi, tf_report* out,
+                       const Rotation* rot = nullptr);
 
 tf_status tune_profile(void* user, int32_t id, tf_report* out) {
   TuneCtx* c = (TuneCtx*)user;
@@ -308,7 +319,7 @@ tf_status tune_profile(void* user, int32_t id, tf_report* out) {
     TF_HIP(hipStreamSynchronize(c->stream));
     ok = bad == 0;
   }
-  st = profile_impl(p, id, c->A, c->B, c->bias, c->Y, c->ws, c->ws_bytes, c->stream, 3, 5, 0, out);
+  st = profile_impl(p, id, c->A, c->B, c->bias, c->Y, c->ws, c->ws_bytes, c->stream, 3, 5, 0, out, c->rot);
   if (st != TF_OK) { out->status = st; return TF_OK; }
   out->parity_ok = ok;
   return TF_OK;
@@ -321,7 +332,8 @@ double median(std::vector<double> v) {
 }
 
 tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, const void* bias, void* Y, void* ws,
-                       size_t ws_bytes, hipStream_t stream, int warmup, int iters, int lpi, tf_report* out) {
+                       size_t ws_bytes, hipStream_t stream, int warmup, int iters, int lpi, tf_report* out,
+                       const Rotation* rot) {
   memset(out, 0, sizeof(*out));
   out->variant_id = id;
   if (warmup < 0 || iters < 1 || lpi < 0) return fail(TF_E_INVALID, "warmup >= 0, iters >= 1, launches_per_iter >= 0");
@@ -332,7 +344,13 @@ tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, cons
   auto timed = [&](int launches, double* us) -> tf_status {
     if (hipEventRecord(e0, stream) != hipSuccess) return fail(TF_E_LAUNCH, "hipEventRecord failed");
     for (int l = 0; l < launches; ++l) {
-      tf_status s2 = do_launch(p, id, A, B, bias, Y, ws, ws_bytes, stream);
+      tf_status s2;
+      if (rot && !rot->A.empty()) {
+        const size_t i = rot->next++ % rot->A.size();
+        s2 = do_launch(p, id, rot->A[i], rot->B[i], bias, rot->Y[i], ws, ws_bytes, stream);
+      } else {
+        s2 = do_launch(p, id, A, B, bias, Y, ws, ws_bytes, stream);
+      }
       if (s2 != TF_OK) return s2;
     }
     if (hipEventRecord(e1, stream) != hipSuccess) return fail(TF_E_LAUNCH, "hipEventRecord failed");
@@ -589,8 +607,34 @@ extern "C" tf_status tf_tune(tf_problem* p, const void* A, const void* B, const 
     if (hipMalloc(&c.yref, std::max<size_t>(c.ybytes, 16)) != hipSuccess) return fail(TF_E_NOMEM, "cannot allocate the reference output");
     if (hipMalloc((void**)&c.bad, 256) != hipSuccess) { (void)hipFree(c.yref); return fail(TF_E_NOMEM, "cannot allocate the mismatch counter"); }
   }
-  st = tf::run_loop(&p->desc, &p->hw, p->family.data(), (int32_t)p->family.size(), &th, tune_profile, &c, best_variant,
-                    best, round_log, log_cap, n_log);
+  Rotation rot;
+  if (th.cold_bytes > 0 && p->desc.M > 0 && p->desc.N > 0 && p->desc.K > 0) {
+    const tf_problem_desc& d = p->desc;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t araw = ((size_t)(d.M - 1) * d.lda + d.K) * 2, braw = ((size_t)(d.K - 1) * d.ldb + d.N) * 2;
+    const size_t abytes = up(araw), bbytes = up(braw);
+    const size_t ybytes = up(c.ybytes), set = abytes + bbytes + ybytes;
+    const size_t n = std::min<size_t>((size_t)th.cold_bytes / set + 2, 256);
+    if (hipMalloc(&rot.base, n * set) != hipSuccess) {
+      (void)hipGetLastError();
+      if (c.yref) (void)hipFree(c.yref);
+      if (c.bad) (void)hipFree(c.bad);
+      return fail(TF_E_NOMEM, "cannot allocate %zu bytes of rotating operand copies (theta.cold_bytes)", n * set);
+    }
+    for (size_t i = 0; i < n && st == TF_OK; ++i) {
+      char* a = (char*)rot.base + i * set;
+      if (hipMemcpyAsync(a, A, araw, hipMemcpyDeviceToDevice, c.stream) != hipSuccess ||
+          hipMemcpyAsync(a + abytes, B, braw, hipMemcpyDeviceToDevice, c.stream) != hipSuccess)
+        st = fail(TF_E_LAUNCH, "copying the operands failed");
+      rot.A.push_back(a); rot.B.push_back(a + abytes); rot.Y.push_back(a + abytes + bbytes);
+    }
+    if (st == TF_OK && hipStreamSynchronize(c.stream) != hipSuccess) st = fail(TF_E_LAUNCH, "copying the operands failed");
+    c.rot = &rot;
+  }
+  if (st == TF_OK)
+    st = tf::run_loop(&p->desc, &p->hw, p->family.data(), (int32_t)p->family.size(), &th, tune_profile, &c, best_variant,
+                      best, round_log, log_cap, n_log);
+  if (rot.base) (void)hipFree(rot.base);
   if (c.yref) (void)hipFree(c.yref);
   if (c.bad) (void)hipFree(c.bad);
   if (st == TF_OK && *best_variant >= 0) {

@@ -46,7 +46,7 @@ struct LdsCfg {
   static constexpr int B_PIECES = B_ROW_BYTES / 64;         // 64-byte pieces per B row
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 blocks");
   static_assert(A_INSTR % NWAVES == 0 && B_INSTR % NWAVES == 0, "tile loads must divide over the waves");
-  static_assert(BN == 64 || BN == 128 || BN == 256, "B row must be 128, 256 or 512 bytes");
+  static_assert(BN == 32 || BN == 64 || BN == 128 || BN == 256, "B row must be 64, 128, 256 or 512 bytes");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 };
 
@@ -486,6 +486,76 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       }
       wait_vmcnt<0>();
     }
+  } else if constexpr (C::DIRECT && C::TM * C::TN <= 2) {
+    // Small wave tiles (skinny problems): a k16-step has only one or two MFMAs, far too few to
+    // cover an LDS read, so the step-by-step pipeline above would stall four times per tile.
+    // Here all fragments of a tile are read at once, into one of two register sets, while the
+    // MFMAs of the previous tile run; one wait + barrier per tile. Unrolled by two so that both
+    // sets are addressed statically.
+    constexpr int D = C::STAGES - 1;
+    constexpr int PER_TILE = C::A_PER_WAVE + C::B_PER_WAVE;
+    static_assert((D - 1) * PER_TILE < 64, "vmcnt range");
+    const unsigned lds0 = (unsigned)(size_t)smem;
+    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * C::BK; };
+    auto tile_b = [&](int t) { return Bk + (long)(t < last ? t : last) * b_step; };
+    bf16x8 fa[2][4][C::TM], fb[2][4][C::TN];
+    auto read_tile = [&](const char* stage, bf16x8 (&a)[4][C::TM], bf16x8 (&b)[4][C::TN]) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i) a[kk][i] = *(const bf16x8*)(stage + a_off[kk] + i * 32 * 128);
+#pragma unroll
+        for (int t = 0; t < C::TN; ++t) {
+          const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + 4 * C::B_ROW_BYTES));
+          const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          b[kk][t] = __builtin_bit_cast(bf16x8, v);
+        }
+      }
+    };
+    auto mfma_tile = [&](const bf16x8 (&a)[4][C::TM], const bf16x8 (&b)[4][C::TN]) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+          for (int t = 0; t < C::TN; ++t)
+            acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[kk][t], a[kk][i], acc[i][t], 0, 0, 0);
+    };
+    if (nkt > 0) {
+#pragma unroll
+      for (int s = 0; s < D; ++s) ld.issue_direct(tile_a(s), tile_b(s), lds0 + s * C::STAGE_BYTES, wave);
+      wait_vmcnt<(D - 1) * PER_TILE>();
+      barrier_lds();
+      ld.issue_direct(tile_a(D), tile_b(D), lds0 + D * C::STAGE_BYTES, wave);
+      read_tile(smem, fa[0], fb[0]);
+      int stage = 0;
+      // one non-final tile t: its fragments are in (ca, cb); (na, nb) receive tile t+1
+      auto step = [&](int t, const bf16x8 (&ca)[4][C::TM], const bf16x8 (&cb)[4][C::TN],
+                      bf16x8 (&na)[4][C::TM], bf16x8 (&nb)[4][C::TN]) {
+        int nstage = stage + 1;
+        if (nstage == C::STAGES) nstage = 0;
+        wait_vmcnt<(D - 1) * PER_TILE>();    // tile t+1 has landed
+        barrier_lds();                       // ... for every wave; every wave holds tile t in registers
+        ld.issue_direct(tile_a(t + 1 + D), tile_b(t + 1 + D), lds0 + stage * C::STAGE_BYTES, wave);
+        read_tile(smem + nstage * C::STAGE_BYTES, na, nb);
+        mfma_tile(ca, cb);
+        stage = nstage;
+      };
+      int kt = 0;
+      for (; kt + 2 <= last; kt += 2) {
+        step(kt, fa[0], fb[0], fa[1], fb[1]);
+        step(kt + 1, fa[1], fb[1], fa[0], fb[0]);
+      }
+      if (kt < last) {
+        step(kt, fa[0], fb[0], fa[1], fb[1]);
+        mfma_tile(fa[1], fb[1]);
+      } else {
+        mfma_tile(fa[0], fb[0]);
+      }
+      wait_vmcnt<0>();
+    }
   } else if constexpr (C::DIRECT) {
     constexpr int D = C::STAGES - 1;                            // tiles in flight ahead of the one computed
     constexpr int PER_TILE = C::A_PER_WAVE + C::B_PER_WAVE;   // transfers per wave per tile
@@ -689,6 +759,14 @@ using K64x64_d3   = LdsCfg< 64,  64, 2, 2, 3, true>;
 using K32x128_d3  = LdsCfg< 32, 128, 1, 4, 3, true>;
 using K32x64_d4   = LdsCfg< 32,  64, 1, 2, 4, true>;
 using K32x128_r2  = LdsCfg< 32, 128, 1, 4, 2, false>;
+using K32x128_d6  = LdsCfg< 32, 128, 1, 4, 6, true>;
+using K32x64_d8   = LdsCfg< 32,  64, 1, 2, 8, true>;
+using K32x256_d4  = LdsCfg< 32, 256, 1, 4, 4, true>;
+using K32x32_d4   = LdsCfg< 32,  32, 1, 1, 4, true>;
+using K32x32_d8   = LdsCfg< 32,  32, 1, 1, 8, true>;
+using K128x128_w8a = LdsCfg<128, 128, 2, 4, 3, true>;   // eight waves: two per SIMD cover each other's overheads
+using K128x128_w8b = LdsCfg<128, 128, 4, 2, 3, true>;
+using K128x128_w8c = LdsCfg<128, 128, 2, 4, 4, true>;
 using K256x256_ab = LdsCfg<256, 256, 4, 1, 2, true, true>;
 using K128x256_ab = LdsCfg<128, 256, 4, 1, 2, true, true>;
 
@@ -697,7 +775,9 @@ static LdsKernelInfo g_table[] = {
     make_info<K128x128_d2>(), make_info<K128x128_d3>(), make_info<K128x128_r2>(),
     make_info<K64x64_r2>(),   make_info<K64x64_d3>(),   make_info<K32x128_d3>(),
     make_info<K32x64_d4>(),   make_info<K32x128_r2>(),  make_info<K256x256_ab>(),
-    make_info<K128x256_ab>(),
+    make_info<K128x256_ab>(),  make_info<K32x128_d6>(),  make_info<K32x64_d8>(),
+    make_info<K32x256_d4>(),  make_info<K32x32_d4>(),   make_info<K32x32_d8>(),
+    make_info<K128x128_w8a>(), make_info<K128x128_w8b>(), make_info<K128x128_w8c>(),
 };
 
 int lds_kernel_count() { return (int)(sizeof(g_table) / sizeof(g_table[0])); }

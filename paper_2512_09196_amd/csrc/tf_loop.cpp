@@ -19,6 +19,7 @@ extern "C" void tf_theta_default(tf_theta* t) {
   t->robust_spread = 0.10;
   t->patience = 4;   // Case Study 3 runs four consecutive non-improving rounds before it stops
   t->max_rounds = 8;
+  t->cold_bytes = 512ll << 20;
 }
 
 extern "C" void tf_hw_nominal(tf_hw* h) {

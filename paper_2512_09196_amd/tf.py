@@ -68,7 +68,8 @@ class Hw(_Struct):
 
 class Theta(_Struct):
     _fields_ = [("first_accept_speedup", C.c_double), ("later_accept_gain", C.c_double),
-                ("robust_spread", C.c_double), ("patience", C.c_int32), ("max_rounds", C.c_int32)]
+                ("robust_spread", C.c_double), ("patience", C.c_int32), ("max_rounds", C.c_int32),
+                ("cold_bytes", C.c_int64)]
 
 
 PARITY_FN = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_int32)

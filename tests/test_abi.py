@@ -39,7 +39,7 @@ int main(void) {
   printf("%zu %zu %zu %zu %zu\n", sizeof(tf_problem_desc), sizeof(tf_variant_desc), sizeof(tf_report), sizeof(tf_hw), sizeof(tf_theta));
   printf("%zu %zu %zu %zu\n", offsetof(tf_variant_desc, workspace_bytes), offsetof(tf_variant_desc, name),
          offsetof(tf_report, t_min_us), offsetof(tf_report, parity_ok));
-  printf("%zu %zu %zu\n", offsetof(tf_report, occupancy_pct), offsetof(tf_hw, clock_mhz), offsetof(tf_theta, patience));
+  printf("%zu %zu %zu\n", offsetof(tf_report, occupancy_pct), offsetof(tf_hw, clock_mhz), offsetof(tf_theta, cold_bytes));
   return 0;
 }'''
     with tempfile.TemporaryDirectory() as d:
@@ -53,7 +53,7 @@ int main(void) {
             ctypes.sizeof(tf.Hw), ctypes.sizeof(tf.Theta),
             tf.VariantDesc.workspace_bytes.offset, tf.VariantDesc.name.offset,
             tf.Report.t_min_us.offset, tf.Report.parity_ok.offset,
-            tf.Report.occupancy_pct.offset, tf.Hw.clock_mhz.offset, tf.Theta.patience.offset]
+            tf.Report.occupancy_pct.offset, tf.Hw.clock_mhz.offset, tf.Theta.cold_bytes.offset]
     assert got == want
 
 

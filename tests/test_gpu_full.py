@@ -101,7 +101,9 @@ def test_tune_on_gpu_c1_and_c2():
                 assert best != 0, "no variant beat the naive kernel"
                 assert rep.parity_ok == 1 and rep.status == 0
                 assert log[0].t_med_us / rep.t_med_us >= 1.05
-                assert rep.t_med_us <= min(r.t_med_us for r in log if r.status == 0 and r.parity_ok) * 1.0001
+                # the arbiter keeps the incumbent unless a candidate is at least 1.02x faster (Algorithm 1's
+                # acceptance threshold after the first round), so the result may trail the log's minimum by that much
+                assert rep.t_med_us <= min(r.t_med_us for r in log if r.status == 0 and r.parity_ok) * 1.02
                 # Y holds the selected kernel's output
                 got = Y.float()[r_t, c_t].double().cpu().numpy()
                 assert np.all(np.abs(got - y) <= gu.strict_bound(y, z, s, w.K))
