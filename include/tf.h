@@ -86,6 +86,8 @@ typedef struct {
   int32_t kind;            /* tf_kind */
   int32_t bm, bn, bk;      /* macro tile */
   int32_t waves_m, waves_n;/* wave grid inside the work-group (64-lane waves) */
+  int32_t waves_k;         /* wave groups along k: each takes 1/waves_k of every K step of the same tile, the groups
+                              add their accumulators through LDS before the epilogue (1 = none) */
   int32_t stages;          /* LDS buffers in the ring */
   int32_t split_k;         /* K slices, summed in fp32 in slice order (1 = no split) */
   int32_t fused_reduce;    /* split_k > 1: 1 = the last slice to arrive reduces inside the GEMM kernel (one launch,
@@ -245,6 +247,9 @@ tf_status tf_tune(tf_problem* p, const void* A, const void* B, const void* bias,
 
 const char* tf_last_error(void);
 const char* tf_version(void);
+/* sizeof of tf_problem_desc, tf_variant_desc, tf_report, tf_hw, tf_theta as this library was built, in that
+ * order (host pointer out): a binding checks them against its own mirrors before it calls anything else. */
+void tf_struct_sizes(int32_t out[5]);
 
 #ifdef __cplusplus
 }

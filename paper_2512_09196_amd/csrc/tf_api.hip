@@ -71,7 +71,7 @@ void build_family(tf_problem* p) {
   {
     tf_variant_desc v;
     memset(&v, 0, sizeof(v));
-    v.kind = TF_KIND_NAIVE; v.bm = 4; v.bn = 64; v.bk = 1; v.waves_m = 4; v.waves_n = 1; v.stages = 0;
+    v.kind = TF_KIND_NAIVE; v.bm = 4; v.bn = 64; v.bk = 1; v.waves_m = 4; v.waves_n = 1; v.waves_k = 1; v.stages = 0;
     v.split_k = 1; v.threads = 256; v.group_m = 1;
     v.grid = (int32_t)(cdivl(d.N, 64) * cdivl(d.M, 4));
     snprintf(v.name, sizeof(v.name), "naive_1elem_per_thread");
@@ -80,7 +80,7 @@ void build_family(tf_problem* p) {
   if (d.M > 0 && d.N > 0) {
     tf_variant_desc v;
     memset(&v, 0, sizeof(v));
-    v.kind = TF_KIND_MFMA_DIRECT; v.bm = 32; v.bn = 32; v.bk = 16; v.waves_m = 1; v.waves_n = 1;
+    v.kind = TF_KIND_MFMA_DIRECT; v.bm = 32; v.bn = 32; v.bk = 16; v.waves_m = 1; v.waves_n = 1; v.waves_k = 1;
     v.split_k = 1; v.threads = 64; v.group_m = 1;
     v.grid = (int32_t)(cdivl(d.N, 32) * cdivl(d.M, 32));
     snprintf(v.name, sizeof(v.name), "mfma32_direct_1wave");
@@ -113,7 +113,7 @@ void build_family(tf_problem* p) {
         if (s == 1 && fused == 0) continue;
         tf_variant_desc v;
         memset(&v, 0, sizeof(v));
-        v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n;
+        v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n; v.waves_k = k.waves_k;
         v.stages = k.stages; v.split_k = s; v.fused_reduce = (s > 1) ? fused : 0;
         v.direct_to_lds = k.direct_to_lds; v.a_bypass_lds = k.a_bypass_lds; v.xcd_swizzle = 1;
         v.group_m = (int32_t)std::min<long>(tm, 8);
@@ -123,8 +123,10 @@ void build_family(tf_problem* p) {
         im.lds_index = i; im.ktiles_per_split = (int)per; im.tiles_m = (int)tm; im.tiles_n = (int)tn;
         im.counter_bytes = s > 1 ? (size_t)((tm * tn * 4 + 255) / 256 * 256) : 0;
         v.workspace_bytes = s > 1 ? (int64_t)(im.counter_bytes + (size_t)s * d.M * d.N * 4) : 0;
-        snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d_s%d_%s_sk%d%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n,
-                 k.stages, k.a_bypass_lds ? "areg" : (k.direct_to_lds ? "direct" : "regs"), s,
+        char wk[8] = "";
+        if (k.waves_k > 1) snprintf(wk, sizeof(wk), "x%d", k.waves_k);
+        snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d%s_s%d_%s_sk%d%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n,
+                 wk, k.stages, k.a_bypass_lds ? "areg" : (k.direct_to_lds ? "direct" : "regs"), s,
                  s > 1 ? (fused ? "f" : "r") : "");
         add_variant(p, v, im);
       }
@@ -423,6 +425,11 @@ std::vector<std::string> split_csv(const std::string& line) {
 // =================================================================== exported functions
 extern "C" const char* tf_last_error(void) { return g_err; }
 extern "C" const char* tf_version(void) { return "tf-gfx950 0.1"; }
+extern "C" void tf_struct_sizes(int32_t out[5]) {
+  if (!out) return;
+  out[0] = (int32_t)sizeof(tf_problem_desc); out[1] = (int32_t)sizeof(tf_variant_desc);
+  out[2] = (int32_t)sizeof(tf_report); out[3] = (int32_t)sizeof(tf_hw); out[4] = (int32_t)sizeof(tf_theta);
+}
 
 extern "C" tf_status tf_hw_query(int32_t device, tf_hw* out) {
   if (!out) return fail(TF_E_INVALID, "null out");

@@ -22,15 +22,21 @@
 
 namespace tf {
 
-template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool DIRECT_, bool ABYPASS_ = false>
+template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool DIRECT_, bool ABYPASS_ = false, int WK_ = 1>
 struct LdsCfg {
   static constexpr int BM = BM_, BN = BN_, BK = 64, WM = WM_, WN = WN_, STAGES = STAGES_;
+  // WK: wave groups along k. With WK = 2 a second set of WM x WN waves works on the same
+  // BM x BN tile but takes the other half of every 64-wide K step; the two sets add their
+  // accumulators through LDS after the main loop. Eight waves then keep the LDS busier than
+  // four can (a wave issues one LDS instruction every twenty-odd cycles) without the extra
+  // fragment reads that a finer split of the tile along m or n costs.
+  static constexpr int WK = WK_, KS = 4 / WK_;             // k16-steps per wave per K step
   static constexpr bool DIRECT = DIRECT_;
   // ABYPASS: the A operand never enters LDS. Each wave loads its own A fragments from memory
   // straight into registers (WN must be 1, so no two waves need the same A rows) and only B is
   // staged. This halves the LDS write traffic, which is what bounds the two-operand scheme.
   static constexpr bool ABYPASS = ABYPASS_;
-  static constexpr int NWAVES = WM * WN, THREADS = NWAVES * 64;
+  static constexpr int NWAVES = WM * WN * WK, THREADS = NWAVES * 64;
   static constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
   static constexpr int TM = WTM / 32, TN = WTN / 32;       // 32x32 MFMA blocks per wave
   static constexpr int A_BYTES = ABYPASS ? 0 : BM * BK * 2, B_BYTES = BK * BN * 2;
@@ -48,6 +54,9 @@ struct LdsCfg {
   static_assert(A_INSTR % NWAVES == 0 && B_INSTR % NWAVES == 0, "tile loads must divide over the waves");
   static_assert(BN == 32 || BN == 64 || BN == 128 || BN == 256, "B row must be 64, 128, 256 or 512 bytes");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
+  static_assert(WK == 1 || (WK == 2 && TM % 2 == 0 && DIRECT && !ABYPASS), "k groups: two, each keeps half of the row blocks");
+  static_assert(WK == 1 || LDS_BYTES >= NWAVES * (TM / 2) * TN * 4096, "the accumulator exchange reuses the tile buffers");
+  static constexpr int TM_OUT = TM / WK;                   // row blocks a wave writes out
 };
 
 // Slot permutation of the 64-byte pieces of B row k (see header).
@@ -214,7 +223,7 @@ template <class C, bool FULL, bool THROUGH>
 __device__ __forceinline__ void store_partial(const f32x16 (&acc)[C::TM][C::TN], float* wsk, const GemmParams& p,
                                               int wm0, int wn0) {
 #pragma unroll
-  for (int i = 0; i < C::TM; ++i) {
+  for (int i = 0; i < C::TM_OUT; ++i) {
     const int m = wm0 + 32 * i;
 #pragma unroll
     for (int t = 0; t < C::TN; ++t)
@@ -236,7 +245,7 @@ template <class C, bool FULL>
 __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0) {
   const size_t slice = (size_t)p.M * p.N;
 #pragma unroll
-  for (int i = 0; i < C::TM; ++i) {
+  for (int i = 0; i < C::TM_OUT; ++i) {
     const int m = wm0 + 32 * i;
 #pragma unroll
     for (int t = 0; t < C::TN; ++t)
@@ -277,7 +286,7 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[C::TM][C::TN], cons
       const float b0 = __builtin_bit_cast(float, braw[0] << 16), b1 = __builtin_bit_cast(float, braw[0] & 0xffff0000u);
       const float b2 = __builtin_bit_cast(float, braw[1] << 16), b3 = __builtin_bit_cast(float, braw[1] & 0xffff0000u);
 #pragma unroll
-      for (int i = 0; i < C::TM; ++i) {
+      for (int i = 0; i < C::TM_OUT; ++i) {
         const int m = wm0 + 32 * i;
         if (FULL || (n_ok && m < p.M)) {
           const float z0 = acc[i][t][4 * q] + b0, z1 = acc[i][t][4 * q + 1] + b1;
@@ -301,7 +310,8 @@ template <class C>
 __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave / C::WN, wave_n = wave % C::WN;
+  const int wave_k = wave / (C::WM * C::WN), wave_mn = wave % (C::WM * C::WN);
+  const int wave_m = wave_mn / C::WN, wave_n = wave_mn % C::WN;
 
   const TileCoord tc = map_tile(p, blockIdx.x);
   const int m0 = tc.tm * C::BM, n0 = tc.tn * C::BN;
@@ -318,7 +328,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     const int g = lane >> 5;
     const int sw = (r >> 1) & 7;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) a_off[kk] = r * 128 + (((2 * kk + g) ^ sw) << 4);
+    for (int kk = 0; kk < 4; ++kk) a_off[kk] = r * 128 + ((((2 * (wave_k * C::KS + kk) + g) & 7) ^ sw) << 4);   // kk < KS used
   }
   int b_off[C::TN];
   {
@@ -329,7 +339,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     for (int t = 0; t < C::TN; ++t) {
       const int j = (wave_n * C::WTN) / 32 + t;
       const int piece = j ^ b_swz<C::B_PIECES>(krow);
-      b_off[t] = C::A_BYTES + krow * C::B_ROW_BYTES + piece * 64 + within;
+      b_off[t] = C::A_BYTES + (krow + wave_k * C::KS * 16) * C::B_ROW_BYTES + piece * 64 + within;
     }
   }
 
@@ -486,7 +496,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       }
       wait_vmcnt<0>();
     }
-  } else if constexpr (C::DIRECT && C::TM * C::TN <= 2) {
+  } else if constexpr (C::DIRECT && C::TM * C::TN * C::KS <= 8) {
     // Small wave tiles (skinny problems): a k16-step has only one or two MFMAs, far too few to
     // cover an LDS read, so the step-by-step pipeline above would stall four times per tile.
     // Here all fragments of a tile are read at once, into one of two register sets, while the
@@ -498,10 +508,10 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     const unsigned lds0 = (unsigned)(size_t)smem;
     auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * C::BK; };
     auto tile_b = [&](int t) { return Bk + (long)(t < last ? t : last) * b_step; };
-    bf16x8 fa[2][4][C::TM], fb[2][4][C::TN];
-    auto read_tile = [&](const char* stage, bf16x8 (&a)[4][C::TM], bf16x8 (&b)[4][C::TN]) {
+    bf16x8 fa[2][C::KS][C::TM], fb[2][C::KS][C::TN];
+    auto read_tile = [&](const char* stage, bf16x8 (&a)[C::KS][C::TM], bf16x8 (&b)[C::KS][C::TN]) {
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
+      for (int kk = 0; kk < C::KS; ++kk) {
 #pragma unroll
         for (int i = 0; i < C::TM; ++i) a[kk][i] = *(const bf16x8*)(stage + a_off[kk] + i * 32 * 128);
 #pragma unroll
@@ -514,9 +524,9 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
         }
       }
     };
-    auto mfma_tile = [&](const bf16x8 (&a)[4][C::TM], const bf16x8 (&b)[4][C::TN]) {
+    auto mfma_tile = [&](const bf16x8 (&a)[C::KS][C::TM], const bf16x8 (&b)[C::KS][C::TN]) {
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
+      for (int kk = 0; kk < C::KS; ++kk)
 #pragma unroll
         for (int i = 0; i < C::TM; ++i)
 #pragma unroll
@@ -532,8 +542,8 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       read_tile(smem, fa[0], fb[0]);
       int stage = 0;
       // one non-final tile t: its fragments are in (ca, cb); (na, nb) receive tile t+1
-      auto step = [&](int t, const bf16x8 (&ca)[4][C::TM], const bf16x8 (&cb)[4][C::TN],
-                      bf16x8 (&na)[4][C::TM], bf16x8 (&nb)[4][C::TN]) {
+      auto step = [&](int t, const bf16x8 (&ca)[C::KS][C::TM], const bf16x8 (&cb)[C::KS][C::TN],
+                      bf16x8 (&na)[C::KS][C::TM], bf16x8 (&nb)[C::KS][C::TN]) {
         int nstage = stage + 1;
         if (nstage == C::STAGES) nstage = 0;
         wait_vmcnt<(D - 1) * PER_TILE>();    // tile t+1 has landed
@@ -690,7 +700,42 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   // A lane therefore owns runs of four consecutive n, which pack into one 8-byte (bf16) or
   // 16-byte (fp32) store without any cross-lane exchange.
   const int lane_m = lane & 31, lane_g = lane >> 5;
-  const int wm0 = m0 + wave_m * C::WTM + lane_m;              // + 32 i
+  if constexpr (C::WK == 2) {
+    // The two k groups hold partial sums of the same wave tile. Group 0 keeps its first TM/2 row
+    // blocks and hands the others to its partner wave of group 1, which does the reverse;
+    // afterwards acc[0 .. TM/2) of every wave holds complete sums of the rows it writes out.
+    constexpr int H = C::TM / 2;
+    wait_vmcnt<0>();
+    barrier_lds();                          // nobody reads tiles any more, no transfer is in flight
+    char* mine = smem + wave * (H * C::TN * 4096);
+    const char* theirs = smem + ((wave_mn + (1 - wave_k) * C::WM * C::WN)) * (H * C::TN * 4096);
+#pragma unroll
+    for (int i = 0; i < H; ++i)
+#pragma unroll
+      for (int t = 0; t < C::TN; ++t) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = wave_k ? acc[i][t][4 * q + e] : acc[i + H][t][4 * q + e];
+          *(f32x4*)(mine + (((i * C::TN + t) * 4 + q) * 64 + lane) * 16) = v;
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][t][r] = wave_k ? acc[i + H][t][r] : acc[i][t][r];
+      }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < H; ++i)
+#pragma unroll
+      for (int t = 0; t < C::TN; ++t)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 v = *(const f32x4*)(theirs + (((i * C::TN + t) * 4 + q) * 64 + lane) * 16);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][t][4 * q + e] += v[e];
+        }
+  }
+  const int wm0 = m0 + wave_m * C::WTM + lane_m + (C::WK == 2 ? wave_k * 32 * (C::TM / 2) : 0);   // + 32 i
   const int wn0 = n0 + wave_n * C::WTN + 4 * lane_g;          // + 32 t + 8 q
   const bool full = (m0 + C::BM <= p.M) && (n0 + C::BN <= p.N);
 
@@ -739,7 +784,7 @@ static void launch_lds(const GemmParams& p, dim3 grid, hipStream_t stream) {
 template <class C>
 static LdsKernelInfo make_info() {
   LdsKernelInfo k;
-  k.bm = C::BM; k.bn = C::BN; k.bk = C::BK; k.waves_m = C::WM; k.waves_n = C::WN;
+  k.bm = C::BM; k.bn = C::BN; k.bk = C::BK; k.waves_m = C::WM; k.waves_n = C::WN; k.waves_k = C::WK;
   k.stages = C::STAGES; k.direct_to_lds = C::DIRECT ? 1 : 0; k.a_bypass_lds = C::ABYPASS ? 1 : 0;
   k.threads = C::THREADS; k.lds_bytes = C::LDS_BYTES;
   k.func = (const void*)tf_gemm_lds_kernel<C>;
@@ -769,6 +814,8 @@ using K128x128_w8b = LdsCfg<128, 128, 4, 2, 3, true>;
 using K128x128_w8c = LdsCfg<128, 128, 2, 4, 4, true>;
 using K256x256_ab = LdsCfg<256, 256, 4, 1, 2, true, true>;
 using K128x256_ab = LdsCfg<128, 256, 4, 1, 2, true, true>;
+using K128x128_k2a = LdsCfg<128, 128, 2, 2, 3, true, false, 2>;   // two k groups of 2x2 waves
+using K128x128_k2b = LdsCfg<128, 128, 2, 2, 4, true, false, 2>;
 
 static LdsKernelInfo g_table[] = {
     make_info<K256x256_d2>(), make_info<K256x128_d2>(), make_info<K128x256_d2>(),
@@ -778,6 +825,7 @@ static LdsKernelInfo g_table[] = {
     make_info<K128x256_ab>(),  make_info<K32x128_d6>(),  make_info<K32x64_d8>(),
     make_info<K32x256_d4>(),  make_info<K32x32_d4>(),   make_info<K32x32_d8>(),
     make_info<K128x128_w8a>(), make_info<K128x128_w8b>(), make_info<K128x128_w8c>(),
+    make_info<K128x128_k2a>(), make_info<K128x128_k2b>(),
 };
 
 int lds_kernel_count() { return (int)(sizeof(g_table) / sizeof(g_table[0])); }

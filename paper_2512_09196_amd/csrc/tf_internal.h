@@ -28,7 +28,7 @@ struct GemmParams {
 
 // One compiled kernel of the LDS-staged MFMA family.
 struct LdsKernelInfo {
-  int bm, bn, bk, waves_m, waves_n, stages, direct_to_lds, a_bypass_lds;
+  int bm, bn, bk, waves_m, waves_n, waves_k, stages, direct_to_lds, a_bypass_lds;
   int threads, lds_bytes;
   const void* func;       // kernel symbol, for hipFuncGetAttributes / occupancy queries
   void (*launch)(const GemmParams&, dim3 grid, hipStream_t);

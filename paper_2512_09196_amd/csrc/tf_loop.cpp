@@ -89,7 +89,7 @@ extern "C" int32_t tf_resident_wgs(const tf_hw* hw, const tf_variant_desc* v) {
   int wps = hw->vgprs_per_simd_lane / regs;
   if (wps < 1) wps = 1;
   if (wps > hw->max_waves_per_simd) wps = hw->max_waves_per_simd;
-  const int wg_waves = v->waves_m * v->waves_n;
+  const int wg_waves = v->waves_m * v->waves_n * (v->waves_k > 1 ? v->waves_k : 1);
   int by_regs = wps * hw->simds_per_cu / wg_waves;
   if (by_regs < 1) by_regs = 1;
   int by_lds = v->lds_bytes > 0 ? hw->lds_bytes_per_cu / v->lds_bytes : 8;
@@ -114,12 +114,15 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   const long slots = (long)hw->cus * resident;
   const long rounds = cdiv(v->grid, slots);
   const long ktiles = cdiv(cdiv(pr->K, 64), v->split_k);
-  const int wg_waves = v->waves_m * v->waves_n;
+  const int mn_waves = v->waves_m * v->waves_n, wg_waves = mn_waves * (v->waves_k > 1 ? v->waves_k : 1);
   // cycles one CU spends on one K tile of one work-group
   const double mfma = v->bm * (double)v->bn / 32.0;              // 128 bm bn flop at 4096 flop/clk
   const double stage_bytes = (v->bm + v->bn) * 128.0;
   const double lds_w = stage_bytes / 64.0;                       // measured LDS write rate, B/clk
-  const double lds_r = wg_waves * ((v->bm / v->waves_m) + (v->bn / v->waves_n)) * 128.0 / 224.0;
+  // fragment reads: every wave of the m x n grid reads its rows of A and columns of B (k groups share
+  // them out); measured rate in B/clk, higher once eight waves keep the LDS queue full
+  const double lds_rate = wg_waves * resident >= 8 ? 200.0 : 130.0;
+  const double lds_r = mn_waves * ((v->bm / v->waves_m) + (v->bn / v->waves_n)) * 128.0 / lds_rate;
   const double ta = stage_bytes / 64.0;                          // global -> CU, B/clk
   double ktile = fmax(mfma, fmax(lds_w + lds_r, ta));
   if (!v->direct_to_lds) ktile *= 1.10;                          // VALU/VGPR traffic of register staging

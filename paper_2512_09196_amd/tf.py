@@ -38,7 +38,7 @@ class ProblemDesc(_Struct):
 
 class VariantDesc(_Struct):
     _fields_ = [("id", C.c_int32), ("kind", C.c_int32), ("bm", C.c_int32), ("bn", C.c_int32), ("bk", C.c_int32),
-                ("waves_m", C.c_int32), ("waves_n", C.c_int32), ("stages", C.c_int32), ("split_k", C.c_int32), ("fused_reduce", C.c_int32),
+                ("waves_m", C.c_int32), ("waves_n", C.c_int32), ("waves_k", C.c_int32), ("stages", C.c_int32), ("split_k", C.c_int32), ("fused_reduce", C.c_int32),
                 ("direct_to_lds", C.c_int32), ("a_bypass_lds", C.c_int32), ("xcd_swizzle", C.c_int32), ("group_m", C.c_int32),
                 ("threads", C.c_int32), ("lds_bytes", C.c_int32), ("grid", C.c_int32),
                 ("workspace_bytes", C.c_int64), ("name", C.c_char * 64)]
@@ -105,6 +105,7 @@ SIGNATURES = {
                             C.c_int32, _P(C.c_int32)]),
     "tf_last_error": (C.c_char_p, []),
     "tf_version": (C.c_char_p, []),
+    "tf_struct_sizes": (None, [_P(C.c_int32)]),
 }
 
 _lib = None
@@ -129,6 +130,12 @@ def lib():
             f = getattr(l, name)
             f.restype = res
             f.argtypes = args
+        built = (C.c_int32 * 5)()
+        l.tf_struct_sizes(built)
+        mine = [C.sizeof(t) for t in (ProblemDesc, VariantDesc, Report, Hw, Theta)]
+        if list(built) != mine:
+            raise RuntimeError("%s was built from another include/tf.h (struct sizes %s, this binding has %s): "
+                               "rebuild it with `python -m paper_2512_09196_amd.build`" % (LIB_PATH, list(built), mine))
         _lib = l
     return _lib
 

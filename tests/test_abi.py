@@ -67,7 +67,7 @@ def test_enumerate_without_gpu_lists_valid_variants_only():
     lds = [v for v in vs if v.kind == tf.TF_KIND_MFMA_LDS]
     assert any(v.bm == 256 and v.bn == 256 for v in lds) and any(v.bm == 128 and v.bn == 128 for v in lds)
     for v in lds:
-        assert v.lds_bytes <= 160 * 1024 and v.threads == 64 * v.waves_m * v.waves_n
+        assert v.lds_bytes <= 160 * 1024 and v.threads == 64 * v.waves_m * v.waves_n * v.waves_k
         tiles = -(-2048 // v.bm) * -(-2048 // v.bn)
         assert v.grid == tiles * v.split_k
         if v.split_k > 1:

@@ -30,6 +30,7 @@ def c_variant(d, i):
     v.id = i
     v.bk = 64
     v.waves_m = v.waves_n = 2
+    v.waves_k = 1
     v.threads = 256
     return v
 
