@@ -54,7 +54,9 @@ typedef enum {
 typedef enum {
   TF_KIND_NAIVE = 0,        /* one thread per output element, scalar FMA loop: the baseline kernel K */
   TF_KIND_MFMA_DIRECT = 1,  /* one wave per 32x32 tile, MFMA operands loaded straight from memory     */
-  TF_KIND_MFMA_LDS = 2      /* LDS-staged, multi-buffered, swizzled MFMA tile kernel                  */
+  TF_KIND_MFMA_LDS = 2,     /* LDS-staged, multi-buffered, swizzled MFMA tile kernel                  */
+  TF_KIND_MFMA_STREAM = 3   /* skinny problems (M <= 32): B streamed once from memory into MFMA operand
+                               registers, no LDS staging; the waves of a work-group split K            */
 } tf_kind;
 
 /* Bottleneck classes produced by tf_refine_hint (Sec. 3.3 "Targeted-Refinement-Hint":

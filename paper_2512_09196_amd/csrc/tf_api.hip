@@ -31,7 +31,7 @@ tf_status fail(tf_status st, const char* fmt, ...) {
   } while (0)
 
 struct VariantImpl {
-  int lds_index;   // index into tf::lds_kernel_table(), -1 for the unstaged kernels
+  int lds_index;   // index into tf::lds_kernel_table() (tf::stream_kernel_table() for the streaming kind), -1 for the unstaged kernels
   int ktiles_per_split;
   int tiles_m, tiles_n;
   size_t counter_bytes;   // leading part of the workspace
@@ -132,6 +132,40 @@ void build_family(tf_problem* p) {
       }
     }
   }
+  // Streaming kernels for skinny problems: K in blocks of 32, each wave of a work-group at least one block.
+  if (d.M <= 32 && d.K % 32 == 0 && d.K >= 32) {
+    const tf::StreamKernelInfo* stab = tf::stream_kernel_table();
+    const long kblocks = d.K / 32;
+    for (int i = 0; i < tf::stream_kernel_count(); ++i) {
+      const tf::StreamKernelInfo& k = stab[i];
+      const long tn = cdivl(d.N, k.block_n);
+      if (k.block_n > 64 && k.block_n / 2 >= d.N) continue;   // block more than twice the problem
+      if (k.m_blocks != (d.M <= 16 ? 1 : 2)) continue;
+      if (k.lds_bytes > p->hw.lds_bytes_per_cu) continue;
+      static const int splits[] = {1, 2, 4, 8, 16, 32};
+      for (int s : splits) {
+        const long per = cdivl(kblocks, s);
+        if (s > 1 && (per < k.waves || per * (s - 1) >= kblocks || tn * s > 8L * cus)) continue;
+        for (int fused = 1; fused >= 0; --fused) {
+          if (s == 1 && fused == 0) continue;
+          tf_variant_desc v;
+          memset(&v, 0, sizeof(v));
+          v.kind = TF_KIND_MFMA_STREAM; v.bm = 16 * k.m_blocks; v.bn = k.block_n; v.bk = 32;
+          v.waves_m = 1; v.waves_n = 1; v.waves_k = k.waves; v.stages = k.depth; v.split_k = s;
+          v.fused_reduce = s > 1 ? fused : 0;
+          v.group_m = 1; v.threads = k.threads; v.lds_bytes = k.lds_bytes;
+          v.grid = (int32_t)(tn * s);
+          VariantImpl im;
+          im.lds_index = i; im.ktiles_per_split = (int)per; im.tiles_m = 1; im.tiles_n = (int)tn;
+          im.counter_bytes = s > 1 ? (size_t)((tn * 4 + 255) / 256 * 256) : 0;
+          v.workspace_bytes = s > 1 ? (int64_t)(im.counter_bytes + (size_t)s * d.M * d.N * 4) : 0;
+          snprintf(v.name, sizeof(v.name), "stream_%dx%dx32_k%d_d%d_sk%d%s", v.bm, k.block_n, k.waves, k.depth, s,
+                   s > 1 ? (fused ? "f" : "r") : "");
+          add_variant(p, v, im);
+        }
+      }
+    }
+  }
   // One counter area for the whole family, so that the partial sums of one variant never
   // land on the counters of another: [counters | partial sums].
   size_t maxc = 0;
@@ -151,7 +185,7 @@ tf_status check_ptrs(const tf_problem* p, const tf_variant_desc& v, const void* 
   if (d.M == 0 || d.N == 0) return TF_OK;
   if (!Y || !bias) return fail(TF_E_INVALID, "null Y or bias pointer");
   if (d.K > 0 && (!A || !B)) return fail(TF_E_INVALID, "null A or B pointer");
-  if (v.kind == TF_KIND_MFMA_LDS) {
+  if (v.kind == TF_KIND_MFMA_LDS || v.kind == TF_KIND_MFMA_STREAM) {
     if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)Y) & 15u || ((uintptr_t)bias & 7u))
       return fail(TF_E_UNSUPPORTED, "variant %s needs 16-byte aligned A, B, Y and 8-byte aligned bias", v.name);
   }
@@ -178,7 +212,6 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
     if (cdivl(d.M, 32) > 65535) return fail(TF_E_UNSUPPORTED, "mfma_direct variant: M too large for the grid");
     tf::launch_mfma_direct(g, stream);
   } else {
-    const tf::LdsKernelInfo& k = tf::lds_kernel_table()[im.lds_index];
     g.tiles_m = im.tiles_m; g.tiles_n = im.tiles_n; g.ktiles_per_split = im.ktiles_per_split;
     if (v.split_k > 1) {
       if (!ws) {
@@ -209,11 +242,15 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
       g.counters = (unsigned*)ws;
       g.ws = (float*)((char*)ws + im.counter_bytes);
     }
-    if (!p->attr_done[im.lds_index]) {
-      TF_HIP(hipFuncSetAttribute(k.func, hipFuncAttributeMaxDynamicSharedMemorySize, k.lds_bytes));
-      p->attr_done[im.lds_index] = 1;
+    const bool streaming = v.kind == TF_KIND_MFMA_STREAM;
+    const int slot = streaming ? tf::lds_kernel_count() + im.lds_index : im.lds_index;
+    const void* func = streaming ? tf::stream_kernel_table()[im.lds_index].func : tf::lds_kernel_table()[im.lds_index].func;
+    if (!p->attr_done[slot]) {
+      TF_HIP(hipFuncSetAttribute(func, hipFuncAttributeMaxDynamicSharedMemorySize, v.lds_bytes));
+      p->attr_done[slot] = 1;
     }
-    k.launch(g, dim3((unsigned)v.grid), stream);
+    if (streaming) tf::stream_kernel_table()[im.lds_index].launch(g, dim3((unsigned)v.grid), stream);
+    else tf::lds_kernel_table()[im.lds_index].launch(g, dim3((unsigned)v.grid), stream);
     if (v.split_k > 1 && !v.fused_reduce) tf::launch_splitk_reduce(g, stream);
   }
   TF_HIP(hipGetLastError());
@@ -227,6 +264,7 @@ void fill_static(tf_problem* p, int id, tf_report* r) {
   int dyn = 0;
   if (v.kind == TF_KIND_NAIVE) func = tf::naive_func();
   else if (v.kind == TF_KIND_MFMA_DIRECT) func = tf::mfma_direct_func();
+  else if (v.kind == TF_KIND_MFMA_STREAM) { func = tf::stream_kernel_table()[p->impl[id].lds_index].func; dyn = v.lds_bytes; }
   else { func = tf::lds_kernel_table()[p->impl[id].lds_index].func; dyn = v.lds_bytes; }
   hipFuncAttributes a;
   memset(&a, 0, sizeof(a));
@@ -470,7 +508,7 @@ extern "C" tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem**
   // host-side loop logic work without a GPU; launching does not)
   p->have_hw = tf_hw_query(desc->device, &p->hw) == TF_OK;
   if (!p->have_hw) { tf_hw_nominal(&p->hw); g_err[0] = 0; }
-  p->attr_done.assign(tf::lds_kernel_count(), 0);
+  p->attr_done.assign(tf::lds_kernel_count() + tf::stream_kernel_count(), 0);
   build_family(p);
   *out = p;
   return TF_OK;

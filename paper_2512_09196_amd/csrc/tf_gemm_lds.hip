@@ -40,7 +40,7 @@ struct LdsCfg {
   static constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
   static constexpr int TM = WTM / 32, TN = WTN / 32;       // 32x32 MFMA blocks per wave
   static constexpr int A_BYTES = ABYPASS ? 0 : BM * BK * 2, B_BYTES = BK * BN * 2;
-  static_assert(!ABYPASS || (WN == 1 && DIRECT && STAGES == 2), "A bypass: one wave column, direct B staging, two buffers");
+  static_assert(!ABYPASS || (WN == 1 && DIRECT && STAGES == 2 && WK_ == 1), "A bypass: one wave column, direct B staging, two buffers");
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
   static constexpr int A_INSTR = A_BYTES / 1024;           // wave-wide 1 KB transfers per tile
@@ -816,6 +816,8 @@ using K256x256_ab = LdsCfg<256, 256, 4, 1, 2, true, true>;
 using K128x256_ab = LdsCfg<128, 256, 4, 1, 2, true, true>;
 using K128x128_k2a = LdsCfg<128, 128, 2, 2, 3, true, false, 2>;   // two k groups of 2x2 waves
 using K128x128_k2b = LdsCfg<128, 128, 2, 2, 4, true, false, 2>;
+using K256x256_w8a = LdsCfg<256, 256, 2, 4, 2, true>;   // eight waves on the big tile: 128x64 or 64x128 per wave
+using K256x256_w8b = LdsCfg<256, 256, 4, 2, 2, true>;
 
 static LdsKernelInfo g_table[] = {
     make_info<K256x256_d2>(), make_info<K256x128_d2>(), make_info<K128x256_d2>(),
@@ -826,6 +828,7 @@ static LdsKernelInfo g_table[] = {
     make_info<K32x256_d4>(),  make_info<K32x32_d4>(),   make_info<K32x32_d8>(),
     make_info<K128x128_w8a>(), make_info<K128x128_w8b>(), make_info<K128x128_w8c>(),
     make_info<K128x128_k2a>(), make_info<K128x128_k2b>(),
+    make_info<K256x256_w8a>(), make_info<K256x256_w8b>(),
 };
 
 int lds_kernel_count() { return (int)(sizeof(g_table) / sizeof(g_table[0])); }

@@ -36,6 +36,18 @@ struct LdsKernelInfo {
 int lds_kernel_count();
 const LdsKernelInfo* lds_kernel_table();
 
+// One compiled kernel of the streaming family for skinny problems (B read once, no LDS staging).
+// GemmParams: tiles_n = column blocks of block_n, ktiles_per_split = K blocks of 32 per slice.
+struct StreamKernelInfo {
+  int m_blocks;           // 16-row blocks of A it covers: M <= 16 m_blocks
+  int waves, depth, threads, lds_bytes;   // depth: register sets per wave (depth - 1 K blocks in flight)
+  int block_n;            // columns per work-group (128 or 64)
+  const void* func;
+  void (*launch)(const GemmParams&, dim3 grid, hipStream_t);
+};
+int stream_kernel_count();
+const StreamKernelInfo* stream_kernel_table();
+
 void launch_naive(const GemmParams&, hipStream_t);
 void launch_mfma_direct(const GemmParams&, hipStream_t);
 const void* naive_func();

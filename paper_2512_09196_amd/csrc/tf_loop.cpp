@@ -83,6 +83,14 @@ extern "C" int32_t tf_refine_hint(const tf_report* prev, const tf_report* cand, 
 static inline long cdiv(long a, long b) { return (a + b - 1) / b; }
 
 extern "C" int32_t tf_resident_wgs(const tf_hw* hw, const tf_variant_desc* v) {
+  if (v->kind == TF_KIND_MFMA_STREAM) {
+    // about 128 registers per lane: four waves per SIMD; LDS only holds the final exchange
+    const int waves = v->waves_k > 0 ? v->waves_k : 1;
+    int r = 4 * hw->simds_per_cu / waves;
+    const int by_lds = v->lds_bytes > 0 ? hw->lds_bytes_per_cu / v->lds_bytes : 8;
+    if (by_lds < r) r = by_lds;
+    return r < 1 ? 1 : (r > 8 ? 8 : r);
+  }
   if (v->kind != TF_KIND_MFMA_LDS) return 8;
   const int acc_regs = (v->bm / v->waves_m) * (v->bn / v->waves_n) / 64;
   const int regs = acc_regs + 96;                      // fragments, staging, addresses
@@ -110,46 +118,82 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   const double hbm_us = bytes / (hw->hbm_gbs_peak * 1e3);
   if (v->kind == TF_KIND_NAIVE) return fmax(flops / (0.004 * hw->bf16_tflops_peak * 1e6), hbm_us) + 2.0;
   if (v->kind == TF_KIND_MFMA_DIRECT) return fmax(flops / (0.02 * hw->bf16_tflops_peak * 1e6), hbm_us) + 2.0;
+  if (v->kind == TF_KIND_MFMA_STREAM) {
+    // B is read once at the rate the chip sustains from HBM, if enough waves keep loads in flight
+    // (about 96 KB per CU; a wave keeps stages - 1 blocks of 8 KB outstanding)
+    const double waves = (double)v->grid * (v->waves_k > 0 ? v->waves_k : 1);
+    double feed = waves * (v->stages > 1 ? v->stages - 1 : 1) * 8192.0 / (98304.0 * hw->cus);
+    if (feed > 1.0) feed = 1.0;
+    const long kblocks = cdiv(cdiv(pr->K, 32), (long)v->split_k * (v->waves_k > 0 ? v->waves_k : 1));
+    const double startup = 1.0 + 4.0 / (double)(kblocks > 0 ? kblocks : 1);      // short runs never reach the steady state
+    // a CU draws at most about 37 GB/s from HBM (less in row pieces under 256 bytes): few work-groups cannot use the chip
+    const double active = v->grid < hw->cus ? (double)v->grid : (double)hw->cus;
+    const double cap_gbs = active * 37.0 * (v->bn >= 128 ? 1.0 : 0.65);
+    double rate = 0.72 * feed * hw->hbm_gbs_peak;
+    if (rate > cap_gbs) rate = cap_gbs;
+    double us = bytes / (rate * 1e3) + startup + 2.5;
+    // slices: the last work-group to arrive sums them after one more trip to memory, or a second launch does
+    if (v->split_k > 1) us += (v->fused_reduce ? 5.5 : 4.5) + 2.0 * v->split_k * 4.0 * pr->M * (double)pr->N / (hw->hbm_gbs_peak * 1e3);
+    return us;
+  }
   const int resident = tf_resident_wgs(hw, v);
   const long slots = (long)hw->cus * resident;
-  const long rounds = cdiv(v->grid, slots);
   const long ktiles = cdiv(cdiv(pr->K, 64), v->split_k);
   const int mn_waves = v->waves_m * v->waves_n, wg_waves = mn_waves * (v->waves_k > 1 ? v->waves_k : 1);
-  // cycles one CU spends on one K tile of one work-group
-  const double mfma = v->bm * (double)v->bn / 32.0;              // 128 bm bn flop at 4096 flop/clk
-  const double stage_bytes = (v->bm + v->bn) * 128.0;
-  const double lds_w = stage_bytes / 64.0;                       // measured LDS write rate, B/clk
-  // fragment reads: every wave of the m x n grid reads its rows of A and columns of B (k groups share
-  // them out); measured rate in B/clk, higher once eight waves keep the LDS queue full
-  const double lds_rate = wg_waves * resident >= 8 ? 200.0 : 130.0;
-  const double lds_r = mn_waves * ((v->bm / v->waves_m) + (v->bn / v->waves_n)) * 128.0 / lds_rate;
-  const double ta = stage_bytes / 64.0;                          // global -> CU, B/clk
-  double ktile = fmax(mfma, fmax(lds_w + lds_r, ta));
-  if (!v->direct_to_lds) ktile *= 1.10;                          // VALU/VGPR traffic of register staging
-  const double exposed = 400.0 / (resident * (v->stages - 1));   // barrier + staging latency not hidden
-  const double epi = v->bm * (double)v->bn / 4.0;                // 16 VALU ops per element, 64 lanes/clk
-  // split-K: every slice writes its fp32 partial tile (about 32 B/clk per CU). Fused, the last
-  // slice of a tile then reads all slices back alone with device-scope loads (about 16 B/clk),
-  // a serial tail; otherwise a second kernel streams the workspace once.
-  double splitk = 0.0, reduce_us = 0.0;
+  // Cycles one CU spends on one K tile (64 wide) of one work-group. The constants are fits to
+  // this family's measured times on MI355X (2048^3, 4096 x 11008 x 4096 and 1024^2 x 16384):
+  //  * the clock under MFMA load is about 1650 MHz, whatever the nominal figure says; all
+  //    cycle counts below are at that clock;
+  //  * an MFMA 32x32x16 issues every 36 cycles, not 32;
+  //  * tiles enter LDS at 140 B/ns per CU (85 B/clk) on either staging path, fragments leave it
+  //    at about 256 B/clk; reads and writes take turns;
+  //  * per K step a chain of barrier, transfer issue, first fragment reads and first MFMA is
+  //    exposed: about 800 cycles with two buffers, 250 with three or more, and a second wave per
+  //    SIMD hides 70 % of it; register staging adds 300, the A-bypass loads 400.
+  const double mfma = v->bm * (double)v->bn / 32.0 * (36.0 / 32.0);
+  const double stage_bytes = (v->a_bypass_lds ? v->bn : v->bm + v->bn) * 128.0;
+  const double lds_w = stage_bytes / 85.0;
+  long co_resident = cdiv(v->grid, hw->cus);       // work-groups really sharing a CU, not how many would fit
+  if (co_resident > resident) co_resident = resident;
+  const double cu_waves = (double)wg_waves * co_resident;
+  const double a_rows = v->a_bypass_lds ? 0.0 : (double)(v->bm / v->waves_m);
+  const double lds_r = mn_waves * (a_rows + (v->bn / v->waves_n)) * 128.0 / 256.0;
+  const double ta = (v->bm + v->bn) * 128.0 / 85.0;              // global -> CU
+  double chain = v->stages >= 3 ? 250.0 : 800.0;
+  if (cu_waves >= 8) chain *= v->waves_k > 1 ? 0.7 : 0.3;       // k groups: half the MFMAs per wave and step to hide it behind
+  if (!v->direct_to_lds) chain += 300.0;
+  if (v->a_bypass_lds) chain += 400.0;
+  const double ktile = fmax(fmax(mfma, lds_w + lds_r), ta) + chain;
+  // per tile: pipeline fill (first tiles from memory), then bias + GELU + pack at about 22 VALU
+  // issue slots per element, or the fp32 partial tile at 32 B/clk when a second kernel reduces
+  const double fill = 2500.0 / (double)co_resident;
+  double tile_end = v->bm * (double)v->bn * 22.0 / 64.0;
+  if (v->waves_k > 1) tile_end += v->bm * (double)v->bn * 4.0 * (1.0 / 85.0 + 1.0 / 256.0) / 2.0 * v->waves_k;   // accumulator exchange
+  double reduce_us = 0.0, fused_tail_us = 0.0;
+  const double mhz = hw->clock_mhz < 1650.0 ? hw->clock_mhz : 1650.0;
   if (v->split_k > 1) {
-    splitk = v->bm * (double)v->bn * 4.0 / 32.0;
-    if (v->fused_reduce) splitk += v->bm * (double)v->bn * 4.0 * v->split_k / 16.0;
-    else reduce_us = 2.5 + (v->split_k + 0.5) * 4.0 * pr->M * (double)pr->N / (0.5 * hw->hbm_gbs_peak * 1e3);
+    if (v->fused_reduce) {
+      // partial tiles go out and come back through device-scope scalar accesses at about
+      // 2 B/clk, and the last slice of a tile reads all of them alone
+      fused_tail_us = v->bm * (double)v->bn * 4.0 * (1.0 + v->split_k) / 2.0 / mhz;
+    } else {
+      tile_end = v->bm * (double)v->bn * 4.0 / 32.0;
+      reduce_us = 3.7 + (v->split_k + 0.5) * 4.0 * pr->M * (double)pr->N / (0.4 * hw->hbm_gbs_peak * 1e3);
+    }
   }
-  // a round gives every CU up to `resident` work-groups, which share its pipes; the last
-  // round may be thinner
-  double cycles = 0.0;
-  long left = v->grid;
-  for (long r = 0; r < rounds; ++r) {
-    const long now = left < slots ? left : slots;
-    const long per_cu = cdiv(now, hw->cus);
-    cycles += per_cu * (ktiles * ktile + epi + splitk) + ktiles * exposed + 2500.0;
-    left -= now;
-  }
-  double us = cycles / hw->clock_mhz;
+  // CUs take the next work-group as they finish one: the makespan is close to the average
+  // number of work-groups per slot, plus a ragged end
+  double rounds = (double)v->grid / (double)slots;
+  rounds = rounds <= 1.0 ? 1.0 : rounds + 0.25;
+  const double per_cu = rounds * (double)co_resident;            // work-groups one CU works through
+  const double us = per_cu * (ktiles * ktile + fill + tile_end) / mhz;
   const double ws_us = v->split_k > 1 ? 2.0 * v->split_k * 4.0 * pr->M * (double)pr->N / (hw->hbm_gbs_peak * 1e3) : 0.0;
-  return fmax(us, hbm_us + ws_us) + 2.0 + reduce_us;
+  // HBM floor: about three quarters of the peak rate when at least 32 KB per CU are in flight
+  // (prefetched tiles of all co-resident work-groups), in proportion below that
+  double inflight = (double)co_resident * (v->stages - 1) * stage_bytes / 32768.0;
+  if (inflight > 1.0) inflight = 1.0;
+  // launch, first tile from HBM and drain: about 4 us per launch
+  return fmax(us, (hbm_us + ws_us) / (0.75 * inflight)) + 4.0 + reduce_us + fused_tail_us;
 }
 
 // ------------------------------------------------------------------ Proposal

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libtf_gfx950.so")
 
 TF_OK, TF_E_INVALID, TF_E_UNSUPPORTED, TF_E_LAUNCH, TF_E_NOMEM, TF_E_RANGE, TF_E_PROFILER = 0, -1, -2, -3, -4, -5, -6
 TF_EPI_BIAS_GELU_ERF, TF_EPI_NONE_F32 = 0, 1
-TF_KIND_NAIVE, TF_KIND_MFMA_DIRECT, TF_KIND_MFMA_LDS = 0, 1, 2
+TF_KIND_NAIVE, TF_KIND_MFMA_DIRECT, TF_KIND_MFMA_LDS, TF_KIND_MFMA_STREAM = 0, 1, 2, 3
 TF_BN_UNKNOWN, TF_BN_UNDERFILLED, TF_BN_HBM, TF_BN_MFMA, TF_BN_LDS_CONFLICT, TF_BN_OCCUPANCY, TF_BN_LATENCY = range(7)
 TF_DEC_CONTINUE, TF_DEC_ACCEPT, TF_DEC_FINISH = 0, 1, 2
 BOTTLENECK_NAMES = ["unknown", "underfilled", "hbm", "mfma", "lds_conflict", "occupancy", "latency"]

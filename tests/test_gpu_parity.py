@@ -99,6 +99,25 @@ def test_skinny_decode_shape_small():
     assert any(n.startswith("lds_32x") for n in ran)
 
 
+@pytest.mark.parametrize("shape", [(16, 512, 2048), (7, 200, 96), (32, 1000, 4128), (17, 136, 32), (1, 8, 64),
+                                   (16, 2056, 1024)])
+def test_streaming_kernels_on_skinny_shapes(shape):
+    # M <= 32: B streamed once, waves split K; ragged column block, rows past M, K of one block only,
+    # uneven runs of K blocks per wave, one- and two-kernel reductions
+    M, N, K = shape
+    A, B, bias = wl.make_custom(M, N, K, seed=11 + N, a_dist=("normal", 1.0), b_dist=("normal", 0.05),
+                                bias_dist=("normal", 0.3))
+    ran = check_all_variants(M, N, K, A, B, bias, only=lambda v: v.kind == tf.TF_KIND_MFMA_STREAM)
+    assert N <= 64 or any(n.startswith("stream_%dx128x" % (16 if M <= 16 else 32)) for n in ran)
+    assert any(n.startswith("stream_%dx64x" % (16 if M <= 16 else 32)) for n in ran)
+    if K >= 2048:
+        assert any(n.endswith("r") for n in ran)
+    # strided operands
+    ran = check_all_variants(M, N, K, *wl.make_custom(M, N, K, seed=5 + K), lda=K + 8, ldb=N + 24, ldy=N + 8,
+                             only=lambda v: v.kind == tf.TF_KIND_MFMA_STREAM)
+    assert ran
+
+
 def test_leading_dimensions_and_padding_columns():
     M, N, K = 150, 200, 320
     A, B, bias = wl.make_custom(M, N, K, seed=17)
