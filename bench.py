@@ -26,6 +26,17 @@ HBM_PEAK_GBS = 8000.0
 MALL_BYTES = 256 << 20
 
 
+# rocprofv3 --pmc readings (KiB per dispatch) of the C2 kernels the loop ends on: (FETCH_SIZE, WRITE_SIZE).
+# A 256 MiB device copy reads FETCH_SIZE 131086 and WRITE_SIZE 262144 KiB, hence the scale factors.
+FETCH_SCALE, WRITE_SCALE = 262144.0 / 131086.4, 1.0
+HBM_TRAFFIC_KIB = {
+    ("C2", "lds_128x128x64_w2x4_s3_direct_sk1"): (24675.1, 8192.0),
+    ("C2", "lds_128x128x64_w4x2_s3_direct_sk1"): (24678.4, 8192.0),
+    ("C2", "lds_128x128x64_w2x4_s4_direct_sk1"): (24672.0, 8192.0),
+    ("C2", "lds_128x128x64_w2x2_s3_direct_sk1"): (24712.0, 8192.0),
+}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -55,6 +66,8 @@ def main():
     ap.add_argument("--variant", default=None, help="time this variant instead of the loop's choice")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-tune", action="store_true", help="skip the loop (needs --variant)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="launch a plain device copy of known size instead (reference reading for the HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)." % args.gpus)
@@ -69,6 +82,18 @@ def main():
         log("bench.py: no GPU visible; there is no CPU path.")
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        # 256 MiB read + 256 MiB written per launch, from buffers that rotate past the memory-side cache
+        n = 128 << 20
+        src = [torch.ones(n, dtype=torch.int16, device="cuda") for _ in range(4)]
+        dst = [torch.empty(n, dtype=torch.int16, device="cuda") for _ in range(4)]
+        torch.cuda.synchronize()
+        for i in range(args.warmup + args.steps):
+            dst[i % 4].copy_(src[i % 4])
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "launches": args.warmup + args.steps,
+                          "bytes_read_per_launch": 2 * n, "bytes_written_per_launch": 2 * n}))
+        return
     w = wl.WORKLOADS[args.workload]
     log("generating %s (M=%d N=%d K=%d, seed %d)" % (w.name, w.M, w.N, w.K, w.seed))
     A, B, bias = wl.make_inputs(w)
@@ -146,7 +171,11 @@ def main():
         roof = {"bound": "mfma", "achieved": w.flops / (kern_us * 1e-6) * 1e-12, "peak": BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    # HBM traffic per launch from the TCC counters (two rocprofv3 --pmc runs of this file with --variant),
+    # scaled by what the same counters read for a plain 256 MiB copy; None for kernels not measured
+    t = HBM_TRAFFIC_KIB.get((w.name, names[vid]))
+    roof["traffic"] = None if t is None else (t[0] * FETCH_SCALE + t[1] * WRITE_SCALE) * 1024.0
+    roof["traffic_unit"] = "bytes per launch"
     roof["kernel"] = names[vid]
     roof["avg_launch_us"] = kern_us
 
