@@ -42,7 +42,11 @@ struct LdsCfg {
   static constexpr int A_BYTES = ABYPASS ? 0 : BM * BK * 2, B_BYTES = BK * BN * 2;
   static_assert(!ABYPASS || (WN == 1 && DIRECT && STAGES == 2 && WK_ == 1), "A bypass: one wave column, direct B staging, two buffers");
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-  static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+  static constexpr int RING_BYTES = STAGES * STAGE_BYTES;
+  // behind the ring: this tile's BN bias values, fetched at kernel start so that the epilogue
+  // does not begin with a trip to memory
+  static constexpr int BIAS_OFF = RING_BYTES, BIAS_BYTES = 512;
+  static constexpr int LDS_BYTES = RING_BYTES + BIAS_BYTES;
   static constexpr int A_INSTR = A_BYTES / 1024;           // wave-wide 1 KB transfers per tile
   static constexpr int B_INSTR = B_BYTES / 1024;
   static constexpr int A_PER_WAVE = A_INSTR / NWAVES, B_PER_WAVE = B_INSTR / NWAVES;
@@ -55,7 +59,7 @@ struct LdsCfg {
   static_assert(BN == 32 || BN == 64 || BN == 128 || BN == 256, "B row must be 64, 128, 256 or 512 bytes");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
   static_assert(WK == 1 || (WK == 2 && TM % 2 == 0 && DIRECT && !ABYPASS), "k groups: two, each keeps half of the row blocks");
-  static_assert(WK == 1 || LDS_BYTES >= NWAVES * (TM / 2) * TN * 4096, "the accumulator exchange reuses the tile buffers");
+  static_assert(WK == 1 || RING_BYTES >= NWAVES * (TM / 2) * TN * 4096, "the accumulator exchange reuses the tile buffers");
   static constexpr int TM_OUT = TM / WK;                   // row blocks a wave writes out
 };
 
@@ -124,6 +128,16 @@ struct TileLoader {
     const unsigned long long sb = (unsigned long long)lo | ((unsigned long long)hi << 32);
     const void* sbase = (const void*)sb;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+  }
+  // same, four bytes per lane (lane l lands at M0 + 4 l; lanes switched off transfer nothing)
+  __device__ __forceinline__ static void gload_lds4(unsigned lds_addr, unsigned voff, const void* base) {
+    const unsigned long long b = (unsigned long long)base;
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
+    const unsigned long long sb = (unsigned long long)lo | ((unsigned long long)hi << 32);
+    const void* sbase = (const void*)sb;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
                  :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
   }
   __device__ __forceinline__ void issue_direct(const uint16_t* Ak, const uint16_t* Bk, unsigned stage_lds, int wave) const {
@@ -273,16 +287,17 @@ __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const 
   }
 }
 
+// bias_lds: this lane's first four bias values in LDS (columns wn0 .. wn0 + 3 of the tile's copy)
 template <class C, bool FULL, int EPI>
-__device__ __forceinline__ void epilogue(const f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0) {
+__device__ __forceinline__ void epilogue(const f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0,
+                                         const char* bias_lds) {
 #pragma unroll
   for (int t = 0; t < C::TN; ++t) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int n = wn0 + 32 * t + 8 * q;
       const bool n_ok = FULL || n < p.N;
-      u32x2 braw = {0u, 0u};
-      if (n_ok) braw = *(const u32x2*)(p.bias + n);
+      const u32x2 braw = *(const u32x2*)(bias_lds + (32 * t + 8 * q) * 2);   // (columns past N hold values nobody stores)
       const float b0 = __builtin_bit_cast(float, braw[0] << 16), b1 = __builtin_bit_cast(float, braw[0] & 0xffff0000u);
       const float b2 = __builtin_bit_cast(float, braw[1] << 16), b3 = __builtin_bit_cast(float, braw[1] & 0xffff0000u);
 #pragma unroll
@@ -353,6 +368,25 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
 
   TileLoader<C> ld;
   ld.init(p, m0, n0, wave, lane);
+  // bias of this tile -> LDS (two values per lane), ahead of the first tile: it is in place when
+  // the first hand-over barrier has been passed
+  if (wave == 0) {
+#pragma unroll
+    for (int r = 0; r < (C::BN + 127) / 128; ++r) {
+      const int c = 128 * r + 2 * lane;                 // column inside the tile
+      if (c < C::BN) {
+        const int n = n0 + c;
+        if constexpr (C::DIRECT) {
+          TileLoader<C>::gload_lds4(__builtin_amdgcn_readfirstlane((unsigned)(size_t)smem + C::BIAS_OFF + 256 * r),
+                                    n < p.N ? (unsigned)n * 2u : 0u, p.bias);
+        } else {
+          unsigned v = 0u;
+          if (n < p.N) v = *(const unsigned*)(p.bias + n);
+          *(unsigned*)(smem + C::BIAS_OFF + c * 2) = v;
+        }
+      }
+    }
+  }
   const uint16_t* Ak = p.A + (long)kt_begin * C::BK;
   const uint16_t* Bk = p.B + (long)kt_begin * C::BK * p.ldb;
   const long b_step = (long)C::BK * p.ldb;
@@ -767,12 +801,17 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   }
 
   // ---- epilogue: + bias, GELU, round to bf16 (or raw fp32 pre-activation)
+  if (nkt <= 0) {            // no K step, so no hand-over has published the bias copy yet
+    wait_vmcnt<0>();
+    __syncthreads();
+  }
+  const char* bias_lds = smem + C::BIAS_OFF + (wave_n * C::WTN + 4 * lane_g) * 2;
   if (p.epi == TF_EPI_NONE_F32) {
-    if (full) epilogue<C, true, TF_EPI_NONE_F32>(acc, p, wm0, wn0);
-    else epilogue<C, false, TF_EPI_NONE_F32>(acc, p, wm0, wn0);
+    if (full) epilogue<C, true, TF_EPI_NONE_F32>(acc, p, wm0, wn0, bias_lds);
+    else epilogue<C, false, TF_EPI_NONE_F32>(acc, p, wm0, wn0, bias_lds);
   } else {
-    if (full) epilogue<C, true, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0);
-    else epilogue<C, false, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0);
+    if (full) epilogue<C, true, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0, bias_lds);
+    else epilogue<C, false, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0, bias_lds);
   }
 }
 
