@@ -92,7 +92,9 @@ typedef struct {
                               add their accumulators through LDS before the epilogue (1 = none) */
   int32_t stages;          /* LDS buffers in the ring */
   int32_t split_k;         /* K slices, summed in fp32 in slice order (1 = no split) */
-  int32_t fused_reduce;    /* split_k > 1: 1 = the last slice to arrive reduces inside the GEMM kernel (one launch,
+  int32_t fused_reduce;    /* split_k > 1: 2 = as 1, with the partial tiles exchanged through the L2 of the one XCD
+                              that all slices of a tile run on (offered when the tile count is a multiple of 8);
+                              1 = the last slice to arrive reduces inside the GEMM kernel (one launch,
                               arrival counters); 0 = a second kernel sums the slices and applies the epilogue */
   int32_t direct_to_lds;   /* 1: global_load_lds staging; 0: via registers (allows a ragged K tail) */
   int32_t a_bypass_lds;    /* 1: A fragments are loaded from memory straight into MFMA operand registers, only B is

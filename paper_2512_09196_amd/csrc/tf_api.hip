@@ -109,7 +109,11 @@ void build_family(tf_problem* p) {
       if (s > 1 && (ktiles / s < 4 || tm * tn >= 2L * cus)) continue;
       const long per = cdivl(ktiles, s);
       if (s > 1 && per * (s - 1) >= ktiles) continue;      // would leave an empty slice
-      for (int fused = 1; fused >= 0; --fused) {
+      // slices summed by the last one to arrive (2: partial tiles exchanged through the L2 of the XCD
+      // all slices of a tile run on, possible when the tile order gives every XCD whole tiles;
+      // 1: through memory, wherever they run) or by a second kernel (0)
+      const int fused_mode = (tm * tn) % 8 == 0 ? 2 : 1;
+      for (int fused = fused_mode; fused >= 0; fused -= fused_mode) {
         if (s == 1 && fused == 0) continue;
         tf_variant_desc v;
         memset(&v, 0, sizeof(v));
@@ -121,13 +125,13 @@ void build_family(tf_problem* p) {
         v.grid = (int32_t)(tm * tn * s);
         VariantImpl im;
         im.lds_index = i; im.ktiles_per_split = (int)per; im.tiles_m = (int)tm; im.tiles_n = (int)tn;
-        im.counter_bytes = s > 1 ? (size_t)((tm * tn * 4 + 255) / 256 * 256) : 0;
+        im.counter_bytes = s > 1 ? (size_t)((tm * tn * 8 + 255) / 256 * 256) : 0;
         v.workspace_bytes = s > 1 ? (int64_t)(im.counter_bytes + (size_t)s * d.M * d.N * 4) : 0;
         char wk[8] = "";
         if (k.waves_k > 1) snprintf(wk, sizeof(wk), "x%d", k.waves_k);
         snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d%s_s%d_%s_sk%d%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n,
                  wk, k.stages, k.a_bypass_lds ? "areg" : (k.direct_to_lds ? "direct" : "regs"), s,
-                 s > 1 ? (fused ? "f" : "r") : "");
+                 s > 1 ? (fused == 2 ? "l" : (fused ? "f" : "r")) : "");
         add_variant(p, v, im);
       }
     }
@@ -146,7 +150,8 @@ void build_family(tf_problem* p) {
       for (int s : splits) {
         const long per = cdivl(kblocks, s);
         if (s > 1 && (per < k.waves || per * (s - 1) >= kblocks || tn * s > 8L * cus)) continue;
-        for (int fused = 1; fused >= 0; --fused) {
+        const int fused_mode = tn % 8 == 0 ? 2 : 1;      // slices of a column block are tn work-groups apart
+        for (int fused = fused_mode; fused >= 0; fused -= fused_mode) {
           if (s == 1 && fused == 0) continue;
           tf_variant_desc v;
           memset(&v, 0, sizeof(v));
@@ -157,10 +162,10 @@ void build_family(tf_problem* p) {
           v.grid = (int32_t)(tn * s);
           VariantImpl im;
           im.lds_index = i; im.ktiles_per_split = (int)per; im.tiles_m = 1; im.tiles_n = (int)tn;
-          im.counter_bytes = s > 1 ? (size_t)((tn * 4 + 255) / 256 * 256) : 0;
+          im.counter_bytes = s > 1 ? (size_t)((tn * 8 + 255) / 256 * 256) : 0;
           v.workspace_bytes = s > 1 ? (int64_t)(im.counter_bytes + (size_t)s * d.M * d.N * 4) : 0;
           snprintf(v.name, sizeof(v.name), "stream_%dx%dx32_k%d_d%d_sk%d%s", v.bm, k.block_n, k.waves, k.depth, s,
-                   s > 1 ? (fused ? "f" : "r") : "");
+                   s > 1 ? (fused == 2 ? "l" : (fused ? "f" : "r")) : "");
           add_variant(p, v, im);
         }
       }

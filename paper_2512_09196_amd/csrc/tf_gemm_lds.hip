@@ -255,7 +255,9 @@ __device__ __forceinline__ void store_partial(const f32x16 (&acc)[C::TM][C::TN],
 
 // Split-K: sum of all slices, always in slice order 0, 1, ... so the result does not depend on
 // which slice arrived last.
-template <class C, bool FULL>
+// THROUGH: device-scope loads (the slices may have been written through other XCDs' L2s);
+// otherwise plain 16-byte loads, for slices known to sit in this XCD's L2.
+template <class C, bool FULL, bool THROUGH>
 __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0) {
   const size_t slice = (size_t)p.M * p.N;
 #pragma unroll
@@ -274,10 +276,14 @@ __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const 
             // from an earlier launch
             const float* q4 = src + (size_t)sidx * slice;
             f32x4 v;
-            v[0] = __hip_atomic_load(q4 + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            v[1] = __hip_atomic_load(q4 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            v[2] = __hip_atomic_load(q4 + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            v[3] = __hip_atomic_load(q4 + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (THROUGH) {
+              v[0] = __hip_atomic_load(q4 + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              v[1] = __hip_atomic_load(q4 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              v[2] = __hip_atomic_load(q4 + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              v[3] = __hip_atomic_load(q4 + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+              v = *(const f32x4*)q4;
+            }
             sum += v;
           }
         }
@@ -784,20 +790,52 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       else store_partial<C, false, false>(acc, wsk, p, wm0, wn0);
       return;
     }
-    if (full) store_partial<C, true, true>(acc, wsk, p, wm0, wn0);
-    else store_partial<C, false, true>(acc, wsk, p, wm0, wn0);
-    // every write-through store of this wave has been acknowledged before the wave reaches the
-    // barrier, so the ticket taken after it is ordered behind the whole work-group's partials
+    // Two ways to hand the partial tiles to the last slice:
+    //  fused_reduce 1: device-scope (write-through) stores and loads, valid wherever the slices run;
+    //  fused_reduce 2: plain stores and loads. The host offers it only when the tile order puts
+    //    all slices of a tile on one XCD (work-group i runs on XCD i mod 8), whose L2 then holds
+    //    the partial tiles: a store acknowledged by the L2 (vmcnt) is what any CU of the same XCD
+    //    reads afterwards, and no CU has read these addresses earlier in the launch. Every slice
+    //    reports the XCD it really ran on with its ticket; if they differ, the tile is poisoned
+    //    with NaN rather than summed from memory that may be stale.
+    const bool local = p.fused_reduce == 2;
+    if (local) {
+      if (full) store_partial<C, true, false>(acc, wsk, p, wm0, wn0);
+      else store_partial<C, false, false>(acc, wsk, p, wm0, wn0);
+    } else {
+      if (full) store_partial<C, true, true>(acc, wsk, p, wm0, wn0);
+      else store_partial<C, false, true>(acc, wsk, p, wm0, wn0);
+    }
+    // every store of this wave has been acknowledged before the wave reaches the barrier, so
+    // the ticket taken after it is ordered behind the whole work-group's partials
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    __shared__ unsigned ticket;
-    unsigned* ctr = p.counters + (tc.tm * p.tiles_n + tc.tn);
-    if (tid == 0) ticket = atomicAdd(ctr, 1u);
+    // ticket word: arrivals in bits 0..7, arrivals per XCD in 7-bit fields above
+    __shared__ unsigned long long ticket;
+    unsigned long long* ctr = (unsigned long long*)p.counters + (tc.tm * p.tiles_n + tc.tn);
+    const unsigned xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 7u;      // HW_REG_XCC_ID, bits 0..3
+    const unsigned long long mine = 1ull + (1ull << (8 + 7 * xcc));
+    if (tid == 0) ticket = atomicAdd(ctr, mine) + mine;
     __syncthreads();
-    if (ticket != (unsigned)(p.split_k - 1)) return;
-    if (tid == 0) *ctr = 0u;          // ready for the next launch
-    if (full) sum_partials<C, true>(acc, p, wm0, wn0);
-    else sum_partials<C, false>(acc, p, wm0, wn0);
+    const unsigned long long tk = ticket;
+    if ((unsigned)(tk & 255u) != (unsigned)p.split_k) return;
+    if (tid == 0) *ctr = 0ull;        // ready for the next launch
+    if (local) {
+      if (full) sum_partials<C, true, false>(acc, p, wm0, wn0);
+      else sum_partials<C, false, false>(acc, p, wm0, wn0);
+      if ((unsigned)((tk >> (8 + 7 * xcc)) & 127u) != (unsigned)p.split_k) {
+        const float nan = __builtin_nanf("");
+#pragma unroll
+        for (int i = 0; i < C::TM_OUT; ++i)
+#pragma unroll
+          for (int t = 0; t < C::TN; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][t][r] = nan;
+      }
+    } else {
+      if (full) sum_partials<C, true, true>(acc, p, wm0, wn0);
+      else sum_partials<C, false, true>(acc, p, wm0, wn0);
+    }
   }
 
   // ---- epilogue: + bias, GELU, round to bf16 (or raw fp32 pre-activation)

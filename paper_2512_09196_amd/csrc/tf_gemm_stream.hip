@@ -158,6 +158,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_stream_kernel(const GemmPa
     }
   }
 
+  bool poisoned = false;
   if (p.split_k > 1) {
     // publish this slice's partial sums
     float* wsk = p.ws + (size_t)ks * slice;
@@ -171,22 +172,31 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_stream_kernel(const GemmPa
         const int m = 16 * (f / C::CW) + m_lane + r;
         if (m >= p.M) continue;
         float* dst = wsk + (size_t)m * p.N + n;
-        if (p.fused_reduce) __hip_atomic_store(dst, sum[o][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // through this XCD's L2
-        else *dst = sum[o][r];                                                                               // the reduce kernel sums the slices
+        if (p.fused_reduce == 1) __hip_atomic_store(dst, sum[o][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // through this XCD's L2
+        else *dst = sum[o][r];     // summed by the reduce kernel, or (fused_reduce 2) left in the L2 all slices share
       }
     }
     if (!p.fused_reduce) return;
     // The last slice of this column block to arrive sums all slices, in slice order. Every store
     // above has been acknowledged before its wave reaches the barrier, so the ticket taken after
     // the barrier is ordered behind the whole work-group's partial sums.
+    // fused_reduce 2: the host has made sure that the slices of a column block are work-groups
+    // with the same id modulo 8, i.e. on one XCD, whose L2 holds the plain stores above; every
+    // slice reports the XCD it really ran on in its ticket (7-bit field per XCD above the arrival
+    // count), and a column block whose slices did not share one is poisoned with NaN.
+    const bool local = p.fused_reduce == 2;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    __shared__ unsigned ticket;
-    unsigned* ctr = p.counters + tn;
-    if (threadIdx.x == 0) ticket = atomicAdd(ctr, 1u);
+    __shared__ unsigned long long ticket;
+    unsigned long long* ctr = (unsigned long long*)p.counters + tn;
+    const unsigned xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 7u;      // HW_REG_XCC_ID
+    const unsigned long long mine = 1ull + (1ull << (8 + 7 * xcc));
+    if (threadIdx.x == 0) ticket = atomicAdd(ctr, mine) + mine;
     __syncthreads();
-    if (ticket != (unsigned)(p.split_k - 1)) return;
-    if (threadIdx.x == 0) *ctr = 0u;            // ready for the next launch
+    const unsigned long long tk = ticket;
+    if ((unsigned)(tk & 255u) != (unsigned)p.split_k) return;
+    if (threadIdx.x == 0) *ctr = 0ull;          // ready for the next launch
+    poisoned = local && (unsigned)((tk >> (8 + 7 * xcc)) & 127u) != (unsigned)p.split_k;
 #pragma unroll
     for (int o = 0; o < OWN; ++o) {
       const int f = wave + o * C::NW;
@@ -197,8 +207,10 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_stream_kernel(const GemmPa
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int m = 16 * (f / C::CW) + m_lane + r;
+          if (m >= p.M) continue;
+          const float* src = p.ws + (size_t)sidx * slice + (size_t)m * p.N + n;
           // device-scope loads: from memory, never from a line this XCD's L2 kept from an earlier launch
-          if (m < p.M) sum[o][r] += __hip_atomic_load(p.ws + (size_t)sidx * slice + (size_t)m * p.N + n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          sum[o][r] += local ? *src : __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
       }
     }
@@ -209,6 +221,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_stream_kernel(const GemmPa
   for (int o = 0; o < OWN; ++o) {
     const int f = wave + o * C::NW;
     if (f >= C::FRAGS || !n_ok) continue;
+    if (poisoned) sum[o] = f32x4{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), __builtin_nanf("")};
     const int n = n_lane + (f % C::CW);
     const float bias = bf16_bits_to_f32(p.bias[n]);
 #pragma unroll

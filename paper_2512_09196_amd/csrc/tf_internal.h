@@ -14,7 +14,7 @@ struct GemmParams {
   const uint16_t* bias;   // [N] bf16 bits
   void* Y;                // [M, ldy]: bf16 bits (TF_EPI_BIAS_GELU_ERF) or float (TF_EPI_NONE_F32)
   float* ws;              // split-K partial sums [split_k][M][N] (unused when split_k == 1)
-  unsigned* counters;     // one arrival counter per output tile, zero between launches
+  unsigned* counters;     // one 8-byte arrival counter per output tile, zero between launches
   int M, N, K;
   long lda, ldb, ldy;     // in elements
   int tiles_m, tiles_n;

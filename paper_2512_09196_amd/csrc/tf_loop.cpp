@@ -133,7 +133,7 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
     if (rate > cap_gbs) rate = cap_gbs;
     double us = bytes / (rate * 1e3) + startup + 2.5;
     // slices: the last work-group to arrive sums them after one more trip to memory, or a second launch does
-    if (v->split_k > 1) us += (v->fused_reduce ? 5.5 : 4.5) + 2.0 * v->split_k * 4.0 * pr->M * (double)pr->N / (hw->hbm_gbs_peak * 1e3);
+    if (v->split_k > 1) us += (v->fused_reduce == 2 ? 2.0 : (v->fused_reduce ? 5.5 : 4.5)) + 2.0 * v->split_k * 4.0 * pr->M * (double)pr->N / (hw->hbm_gbs_peak * 1e3);
     return us;
   }
   const int resident = tf_resident_wgs(hw, v);
@@ -172,7 +172,10 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   double reduce_us = 0.0, fused_tail_us = 0.0;
   const double mhz = hw->clock_mhz < 1650.0 ? hw->clock_mhz : 1650.0;
   if (v->split_k > 1) {
-    if (v->fused_reduce) {
+    if (v->fused_reduce == 2) {
+      // partial tiles stay in the L2 the slices share: 16-byte stores and loads, one round of tickets
+      fused_tail_us = 1.5 + v->bm * (double)v->bn * 4.0 * (1.0 + v->split_k) / 64.0 / mhz;
+    } else if (v->fused_reduce) {
       // partial tiles go out and come back through device-scope scalar accesses at about
       // 2 B/clk, and the last slice of a tile reads all of them alone
       fused_tail_us = v->bm * (double)v->bn * 4.0 * (1.0 + v->split_k) / 2.0 / mhz;

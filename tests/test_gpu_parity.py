@@ -205,6 +205,28 @@ def test_split_k_is_deterministic_and_counters_self_clean():
                 assert np.array_equal(raw, first), "run %d of %s differs" % (rep, v.name.decode())
 
 
+def test_l2_local_reduction_equals_the_two_kernel_reduction_bit_for_bit():
+    # fused_reduce 2 keeps the partial tiles in the L2 of the XCD all slices of a tile run on; it sums
+    # the slices in the same order as the reduce kernel, so the fp32 pre-activations must be identical,
+    # launch after launch, also right after other variants have used the same workspace
+    for (M, N, K) in ((512, 512, 4096), (16, 1024, 4096), (1024, 256, 2048)):
+        A, B, bias = wl.make_custom(M, N, K, seed=61 + M, a_dist=("normal", 1.0), b_dist=("normal", 0.05))
+        dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+        out = gu.OutBuf(M, N, f32=True)
+        with tf.Problem(M, N, K, epi=tf.TF_EPI_NONE_F32) as prob:
+            by_name = {v.name.decode(): v for v in prob.variants()}
+            local = [n for n, v in by_name.items() if v.split_k > 1 and v.fused_reduce == 2]
+            assert local, "no variant with the L2-local reduction for %s" % ((M, N, K),)
+            for rep in range(2):
+                for n in local:
+                    twin = by_name[n[:-1] + "r"]
+                    print("case", (M, N, K), n, "rep", rep, flush=True)
+                    _, ok1, raw_l = gu.run_variant(prob, by_name[n].id, dA, dB, dbias, out)
+                    _, ok2, raw_r = gu.run_variant(prob, twin.id, dA, dB, dbias, out)
+                    assert ok1 and ok2 and not np.isnan(raw_l).any(), n
+                    assert np.array_equal(raw_l, raw_r), n
+
+
 def test_split_k_variants_with_different_tile_counts_share_one_workspace():
     # tile shapes with 4, 8, 16 and 64 output tiles take turns on the problem's workspace:
     # the partial sums of one must never land on the arrival counters of another
