@@ -178,6 +178,11 @@ def main():
     roof["traffic_unit"] = "bytes per launch"
     roof["kernel"] = names[vid]
     roof["avg_launch_us"] = kern_us
+    # context: what this chip sustains right now on a register-only MFMA loop with data-like operands and on a
+    # 1 GiB streaming read; `frac` stays the fraction of the published peak
+    mfma_meas, hbm_meas = tf.hw_measure(0, stream)
+    roof["measured_achievable"] = {"mfma_tflops": mfma_meas, "hbm_read_gbs": hbm_meas,
+                                   "frac_of_measured": roof["achieved"] / (hbm_meas if w.bound == "hbm" else mfma_meas)}
 
     out = {
         "metric": "GEMM+epilogue TFLOP/s (bf16 GELU_erf(A.B+bias), fp32 accumulate)",

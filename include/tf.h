@@ -159,6 +159,12 @@ void tf_theta_default(tf_theta* out);
 tf_status tf_hw_query(int32_t device, tf_hw* out);
 /* Same structure without touching a GPU: the published MI355X figures. */
 void tf_hw_nominal(tf_hw* out);
+/* What device `device` sustains, measured now (host pointers out, either may be NULL): bf16 MFMA
+ * TFLOP/s of a register-only 32x32x16 loop on data-like operands running for a few milliseconds
+ * (the clock under MFMA load depends on the operand bits), and GB/s of a streaming read of 1 GiB
+ * that the library allocates and frees. Synchronises hip_stream. Context for the roofline
+ * fractions, which are quoted against the published peaks. */
+tf_status tf_hw_measure(int32_t device, void* hip_stream, double* mfma_tflops, double* hbm_read_gbs);
 
 /* Validates desc (host pointer) and creates the problem. M, N, K >= 0. */
 tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem** out);

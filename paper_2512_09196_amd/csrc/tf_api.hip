@@ -498,6 +498,57 @@ extern "C" tf_status tf_hw_query(int32_t device, tf_hw* out) {
   return TF_OK;
 }
 
+extern "C" tf_status tf_hw_measure(int32_t device, void* hip_stream, double* mfma_tflops, double* hbm_read_gbs) {
+  tf_hw hw;
+  tf_status st = tf_hw_query(device, &hw);
+  if (st != TF_OK) return st;
+  TF_HIP(hipSetDevice(device));
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  TF_HIP(hipEventCreate(&e0));
+  TF_HIP(hipEventCreate(&e1));
+  void* sink = nullptr;
+  void* big = nullptr;
+  auto cleanup = [&]() {
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    if (sink) (void)hipFree(sink);
+    if (big) (void)hipFree(big);
+  };
+  if (hipMalloc(&sink, 256) != hipSuccess) { cleanup(); return fail(TF_E_NOMEM, "cannot allocate the sink"); }
+  float ms = 0.f;
+  if (mfma_tflops) {
+    // two waves per SIMD, about 3 ms per launch: long enough for the clock to settle
+    const int wgs = hw.cus * 2, iters = 20000;
+    double best = 0.0;
+    for (int rep = 0; rep < 3; ++rep) {
+      if (hipEventRecord(e0, stream) != hipSuccess) { cleanup(); return fail(TF_E_LAUNCH, "hipEventRecord failed"); }
+      tf::launch_calib_mfma((float*)sink, wgs, iters, stream);
+      if (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+          hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { cleanup(); return fail(TF_E_LAUNCH, "MFMA calibration launch failed"); }
+      const double flops = (double)wgs * 4.0 * iters * 4.0 * 32768.0;
+      if (rep > 0) best = std::max(best, flops / (ms * 1e-3) * 1e-12);    // the first launch warms the clock up
+    }
+    *mfma_tflops = best;
+  }
+  if (hbm_read_gbs) {
+    const size_t bytes = (size_t)1 << 30;
+    if (hipMalloc(&big, bytes) != hipSuccess) { cleanup(); return fail(TF_E_NOMEM, "cannot allocate 1 GiB for the read calibration"); }
+    tf::launch_fill_u32((unsigned*)big, bytes / 4, 1u, stream);
+    double best = 0.0;
+    for (int rep = 0; rep < 4; ++rep) {
+      if (hipEventRecord(e0, stream) != hipSuccess) { cleanup(); return fail(TF_E_LAUNCH, "hipEventRecord failed"); }
+      tf::launch_calib_read(big, bytes, (unsigned*)sink, hw.cus * 8, stream);
+      if (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+          hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { cleanup(); return fail(TF_E_LAUNCH, "read calibration launch failed"); }
+      if (rep > 0) best = std::max(best, (double)bytes / (ms * 1e-3) * 1e-9);
+    }
+    *hbm_read_gbs = best;
+  }
+  cleanup();
+  TF_HIP(hipGetLastError());
+  return TF_OK;
+}
+
 extern "C" tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem** out) {
   if (!desc || !out) return fail(TF_E_INVALID, "null argument");
   *out = nullptr;

@@ -53,6 +53,8 @@ void launch_mfma_direct(const GemmParams&, hipStream_t);
 const void* naive_func();
 const void* mfma_direct_func();
 void launch_fill_u32(unsigned* p, size_t n, unsigned v, hipStream_t);
+void launch_calib_mfma(float* sink, int wgs, int iters, hipStream_t);                       // 4 * iters MFMA 32x32x16 per wave, 4 waves per work-group
+void launch_calib_read(const void* src, size_t bytes, unsigned* sink, int wgs, hipStream_t);  // reads every byte once
 void launch_splitk_reduce(const GemmParams&, hipStream_t);   // sums ws slices in order, bias + epilogue -> Y
 const void* splitk_reduce_func();
 

@@ -80,6 +80,7 @@ SIGNATURES = {
     "tf_theta_default": (None, [_P(Theta)]),
     "tf_hw_query": (C.c_int32, [C.c_int32, _P(Hw)]),
     "tf_hw_nominal": (None, [_P(Hw)]),
+    "tf_hw_measure": (C.c_int32, [C.c_int32, C.c_void_p, _P(C.c_double), _P(C.c_double)]),
     "tf_problem_create": (C.c_int32, [_P(ProblemDesc), _P(C.c_void_p)]),
     "tf_problem_destroy": (None, [C.c_void_p]),
     "tf_variant_enumerate": (C.c_int32, [C.c_void_p, _P(VariantDesc), C.c_int32]),
@@ -125,6 +126,13 @@ def lib():
             raise RuntimeError(
                 "%s is missing: build it with `python -m paper_2512_09196_amd.build` "
                 "(the HIP library is the only implementation)" % LIB_PATH)
+        # PyTorch ships its own HIP runtime. If it is going to be used in this process (device memory,
+        # streams), it must be loaded first, so that this library binds to the same runtime instance
+        # instead of bringing in a second one that does not see the first one's device state.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         l = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             f = getattr(l, name)
@@ -178,6 +186,13 @@ def hw_query(device: int = 0) -> Hw:
     h = Hw()
     _check(lib().tf_hw_query(device, C.byref(h)))
     return h
+
+
+def hw_measure(device: int = 0, stream=None):
+    """(bf16 MFMA TFLOP/s of a register-only loop, GB/s of a 1 GiB streaming read), measured now."""
+    a, b = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().tf_hw_measure(device, _stream(stream), C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 def arbiter(cand: Report, best: Report, theta: Theta, best_is_baseline: bool, stall_rounds: int, rnd: int) -> int:

@@ -130,3 +130,10 @@ def test_profile_report_fields():
         assert r.grid == v.grid and 1 <= r.waves_per_simd <= 8 and r.vgprs > 0 and r.lds_bytes >= v.lds_bytes
         assert 0 < r.grid_fill <= 1.0 and r.spill_bytes == 0
         assert r.tflops > 100.0       # an MFMA kernel on this shape is far above any VALU rate
+
+
+def test_measured_peaks_are_plausible():
+    mfma, hbm = tf.hw_measure(0)
+    print("measured: %.0f TFLOP/s bf16 MFMA, %.0f GB/s HBM read" % (mfma, hbm), flush=True)
+    # below the published peaks, and not absurdly so
+    assert 800.0 < mfma < 2516.6 and 3000.0 < hbm < 8000.0
