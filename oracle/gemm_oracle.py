@@ -54,6 +54,10 @@ def _load():
             lib.tfo_gemm_bias_gelu.argtypes = [
                 ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long,
                 u16p, ctypes.c_long, u16p, f64p, f64p, f64p]
+            lib.tfo_batched_vecmat.restype = ctypes.c_int
+            lib.tfo_batched_vecmat.argtypes = [
+                ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long,
+                u16p, ctypes.c_long, f64p, f64p]
             lib.tfo_gemm_bias_gelu_at.restype = ctypes.c_int
             lib.tfo_gemm_bias_gelu_at.argtypes = [
                 ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long,
@@ -130,3 +134,21 @@ def gemm_bias_gelu_at(A, B, bias, rows, cols):
     if rc != 0:
         raise RuntimeError(f"tfo_gemm_bias_gelu_at failed with {rc}")
     return y, z, s
+
+
+def batched_vecmat(A, B):
+    """C[m, n] = sum_k A[m, k] B[m, n, k] (the paper's Case Study 2) in double, and S = sum |a b|.
+
+    A: uint16 [M, K], B: uint16 [M, N, K], bf16 bit patterns. Returns (C, S), float64 [M, N]."""
+    A, B = _u16(A, "A"), _u16(B, "B")
+    if A.ndim != 2 or B.ndim != 3 or B.shape[0] != A.shape[0] or B.shape[2] != A.shape[1]:
+        raise ValueError(f"shape mismatch A{A.shape} B{B.shape}")
+    M, K = A.shape
+    N = B.shape[1]
+    c = np.empty((M, N), np.float64)
+    s = np.empty((M, N), np.float64)
+    rc = _load().tfo_batched_vecmat(M, N, K, _ptr(A, ctypes.c_uint16), K, _ptr(B, ctypes.c_uint16), K,
+                                    _ptr(c, ctypes.c_double), _ptr(s, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError(f"tfo_batched_vecmat failed with {rc}")
+    return c, s

@@ -1,5 +1,6 @@
 /*
- * CPU oracle for the fused tile kernel  Y = GELU_erf(A.B + bias).
+ * CPU oracle for the fused tile kernel  Y = GELU_erf(A.B + bias), and (last function of the
+ * file) for the batched vector-matrix product of the paper's Case Study 2.
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
  * GPU kernels are checked against.  It is single-threaded, has no blocking,
@@ -130,6 +131,44 @@ int tfo_gemm_bias_gelu_at(int M, int N, int K,
         if (z) z[t] = zz;
         if (y) y[t] = tfo_gelu(zz);
         if (s) s[t] = abs_acc + fabs(bv);
+    }
+    return 0;
+}
+
+/*
+ * Batched vector-matrix product of the paper's Case Study 2:
+ *     C[m][n] = sum_{k=0}^{K-1} A[m][k] * B[m][n][k]
+ * A is [M][lda] (lda >= K), B is [M][N][ldb] (ldb >= K, k contiguous, the matrices of the batch
+ * one after the other), all bf16 bit patterns; C and S are [M][N] doubles (S = sum |a b|, the
+ * scale of a rounding-error bound; may be NULL). The definition written out: three nested
+ * loops, products and sums in double, k ascending.
+ * Pinned by tests/test_oracle_bvm.py: exact rational arithmetic on small cases, A = ones (row
+ * sums of B by an independent exactly rounded summation), a Kronecker-delta B that picks single
+ * elements of A, the one-row case against a library matrix-vector product, integer operands,
+ * power-of-two scaling.
+ */
+int tfo_batched_vecmat(int M, int N, int K,
+                       const uint16_t *A, long lda,
+                       const uint16_t *B, long ldb,
+                       double *C, double *S)
+{
+    if (M < 0 || N < 0 || K < 0) return -1;
+    if (lda < K || ldb < K) return -1;
+    if (M > 0 && N > 0 && !C) return -1;
+    if (M > 0 && N > 0 && K > 0 && (!A || !B)) return -1;
+    for (int m = 0; m < M; ++m) {
+        for (int n = 0; n < N; ++n) {
+            const uint16_t *brow = B + ((size_t)m * (size_t)N + (size_t)n) * (size_t)ldb;
+            double acc = 0.0, abs_acc = 0.0;
+            for (int k = 0; k < K; ++k) {
+                const double p = tfo_bf16_to_double(A[(size_t)m * (size_t)lda + (size_t)k]) *
+                                 tfo_bf16_to_double(brow[k]);
+                acc += p;
+                abs_acc += fabs(p);
+            }
+            C[(size_t)m * (size_t)N + (size_t)n] = acc;
+            if (S) S[(size_t)m * (size_t)N + (size_t)n] = abs_acc;
+        }
     }
     return 0;
 }

@@ -163,3 +163,37 @@ def make_custom(M, N, K, seed, a_dist=("uniform", None), b_dist=("uniform", None
     B = _draw(b_dist, seed, 1, (K, N))
     bias = _draw(bias_dist, seed, 2, (N,))
     return A, B, bias
+
+
+# ---- batched vector-matrix product (the paper's Case Study 2): C[m, n] = sum_k A[m, k] B[m, n, k].
+# The paper gives no shapes; these are chosen here. V1 is small enough for the CPU oracle in well
+# under a second and still has several row groups and a ragged last k chunk; V2 reads 1 GiB of B.
+@dataclass(frozen=True)
+class VecmatWorkload:
+    name: str
+    M: int
+    N: int
+    K: int
+    seed: int
+
+    @property
+    def flops(self) -> int:
+        return 2 * self.M * self.N * self.K
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        """A and B read once (bf16), C written once (fp32)."""
+        return 2 * (self.M * self.K + self.M * self.N * self.K) + 4 * self.M * self.N
+
+
+VECMAT_WORKLOADS = {
+    "V1": VecmatWorkload("V1", 8, 520, 1000, 10),
+    "V2": VecmatWorkload("V2", 32, 4096, 4096, 11),
+}
+
+
+def make_vecmat(M, N, K, seed):
+    """(A[M,K] ~ N(0,1), B[M,N,K] ~ uniform[-1,1)/sqrt(K)) as uint16 bf16 bit patterns."""
+    A = normal_bf16(seed, 0, (M, K), 1.0)
+    B = uniform_bf16(seed, 1, (M, N, K), max(K, 1) ** -0.5)
+    return A, B
