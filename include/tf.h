@@ -55,8 +55,14 @@ typedef enum {
   TF_KIND_NAIVE = 0,        /* one thread per output element, scalar FMA loop: the baseline kernel K */
   TF_KIND_MFMA_DIRECT = 1,  /* one wave per 32x32 tile, MFMA operands loaded straight from memory     */
   TF_KIND_MFMA_LDS = 2,     /* LDS-staged, multi-buffered, swizzled MFMA tile kernel                  */
-  TF_KIND_MFMA_STREAM = 3   /* skinny problems (M <= 32): B streamed once from memory into MFMA operand
+  TF_KIND_MFMA_STREAM = 3,  /* skinny problems (M <= 32): B streamed once from memory into MFMA operand
                                registers, no LDS staging; the waves of a work-group split K            */
+  TF_KIND_VECMAT_NAIVE = 4, /* TF_OP_BATCHED_VECMAT baseline: one thread per output, scalar loop over k */
+  TF_KIND_VECMAT_STREAM = 5 /* TF_OP_BATCHED_VECMAT: a wave per group of rows, k-contiguous 16-byte loads,
+                               lane-exchange reduction. Descriptor fields: bm = rows per wave, bk = 512,
+                               stages = k chunks in flight per row, waves_k = waves per work-group,
+                               group_m = work-groups per compute unit the grid is cut to (0 = one wave
+                               per row group)                                                          */
 } tf_kind;
 
 /* Bottleneck classes produced by tf_refine_hint (Sec. 3.3 "Targeted-Refinement-Hint":
@@ -73,12 +79,23 @@ typedef enum {
 
 typedef enum { TF_DEC_CONTINUE = 0, TF_DEC_ACCEPT = 1, TF_DEC_FINISH = 2 } tf_decision;
 
+/* The operation. */
+typedef enum {
+  TF_OP_GEMM_EPILOGUE = 0,  /* Y = epilogue(A.B + bias): A [M][lda], B [K][ldb], bias [N], Y [M][ldy] */
+  TF_OP_BATCHED_VECMAT = 1  /* Case Study 2 of the paper (Sec. 5): C[m][n] = sum_k A[m][k] B[m][n][k].
+                               A [M][lda] bf16 (lda >= K); B [M][N][ldb] bf16, k contiguous (ldb >= K),
+                               matrix m starting N * ldb elements after matrix m - 1; Y = C as fp32
+                               [M][ldy] (epi must be TF_EPI_NONE_F32); bias is not read (may be NULL) */
+} tf_op;
+
 /* The problem: shapes and strides of one call of the tile kernel. */
 typedef struct {
   int32_t M, N, K;
-  int64_t lda, ldb, ldy;   /* leading dimensions in elements; lda >= K, ldb >= N, ldy >= N */
+  int64_t lda, ldb, ldy;   /* leading dimensions in elements; lda >= K, ldb >= N (TF_OP_BATCHED_VECMAT: >= K), ldy >= N */
   int32_t epi;             /* tf_epilogue */
   int32_t device;          /* HIP device ordinal */
+  int32_t op;              /* tf_op */
+  int32_t reserved;        /* zero */
 } tf_problem_desc;
 
 /* One member of the kernel family: the paper's "tiling/block shapes, num_warps, vectorization

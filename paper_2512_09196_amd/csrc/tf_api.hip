@@ -64,10 +64,50 @@ void add_variant(tf_problem* p, const tf_variant_desc& v, const VariantImpl& im)
   p->impl.push_back(im);
 }
 
+// C[m][n] = sum_k A[m][k] B[m][n][k]: the naive kernel, then the streaming family at several grid sizes.
+void build_vecmat_family(tf_problem* p) {
+  const tf_problem_desc& d = p->desc;
+  {
+    tf_variant_desc v;
+    memset(&v, 0, sizeof(v));
+    v.kind = TF_KIND_VECMAT_NAIVE; v.bm = 1; v.bn = 256; v.bk = 1; v.waves_m = 4; v.waves_n = 1; v.waves_k = 1;
+    v.split_k = 1; v.threads = 256; v.group_m = 0;
+    v.grid = (int32_t)(cdivl(d.N, 256) * std::max(d.M, 1));
+    snprintf(v.name, sizeof(v.name), "vecmat_naive_1elem_per_thread");
+    add_variant(p, v, VariantImpl{-1, 0, 0, 0, 0});
+  }
+  // 16-byte loads along k: rows must start on 16 bytes and K be a multiple of 8
+  const bool aligned = d.M > 0 && d.N > 0 && d.K >= 8 && d.K % 8 == 0 && d.lda % 8 == 0 && d.ldb % 8 == 0 && d.M <= 65535;
+  if (!aligned) return;
+  const int cus = p->hw.cus > 0 ? p->hw.cus : 256;
+  const tf::VecmatKernelInfo* tab = tf::vecmat_kernel_table();
+  for (int i = 0; i < tf::vecmat_kernel_count(); ++i) {
+    const tf::VecmatKernelInfo& k = tab[i];
+    if (k.unroll > 2 && (long)(k.unroll / 2) * 512 >= d.K) continue;     // twice as many chunks in flight as the row has
+    const long groups = cdivl(d.N, k.rows) * d.M;
+    const long full = cdivl(groups, k.waves);
+    static const int per_cu[] = {0, 4, 8};       // 0: one wave per row group; else the grid is cut to that many work-groups per CU
+    for (int g : per_cu) {
+      long grid = g == 0 ? full : std::min<long>(full, (long)g * cus);
+      if (g != 0 && grid == full) continue;      // same launch as g = 0
+      if (grid > 0x7fffffffL) continue;
+      tf_variant_desc v;
+      memset(&v, 0, sizeof(v));
+      v.kind = TF_KIND_VECMAT_STREAM; v.bm = k.rows; v.bn = 1; v.bk = 512; v.waves_m = 1; v.waves_n = 1; v.waves_k = k.waves;
+      v.stages = k.unroll; v.split_k = 1; v.threads = k.threads; v.group_m = g;
+      v.grid = (int32_t)grid;
+      snprintf(v.name, sizeof(v.name), "vecmat_r%d_u%d_w%d_g%d", k.rows, k.unroll, k.waves, g);
+      VariantImpl im{i, 0, 0, 0, 0};
+      add_variant(p, v, im);
+    }
+  }
+}
+
 void build_family(tf_problem* p) {
   const tf_problem_desc& d = p->desc;
   p->family.clear();
   p->impl.clear();
+  if (d.op == TF_OP_BATCHED_VECMAT) { build_vecmat_family(p); return; }
   {
     tf_variant_desc v;
     memset(&v, 0, sizeof(v));
@@ -188,6 +228,14 @@ tf_status check_ptrs(const tf_problem* p, const tf_variant_desc& v, const void* 
                      void* Y) {
   const tf_problem_desc& d = p->desc;
   if (d.M == 0 || d.N == 0) return TF_OK;
+  if (d.op == TF_OP_BATCHED_VECMAT) {
+    if (!Y) return fail(TF_E_INVALID, "null Y pointer");
+    if (d.K > 0 && (!A || !B)) return fail(TF_E_INVALID, "null A or B pointer");
+    if (v.kind == TF_KIND_VECMAT_STREAM && (((uintptr_t)A | (uintptr_t)B) & 15u))
+      return fail(TF_E_UNSUPPORTED, "variant %s needs 16-byte aligned A and B", v.name);
+    if ((uintptr_t)Y & 3u) return fail(TF_E_UNSUPPORTED, "Y must be 4-byte aligned");
+    return TF_OK;
+  }
   if (!Y || !bias) return fail(TF_E_INVALID, "null Y or bias pointer");
   if (d.K > 0 && (!A || !B)) return fail(TF_E_INVALID, "null A or B pointer");
   if (v.kind == TF_KIND_MFMA_LDS || v.kind == TF_KIND_MFMA_STREAM) {
@@ -210,7 +258,12 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
   g.A = (const uint16_t*)A; g.B = (const uint16_t*)B; g.bias = (const uint16_t*)bias; g.Y = Y;
   g.M = d.M; g.N = d.N; g.K = d.K; g.lda = d.lda; g.ldb = d.ldb; g.ldy = d.ldy;
   g.epi = d.epi; g.split_k = v.split_k; g.fused_reduce = v.fused_reduce; g.group_m = v.group_m > 0 ? v.group_m : 1; g.xcd_swizzle = v.xcd_swizzle;
-  if (v.kind == TF_KIND_NAIVE) {
+  if (v.kind == TF_KIND_VECMAT_NAIVE) {
+    if (d.M > 65535) return fail(TF_E_UNSUPPORTED, "naive variant: M too large for the grid");
+    tf::launch_vecmat_naive(g, stream);
+  } else if (v.kind == TF_KIND_VECMAT_STREAM) {
+    tf::vecmat_kernel_table()[im.lds_index].launch(g, dim3((unsigned)v.grid), stream);
+  } else if (v.kind == TF_KIND_NAIVE) {
     if (cdivl(d.M, 4) > 65535) return fail(TF_E_UNSUPPORTED, "naive variant: M too large for the grid");
     tf::launch_naive(g, stream);
   } else if (v.kind == TF_KIND_MFMA_DIRECT) {
@@ -267,7 +320,9 @@ void fill_static(tf_problem* p, int id, tf_report* r) {
   const tf_variant_desc& v = p->family[id];
   const void* func = nullptr;
   int dyn = 0;
-  if (v.kind == TF_KIND_NAIVE) func = tf::naive_func();
+  if (v.kind == TF_KIND_VECMAT_NAIVE) func = tf::vecmat_naive_func();
+  else if (v.kind == TF_KIND_VECMAT_STREAM) func = tf::vecmat_kernel_table()[p->impl[id].lds_index].func;
+  else if (v.kind == TF_KIND_NAIVE) func = tf::naive_func();
   else if (v.kind == TF_KIND_MFMA_DIRECT) func = tf::mfma_direct_func();
   else if (v.kind == TF_KIND_MFMA_STREAM) { func = tf::stream_kernel_table()[p->impl[id].lds_index].func; dyn = v.lds_bytes; }
   else { func = tf::lds_kernel_table()[p->impl[id].lds_index].func; dyn = v.lds_bytes; }
@@ -431,7 +486,9 @@ tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, cons
   out->t_mean_us = sum / ts.size();
   const tf_problem_desc& d = p->desc;
   const double flops = 2.0 * d.M * (double)d.N * d.K;
-  const double bytes = 2.0 * ((double)d.M * d.K + (double)d.K * d.N + (double)d.M * d.N + d.N);
+  const double bytes = d.op == TF_OP_BATCHED_VECMAT
+                           ? 2.0 * ((double)d.M * d.K + (double)d.M * d.N * d.K) + 4.0 * (double)d.M * d.N
+                           : 2.0 * ((double)d.M * d.K + (double)d.K * d.N + (double)d.M * d.N + d.N);
   out->arithmetic_intensity = bytes > 0 ? flops / bytes : 0.0;
   if (out->t_med_us > 0.0) {
     out->tflops = flops / out->t_med_us * 1e-6;
@@ -553,8 +610,11 @@ extern "C" tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem**
   if (!desc || !out) return fail(TF_E_INVALID, "null argument");
   *out = nullptr;
   if (desc->M < 0 || desc->N < 0 || desc->K < 0) return fail(TF_E_INVALID, "negative dimension");
-  if (desc->lda < desc->K || desc->ldb < desc->N || desc->ldy < desc->N)
+  if (desc->op != TF_OP_GEMM_EPILOGUE && desc->op != TF_OP_BATCHED_VECMAT) return fail(TF_E_INVALID, "unknown operation %d", desc->op);
+  const bool vecmat = desc->op == TF_OP_BATCHED_VECMAT;
+  if (desc->lda < desc->K || desc->ldb < (vecmat ? desc->K : desc->N) || desc->ldy < desc->N)
     return fail(TF_E_INVALID, "leading dimension smaller than the row length");
+  if (vecmat && desc->epi != TF_EPI_NONE_F32) return fail(TF_E_INVALID, "the batched vector-matrix product writes fp32 (TF_EPI_NONE_F32)");
   if (desc->epi != TF_EPI_BIAS_GELU_ERF && desc->epi != TF_EPI_NONE_F32) return fail(TF_E_INVALID, "unknown epilogue %d", desc->epi);
   tf_problem* p = new (std::nothrow) tf_problem();
   if (!p) return fail(TF_E_NOMEM, "out of host memory");
@@ -712,7 +772,9 @@ extern "C" tf_status tf_tune(tf_problem* p, const void* A, const void* B, const 
   if (th.cold_bytes > 0 && p->desc.M > 0 && p->desc.N > 0 && p->desc.K > 0) {
     const tf_problem_desc& d = p->desc;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-    const size_t araw = ((size_t)(d.M - 1) * d.lda + d.K) * 2, braw = ((size_t)(d.K - 1) * d.ldb + d.N) * 2;
+    const size_t araw = ((size_t)(d.M - 1) * d.lda + d.K) * 2;
+    const size_t braw = d.op == TF_OP_BATCHED_VECMAT ? (((size_t)d.M * d.N - 1) * d.ldb + d.K) * 2
+                                                     : ((size_t)(d.K - 1) * d.ldb + d.N) * 2;
     const size_t abytes = up(araw), bbytes = up(braw);
     const size_t ybytes = up(c.ybytes), set = abytes + bbytes + ybytes;
     const size_t n = std::min<size_t>((size_t)th.cold_bytes / set + 2, 256);

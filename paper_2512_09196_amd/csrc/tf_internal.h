@@ -48,6 +48,20 @@ struct StreamKernelInfo {
 int stream_kernel_count();
 const StreamKernelInfo* stream_kernel_table();
 
+// One compiled kernel of the streaming family of the batched vector-matrix product.
+// GemmParams: A [M][lda], B [M][N][ldb] (k contiguous), Y fp32 [M][ldy]; group_m unused.
+struct VecmatKernelInfo {
+  int rows;               // rows (m, n .. n + rows - 1) a wave works on at a time
+  int unroll;             // 512-element k chunks in flight per row
+  int waves, threads;
+  const void* func;
+  void (*launch)(const GemmParams&, dim3 grid, hipStream_t);
+};
+int vecmat_kernel_count();
+const VecmatKernelInfo* vecmat_kernel_table();
+void launch_vecmat_naive(const GemmParams&, hipStream_t);
+const void* vecmat_naive_func();
+
 void launch_naive(const GemmParams&, hipStream_t);
 void launch_mfma_direct(const GemmParams&, hipStream_t);
 const void* naive_func();

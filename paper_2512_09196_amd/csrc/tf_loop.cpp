@@ -116,6 +116,23 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   const double flops = 2.0 * pr->M * (double)pr->N * pr->K;
   const double bytes = 2.0 * ((double)pr->M * pr->K + (double)pr->K * pr->N + (double)pr->M * pr->N + pr->N);
   const double hbm_us = bytes / (hw->hbm_gbs_peak * 1e3);
+  if (v->kind == TF_KIND_VECMAT_NAIVE || v->kind == TF_KIND_VECMAT_STREAM) {
+    // C[m][n] = sum_k A[m][k] B[m][n][k]: B is read once; everything else is small
+    const double vbytes = 2.0 * ((double)pr->M * pr->K + (double)pr->M * pr->N * pr->K) + 4.0 * (double)pr->M * pr->N;
+    const double floor_us = vbytes / (hw->hbm_gbs_peak * 1e3);
+    if (v->kind == TF_KIND_VECMAT_NAIVE) return floor_us / 0.12 + 3.0;     // 64 lines per load instruction
+    // bytes a CU keeps in flight: resident waves (at most 16 by registers) x rows x chunks x 1 KB; about
+    // 48 KB are needed for the rate the chip sustains (0.72 of the peak)
+    double waves_per_cu = (double)v->grid * v->waves_k / hw->cus;
+    if (waves_per_cu > 16.0) waves_per_cu = 16.0;
+    double feed = waves_per_cu * v->bm * v->stages * 1024.0 / 49152.0;
+    if (feed > 1.0) feed = 1.0;
+    // a wave that takes many row groups in turn pays the memory latency once per group
+    const double groups = (double)pr->M * (double)((pr->N + v->bm - 1) / v->bm);
+    const double per_wave = groups / ((double)v->grid * v->waves_k);
+    const double serial_us = per_wave * 2.0 / (waves_per_cu > 4.0 ? waves_per_cu / 4.0 : 1.0);
+    return fmax(floor_us / (0.72 * feed), serial_us) + 3.0;
+  }
   if (v->kind == TF_KIND_NAIVE) return fmax(flops / (0.004 * hw->bf16_tflops_peak * 1e6), hbm_us) + 2.0;
   if (v->kind == TF_KIND_MFMA_DIRECT) return fmax(flops / (0.02 * hw->bf16_tflops_peak * 1e6), hbm_us) + 2.0;
   if (v->kind == TF_KIND_MFMA_STREAM) {

@@ -16,6 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libtf_gfx950.so")
 TF_OK, TF_E_INVALID, TF_E_UNSUPPORTED, TF_E_LAUNCH, TF_E_NOMEM, TF_E_RANGE, TF_E_PROFILER = 0, -1, -2, -3, -4, -5, -6
 TF_EPI_BIAS_GELU_ERF, TF_EPI_NONE_F32 = 0, 1
 TF_KIND_NAIVE, TF_KIND_MFMA_DIRECT, TF_KIND_MFMA_LDS, TF_KIND_MFMA_STREAM = 0, 1, 2, 3
+TF_KIND_VECMAT_NAIVE, TF_KIND_VECMAT_STREAM = 4, 5
+TF_OP_GEMM_EPILOGUE, TF_OP_BATCHED_VECMAT = 0, 1
 TF_BN_UNKNOWN, TF_BN_UNDERFILLED, TF_BN_HBM, TF_BN_MFMA, TF_BN_LDS_CONFLICT, TF_BN_OCCUPANCY, TF_BN_LATENCY = range(7)
 TF_DEC_CONTINUE, TF_DEC_ACCEPT, TF_DEC_FINISH = 0, 1, 2
 BOTTLENECK_NAMES = ["unknown", "underfilled", "hbm", "mfma", "lds_conflict", "occupancy", "latency"]
@@ -33,7 +35,7 @@ class _Struct(C.Structure):
 class ProblemDesc(_Struct):
     _fields_ = [("M", C.c_int32), ("N", C.c_int32), ("K", C.c_int32),
                 ("lda", C.c_int64), ("ldb", C.c_int64), ("ldy", C.c_int64),
-                ("epi", C.c_int32), ("device", C.c_int32)]
+                ("epi", C.c_int32), ("device", C.c_int32), ("op", C.c_int32), ("reserved", C.c_int32)]
 
 
 class VariantDesc(_Struct):
@@ -256,9 +258,15 @@ def report_set_counters(report: Report, hw: Hw, csv_path: str, kernel_substr: st
 class Problem:
     """tf_problem handle: one (M, N, K, strides, epilogue) instance of the tile kernel."""
 
-    def __init__(self, M, N, K, lda=None, ldb=None, ldy=None, epi=TF_EPI_BIAS_GELU_ERF, device=0):
-        self.desc = ProblemDesc(M, N, K, K if lda is None else lda, N if ldb is None else ldb,
-                                N if ldy is None else ldy, epi, device)
+    def __init__(self, M, N, K, lda=None, ldb=None, ldy=None, epi=TF_EPI_BIAS_GELU_ERF, device=0,
+                 op=TF_OP_GEMM_EPILOGUE):
+        if op == TF_OP_BATCHED_VECMAT:
+            # C[m, n] = sum_k A[m, k] B[m, n, k]: B rows are K long, the output is fp32
+            ldb_default, epi = K, TF_EPI_NONE_F32
+        else:
+            ldb_default = N
+        self.desc = ProblemDesc(M, N, K, K if lda is None else lda, ldb_default if ldb is None else ldb,
+                                N if ldy is None else ldy, epi, device, op, 0)
         self._h = C.c_void_p()
         _check(lib().tf_problem_create(C.byref(self.desc), C.byref(self._h)))
 
