@@ -116,6 +116,8 @@ typedef struct {
   int32_t direct_to_lds;   /* 1: global_load_lds staging; 0: via registers (allows a ragged K tail) */
   int32_t a_bypass_lds;    /* 1: A fragments are loaded from memory straight into MFMA operand registers, only B is
                               staged in LDS (one wave column per work-group) */
+  int32_t tail_cols;       /* > 0: column split. This kernel covers the first N - tail_cols columns in whole rounds of
+                              work-groups; a second launch with 128x128 tiles covers the last tail_cols columns */
   int32_t xcd_swizzle;     /* 1: work-group ids renumbered so that neighbouring tiles share an XCD L2 */
   int32_t group_m;         /* tile rows per group in the tile order */
   int32_t threads;         /* work-group size */

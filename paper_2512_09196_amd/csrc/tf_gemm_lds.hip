@@ -61,6 +61,10 @@ struct LdsCfg {
   static_assert(WK == 1 || (WK == 2 && TM % 2 == 0 && DIRECT && !ABYPASS), "k groups: two, each keeps half of the row blocks");
   static_assert(WK == 1 || RING_BYTES >= NWAVES * (TM / 2) * TN * 4096, "the accumulator exchange reuses the tile buffers");
   static constexpr int TM_OUT = TM / WK;                   // row blocks a wave writes out
+  // The in-kernel split-K reduction is only compiled for wave tiles of at most 64 accumulator
+  // registers: behind bigger ones its code makes the compiler spill, and the scratch memory
+  // that reserves per wave slows every launch of the kernel, split or not.
+  static constexpr bool FUSED_OK = TM * TN <= 4;
 };
 
 // Slot permutation of the 64-byte pieces of B row k (see header).
@@ -783,13 +787,14 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     // publish the partial tile; the last slice to arrive sums all slices in slice order
     const size_t slice = (size_t)p.M * p.N;
     float* wsk = p.ws + (size_t)tc.ks * slice;
-    if (!p.fused_reduce) {
+    if (!C::FUSED_OK || !p.fused_reduce) {
       // two-kernel split-K: plain stores; a reduce kernel launched behind this one sums the
       // slices in slice order and applies the epilogue (the kernel boundary orders the two)
       if (full) store_partial<C, true, false>(acc, wsk, p, wm0, wn0);
       else store_partial<C, false, false>(acc, wsk, p, wm0, wn0);
       return;
     }
+    if constexpr (C::FUSED_OK) {
     // Two ways to hand the partial tiles to the last slice:
     //  fused_reduce 1: device-scope (write-through) stores and loads, valid wherever the slices run;
     //  fused_reduce 2: plain stores and loads. The host offers it only when the tile order puts
@@ -836,6 +841,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       if (full) sum_partials<C, true, true>(acc, p, wm0, wn0);
       else sum_partials<C, false, true>(acc, p, wm0, wn0);
     }
+    }
   }
 
   // ---- epilogue: + bias, GELU, round to bf16 (or raw fp32 pre-activation)
@@ -863,7 +869,7 @@ static LdsKernelInfo make_info() {
   LdsKernelInfo k;
   k.bm = C::BM; k.bn = C::BN; k.bk = C::BK; k.waves_m = C::WM; k.waves_n = C::WN; k.waves_k = C::WK;
   k.stages = C::STAGES; k.direct_to_lds = C::DIRECT ? 1 : 0; k.a_bypass_lds = C::ABYPASS ? 1 : 0;
-  k.threads = C::THREADS; k.lds_bytes = C::LDS_BYTES;
+  k.threads = C::THREADS; k.lds_bytes = C::LDS_BYTES; k.fused_ok = C::FUSED_OK ? 1 : 0;
   k.func = (const void*)tf_gemm_lds_kernel<C>;
   k.launch = launch_lds<C>;
   return k;

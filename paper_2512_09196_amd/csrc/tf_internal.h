@@ -30,6 +30,7 @@ struct GemmParams {
 struct LdsKernelInfo {
   int bm, bn, bk, waves_m, waves_n, waves_k, stages, direct_to_lds, a_bypass_lds;
   int threads, lds_bytes;
+  int fused_ok;           // 1: the kernel contains the in-kernel split-K reduction (fused_reduce 1 and 2)
   const void* func;       // kernel symbol, for hipFuncGetAttributes / occupancy queries
   void (*launch)(const GemmParams&, dim3 grid, hipStream_t);
 };

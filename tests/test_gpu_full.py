@@ -137,3 +137,24 @@ def test_measured_peaks_are_plausible():
     print("measured: %.0f TFLOP/s bf16 MFMA, %.0f GB/s HBM read" % (mfma, hbm), flush=True)
     # below the published peaks, and not absurdly so
     assert 800.0 < mfma < 2516.6 and 3000.0 < hbm < 8000.0
+
+
+def test_no_kernel_reserves_much_scratch_memory():
+    # register spills outside the hot loop still make every wave reserve scratch memory, which slows
+    # each launch: the tile kernels must stay (almost) spill free
+    torch = gu.torch_mod()
+    M, N, K = 1024, 1024, 512
+    A, B, bias = wl.make_custom(M, N, K, seed=3)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    seen = {}
+    with tf.Problem(M, N, K) as prob:
+        for v in prob.variants():
+            key = (v.kind, v.bm, v.bn, v.waves_m, v.waves_n, v.waves_k, v.stages, v.direct_to_lds, v.a_bypass_lds)
+            if v.kind not in (tf.TF_KIND_MFMA_LDS, tf.TF_KIND_MFMA_STREAM) or key in seen or v.split_k > 1:
+                continue
+            r = prob.profile(v.id, dA, dB, dbias, Y, warmup=0, iters=1, launches_per_iter=1)
+            seen[key] = r.spill_bytes
+            limit = 1100 if v.a_bypass_lds else 128
+            assert r.spill_bytes <= limit, "%s reserves %d bytes of scratch per lane" % (v.name.decode(), r.spill_bytes)
+    assert len(seen) >= 15
