@@ -58,6 +58,10 @@ def _load():
             lib.tfo_batched_vecmat.argtypes = [
                 ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long,
                 u16p, ctypes.c_long, f64p, f64p]
+            lib.tfo_batched_gemm_tn.restype = ctypes.c_int
+            lib.tfo_batched_gemm_tn.argtypes = [
+                ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long, ctypes.c_long,
+                u16p, ctypes.c_long, ctypes.c_long, f64p, f64p]
             lib.tfo_gemm_bias_gelu_at.restype = ctypes.c_int
             lib.tfo_gemm_bias_gelu_at.argtypes = [
                 ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long,
@@ -151,4 +155,23 @@ def batched_vecmat(A, B):
                                     _ptr(c, ctypes.c_double), _ptr(s, ctypes.c_double))
     if rc != 0:
         raise RuntimeError(f"tfo_batched_vecmat failed with {rc}")
+    return c, s
+
+
+def batched_gemm_tn(A, B):
+    """C[b, m, n] = sum_k A[b, k, m] B[b, k, n] (the paper's Case Study 3, dB = dO^T A) in double, and S = sum |a b|.
+
+    A: uint16 [batch, K, M], B: uint16 [batch, K, N], bf16 bit patterns. Returns (C, S), float64 [batch, M, N]."""
+    A, B = _u16(A, "A"), _u16(B, "B")
+    if A.ndim != 3 or B.ndim != 3 or A.shape[0] != B.shape[0] or A.shape[1] != B.shape[1]:
+        raise ValueError(f"shape mismatch A{A.shape} B{B.shape}")
+    batch, K, M = A.shape
+    N = B.shape[2]
+    c = np.empty((batch, M, N), np.float64)
+    s = np.empty((batch, M, N), np.float64)
+    rc = _load().tfo_batched_gemm_tn(batch, M, N, K, _ptr(A, ctypes.c_uint16), M, K * M,
+                                     _ptr(B, ctypes.c_uint16), N, K * N,
+                                     _ptr(c, ctypes.c_double), _ptr(s, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError(f"tfo_batched_gemm_tn failed with {rc}")
     return c, s

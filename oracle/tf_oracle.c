@@ -1,6 +1,7 @@
 /*
- * CPU oracle for the fused tile kernel  Y = GELU_erf(A.B + bias), and (last function of the
- * file) for the batched vector-matrix product of the paper's Case Study 2.
+ * CPU oracle for the fused tile kernel  Y = GELU_erf(A.B + bias), and (last two functions of
+ * the file) for the batched vector-matrix product of the paper's Case Study 2 and the batched
+ * transposed-operand product of its Case Study 3.
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
  * GPU kernels are checked against.  It is single-threaded, has no blocking,
@@ -168,6 +169,48 @@ int tfo_batched_vecmat(int M, int N, int K,
             }
             C[(size_t)m * (size_t)N + (size_t)n] = acc;
             if (S) S[(size_t)m * (size_t)N + (size_t)n] = abs_acc;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Batched product with the first operand given transposed, the gradient term of the paper's
+ * Case Study 3 (dB = dO^T A, one product per chunk):
+ *     C[b][m][n] = sum_{k=0}^{K-1} A[b][k][m] * B[b][k][n]
+ * A[b] is [K][lda] (lda >= M, m contiguous), B[b] is [K][ldb] (ldb >= N), consecutive batch
+ * items stride_a resp. stride_b elements apart; all bf16 bit patterns. C and S (sum |a b|, may
+ * be NULL) are dense [batch][M][N] doubles. Four nested loops, k ascending, sums in double.
+ * Pinned by tests/test_oracle_bgemm.py: exact rational arithmetic, selector matrices that copy
+ * single rows of B, integer operands against an int64 contraction, the one-item case against a
+ * library matrix product of the explicitly transposed operand, power-of-two scaling, batch
+ * independence.
+ */
+int tfo_batched_gemm_tn(int batch, int M, int N, int K,
+                        const uint16_t *A, long lda, long stride_a,
+                        const uint16_t *B, long ldb, long stride_b,
+                        double *C, double *S)
+{
+    if (batch < 0 || M < 0 || N < 0 || K < 0) return -1;
+    if (lda < M || ldb < N) return -1;
+    if (batch > 0 && M > 0 && N > 0 && !C) return -1;
+    if (batch > 0 && M > 0 && N > 0 && K > 0 && (!A || !B)) return -1;
+    for (int b = 0; b < batch; ++b) {
+        const uint16_t *Ab = A + (size_t)b * (size_t)stride_a;
+        const uint16_t *Bb = B + (size_t)b * (size_t)stride_b;
+        for (int m = 0; m < M; ++m) {
+            for (int n = 0; n < N; ++n) {
+                double acc = 0.0, abs_acc = 0.0;
+                for (int k = 0; k < K; ++k) {
+                    const double p = tfo_bf16_to_double(Ab[(size_t)k * (size_t)lda + (size_t)m]) *
+                                     tfo_bf16_to_double(Bb[(size_t)k * (size_t)ldb + (size_t)n]);
+                    acc += p;
+                    abs_acc += fabs(p);
+                }
+                const size_t o = ((size_t)b * (size_t)M + (size_t)m) * (size_t)N + (size_t)n;
+                C[o] = acc;
+                if (S) S[o] = abs_acc;
+            }
         }
     }
     return 0;

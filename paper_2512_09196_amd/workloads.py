@@ -197,3 +197,38 @@ def make_vecmat(M, N, K, seed):
     A = normal_bf16(seed, 0, (M, K), 1.0)
     B = uniform_bf16(seed, 1, (M, N, K), max(K, 1) ** -0.5)
     return A, B
+
+
+# ---- batched product with a transposed first operand (the paper's Case Study 3, dB = dO^T A):
+# C[b, m, n] = sum_k A[b, k, m] B[b, k, n], one product per (batch, chunk) item, k = position in the chunk.
+# The paper gives no shapes; T1 is the small ragged case, T2 has the flops of the 2048^3 GEMM.
+@dataclass(frozen=True)
+class BatchedGemmWorkload:
+    name: str
+    batch: int
+    M: int
+    N: int
+    K: int
+    seed: int
+
+    @property
+    def flops(self) -> int:
+        return 2 * self.batch * self.M * self.N * self.K
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        """A and B read once (bf16), C written once (fp32)."""
+        return self.batch * (2 * self.K * (self.M + self.N) + 4 * self.M * self.N)
+
+
+BGEMM_WORKLOADS = {
+    "T1": BatchedGemmWorkload("T1", 3, 136, 200, 128, 20),
+    "T2": BatchedGemmWorkload("T2", 32, 1024, 1024, 256, 21),
+}
+
+
+def make_bgemm(batch, M, N, K, seed):
+    """(A[batch,K,M], B[batch,K,N]) ~ N(0,1) resp. uniform[-1,1)/sqrt(K), as uint16 bf16 bit patterns."""
+    A = normal_bf16(seed, 0, (batch, K, M), 1.0)
+    B = uniform_bf16(seed, 1, (batch, K, N), max(K, 1) ** -0.5)
+    return A, B
