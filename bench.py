@@ -72,13 +72,29 @@ def cpu_baseline_vecmat(w, A, B, budget_s=12.0):
             "sample": "first %d of %d matrices of %s (%.2f GMAC) in %.2f s" % (rows, w.M, w.name, flops / 2e9, dt)}
 
 
+def cpu_baseline_bgemm(w, A, B, budget_s=12.0):
+    """The batched transposed-operand oracle as it stands, single thread, on the first items of the batch."""
+    from oracle import gemm_oracle as orc
+    t0 = time.perf_counter()
+    orc.batched_gemm_tn(A[:1, :, :64], B[:1])
+    dt = (time.perf_counter() - t0) * w.M / 64.0
+    items = int(max(1, min(w.batch, budget_s / max(dt, 1e-6))))
+    t0 = time.perf_counter()
+    orc.batched_gemm_tn(A[:items], B[:items])
+    dt = time.perf_counter() - t0
+    flops = 2.0 * items * w.M * w.N * w.K
+    return {"value": flops / dt * 1e-12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d of %d items of %s (%.2f GMAC) in %.2f s" % (items, w.batch, w.name, flops / 2e9, dt)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "V1", "V2"],
-                    help="C1..C5: Y = GELU_erf(A.B + bias); V1, V2: batched vector-matrix product C[m,n] = sum_k A[m,k] B[m,n,k]")
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "V1", "V2", "T1", "T2"],
+                    help="C1..C5: Y = GELU_erf(A.B + bias); V1, V2: batched vector-matrix product C[m,n] = sum_k A[m,k] B[m,n,k]; "
+                         "T1, T2: batched transposed-operand product C[b] = A[b]^T B[b]")
     ap.add_argument("--variant", default=None, help="time this variant instead of the loop's choice")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-tune", action="store_true", help="skip the loop (needs --variant)")
@@ -111,10 +127,15 @@ def main():
                           "bytes_read_per_launch": 2 * n, "bytes_written_per_launch": 2 * n}))
         return
     vecmat = args.workload.startswith("V")
-    w = wl.VECMAT_WORKLOADS[args.workload] if vecmat else wl.WORKLOADS[args.workload]
+    bgemm = args.workload.startswith("T")
+    w = (wl.VECMAT_WORKLOADS[args.workload] if vecmat else wl.BGEMM_WORKLOADS[args.workload] if bgemm
+         else wl.WORKLOADS[args.workload])
     log("generating %s (M=%d N=%d K=%d, seed %d)" % (w.name, w.M, w.N, w.K, w.seed))
     if vecmat:
         A, B = wl.make_vecmat(w.M, w.N, w.K, w.seed)
+        bias = None
+    elif bgemm:
+        A, B = wl.make_bgemm(w.batch, w.M, w.N, w.K, w.seed)
         bias = None
     else:
         A, B, bias = wl.make_inputs(w)
@@ -123,12 +144,17 @@ def main():
     log("buffer sets: %d x %.1f MB" % (nbuf, set_bytes / 1e6))
     dA = [torch.from_numpy(A.view(np.int16)).cuda() for _ in range(nbuf)]
     dB = [torch.from_numpy(B.view(np.int16)).cuda() for _ in range(nbuf)]
-    db = [None if vecmat else torch.from_numpy(bias.view(np.int16)).cuda() for _ in range(nbuf)]
-    dY = [torch.empty((w.M, w.N), dtype=torch.float32 if vecmat else torch.bfloat16, device="cuda") for _ in range(nbuf)]
+    nobias = vecmat or bgemm
+    db = [None if nobias else torch.from_numpy(bias.view(np.int16)).cuda() for _ in range(nbuf)]
+    yshape = (w.batch, w.M, w.N) if bgemm else (w.M, w.N)
+    dY = [torch.empty(yshape, dtype=torch.float32 if nobias else torch.bfloat16, device="cuda") for _ in range(nbuf)]
     stream = torch.cuda.current_stream()
-    bound_kind = "hbm" if vecmat else w.bound
+    bound_kind = "hbm" if nobias else w.bound      # T2: 179 flop/byte with the fp32 output counted, below the ridge
 
-    prob = tf.Problem(w.M, w.N, w.K, op=tf.TF_OP_BATCHED_VECMAT if vecmat else tf.TF_OP_GEMM_EPILOGUE)
+    if bgemm:
+        prob = tf.Problem(w.M, w.N, w.K, op=tf.TF_OP_BATCHED_GEMM_TN, batch=w.batch)
+    else:
+        prob = tf.Problem(w.M, w.N, w.K, op=tf.TF_OP_BATCHED_VECMAT if vecmat else tf.TF_OP_GEMM_EPILOGUE)
     variants = prob.variants()
     names = [v.name.decode() for v in variants]
     tune = None
@@ -163,7 +189,7 @@ def main():
     run = tf.lib().tf_variant_run
     sp = ctypes.c_void_p(stream.cuda_stream)
     argsets = [(prob._h, vid, ctypes.c_void_p(dA[j].data_ptr()), ctypes.c_void_p(dB[j].data_ptr()),
-                None if vecmat else ctypes.c_void_p(db[j].data_ptr()), ctypes.c_void_p(dY[j].data_ptr()), None, 0, sp)
+                None if nobias else ctypes.c_void_p(db[j].data_ptr()), ctypes.c_void_p(dY[j].data_ptr()), None, 0, sp)
                for j in range(nbuf)]
     prob.run(vid, dA[0], dB[0], db[0], dY[0], stream=stream)    # first use: workspace, attributes, errors raised
 
@@ -208,11 +234,12 @@ def main():
 
     out = {
         "metric": ("batched vector-matrix product TFLOP/s (C[m,n] = sum_k A[m,k] B[m,n,k], bf16 in, fp32 out)" if vecmat
+                   else "batched transposed-operand product TFLOP/s (C[b] = A[b]^T B[b], bf16 in, fp32 out)" if bgemm
                    else "GEMM+epilogue TFLOP/s (bf16 GELU_erf(A.B+bias), fp32 accumulate)"),
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if vecmat else "bf16", "data": "synthetic",
-        "config": {"workload": "%s: M=%d N=%d K=%d bf16, seed %d" % (w.name, w.M, w.N, w.K, w.seed),
+        "config": {"workload": "%s: %sM=%d N=%d K=%d bf16, seed %d" % (w.name, "batch=%d " % w.batch if bgemm else "", w.M, w.N, w.K, w.seed),
                    "variant": names[vid], "grid": v.grid, "split_k": v.split_k, "buffer_sets": nbuf},
         "pct_bf16_mfma_peak": 100.0 * tflops / BF16_PEAK_TFLOPS,
         "hbm_gbs_algorithmic": w.algorithmic_bytes / (ms_per_step * 1e-3) * 1e-9,
@@ -221,7 +248,8 @@ def main():
     }
     if not args.no_cpu:
         log("timing the CPU oracle on a bounded sample ...")
-        out["cpu_baseline"] = cpu_baseline_vecmat(w, A, B) if vecmat else cpu_baseline(w, A, B, bias)
+        out["cpu_baseline"] = (cpu_baseline_vecmat(w, A, B) if vecmat else cpu_baseline_bgemm(w, A, B) if bgemm
+                               else cpu_baseline(w, A, B, bias))
     else:
         out["cpu_baseline"] = None
     prob.close()

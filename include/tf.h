@@ -58,11 +58,13 @@ typedef enum {
   TF_KIND_MFMA_STREAM = 3,  /* skinny problems (M <= 32): B streamed once from memory into MFMA operand
                                registers, no LDS staging; the waves of a work-group split K            */
   TF_KIND_VECMAT_NAIVE = 4, /* TF_OP_BATCHED_VECMAT baseline: one thread per output, scalar loop over k */
-  TF_KIND_VECMAT_STREAM = 5 /* TF_OP_BATCHED_VECMAT: a wave per group of rows, k-contiguous 16-byte loads,
+  TF_KIND_VECMAT_STREAM = 5, /* TF_OP_BATCHED_VECMAT: a wave per group of rows, k-contiguous 16-byte loads,
                                lane-exchange reduction. Descriptor fields: bm = rows per wave, bk = 512,
                                stages = k chunks in flight per row, waves_k = waves per work-group,
                                group_m = work-groups per compute unit the grid is cut to (0 = one wave
                                per row group)                                                          */
+  TF_KIND_BGEMM_TN_NAIVE = 6 /* TF_OP_BATCHED_GEMM_TN baseline: one thread per output element (its tile kernels
+                               are TF_KIND_MFMA_LDS, see trans_a)                                       */
 } tf_kind;
 
 /* Bottleneck classes produced by tf_refine_hint (Sec. 3.3 "Targeted-Refinement-Hint":
@@ -82,10 +84,16 @@ typedef enum { TF_DEC_CONTINUE = 0, TF_DEC_ACCEPT = 1, TF_DEC_FINISH = 2 } tf_de
 /* The operation. */
 typedef enum {
   TF_OP_GEMM_EPILOGUE = 0,  /* Y = epilogue(A.B + bias): A [M][lda], B [K][ldb], bias [N], Y [M][ldy] */
-  TF_OP_BATCHED_VECMAT = 1  /* Case Study 2 of the paper (Sec. 5): C[m][n] = sum_k A[m][k] B[m][n][k].
+  TF_OP_BATCHED_VECMAT = 1, /* Case Study 2 of the paper (Sec. 5): C[m][n] = sum_k A[m][k] B[m][n][k].
                                A [M][lda] bf16 (lda >= K); B [M][N][ldb] bf16, k contiguous (ldb >= K),
                                matrix m starting N * ldb elements after matrix m - 1; Y = C as fp32
                                [M][ldy] (epi must be TF_EPI_NONE_F32); bias is not read (may be NULL) */
+  TF_OP_BATCHED_GEMM_TN = 2 /* Case Study 3 of the paper (Sec. 5), dB = dO^T A per chunk:
+                               C[b][m][n] = sum_k A[b][k][m] B[b][k][n], b < batch.
+                               A [batch][K][lda] bf16 with m contiguous (lda >= M), B [batch][K][ldb] bf16
+                               (ldb >= N), Y = C as fp32 [batch][M][ldy] (epi must be TF_EPI_NONE_F32);
+                               consecutive items are stride_a / stride_b / stride_y elements apart;
+                               bias is not read (may be NULL) */
 } tf_op;
 
 /* The problem: shapes and strides of one call of the tile kernel. */
@@ -95,7 +103,9 @@ typedef struct {
   int32_t epi;             /* tf_epilogue */
   int32_t device;          /* HIP device ordinal */
   int32_t op;              /* tf_op */
-  int32_t reserved;        /* zero */
+  int32_t batch;           /* TF_OP_BATCHED_GEMM_TN: number of items (>= 0); otherwise ignored */
+  int64_t stride_a, stride_b, stride_y;   /* TF_OP_BATCHED_GEMM_TN: elements between consecutive items
+                                             (>= K * lda, K * ldb, M * ldy); otherwise ignored */
 } tf_problem_desc;
 
 /* One member of the kernel family: the paper's "tiling/block shapes, num_warps, vectorization
@@ -116,6 +126,9 @@ typedef struct {
   int32_t direct_to_lds;   /* 1: global_load_lds staging; 0: via registers (allows a ragged K tail) */
   int32_t a_bypass_lds;    /* 1: A fragments are loaded from memory straight into MFMA operand registers, only B is
                               staged in LDS (one wave column per work-group) */
+  int32_t trans_a;         /* TF_OP_BATCHED_GEMM_TN, tile kernels: 1 = the A tile is staged as it lies in memory
+                              ([k][m]) and transposed by the LDS read; 0 = a separate pass first writes A^T
+                              into the workspace and the tile kernel reads that                        */
   int32_t tail_cols;       /* > 0: column split. This kernel covers the first N - tail_cols columns in whole rounds of
                               work-groups; a second launch with 128x128 tiles covers the last tail_cols columns */
   int32_t xcd_swizzle;     /* 1: work-group ids renumbered so that neighbouring tiles share an XCD L2 */

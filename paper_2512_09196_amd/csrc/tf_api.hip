@@ -106,11 +106,62 @@ void build_vecmat_family(tf_problem* p) {
   }
 }
 
+// C[b] = A[b]^T B[b]: the naive kernel; tile kernels that stage A as it lies in memory and transpose it in
+// the LDS read (trans_a = 1); and tile kernels behind a separate transposing pass (trans_a = 0).
+void build_bgemm_family(tf_problem* p) {
+  const tf_problem_desc& d = p->desc;
+  const int batch = std::max(d.batch, 0);
+  {
+    tf_variant_desc v;
+    memset(&v, 0, sizeof(v));
+    v.kind = TF_KIND_BGEMM_TN_NAIVE; v.bm = 4; v.bn = 64; v.bk = 1; v.waves_m = 4; v.waves_n = 1; v.waves_k = 1;
+    v.split_k = 1; v.threads = 256; v.group_m = 1;
+    v.grid = (int32_t)(cdivl(d.N, 64) * cdivl(d.M, 4) * std::max(batch, 1));
+    snprintf(v.name, sizeof(v.name), "bgemm_tn_naive_1elem_per_thread");
+    add_variant(p, v, VariantImpl{-1, 0, 0, 0, 0});
+  }
+  // tile kernels: direct staging only (K a multiple of 64), 16-byte chunks inside rows, 32-bit tile offsets
+  const bool aligned = batch > 0 && d.M >= 8 && d.N >= 8 && d.K >= 64 && d.K % 64 == 0 && d.M % 8 == 0 && d.N % 8 == 0 &&
+                       d.lda % 8 == 0 && d.ldb % 8 == 0 && d.ldy % 4 == 0 && d.stride_a % 8 == 0 && d.stride_b % 8 == 0 &&
+                       d.stride_y % 4 == 0 && cdivl(d.M, 4) <= 65535 &&
+                       (double)d.K * (double)d.lda * 2.0 < 4294967296.0 && (double)d.K * (double)d.ldb * 2.0 < 4294967296.0 &&
+                       (double)d.M * (double)d.K * 2.0 < 4294967296.0;
+  if (!aligned) return;
+  const tf::LdsKernelInfo* tab = tf::lds_kernel_table();
+  for (int pass = 0; pass < 2; ++pass) {          // 0: transposed staging, 1: separate transposing pass
+    for (int i = 0; i < tf::lds_kernel_count(); ++i) {
+      const tf::LdsKernelInfo& k = tab[i];
+      if (!k.direct_to_lds || k.a_bypass_lds || k.waves_k != 1) continue;
+      if (pass == 0 && !k.trans_a) continue;
+      if (pass == 1 && (k.trans_a || k.bm < 64 || k.bn < 64 || (k.bm == 128 && k.bn == 128 && k.waves_m * k.waves_n == 4 && k.stages == 2))) continue;
+      if (k.bm > 32 && k.bm / 2 >= d.M) continue;
+      if (k.bn > 64 && k.bn / 2 >= d.N) continue;
+      if (k.lds_bytes > p->hw.lds_bytes_per_cu) continue;
+      const long tm = cdivl(d.M, k.bm), tn = cdivl(d.N, k.bn);
+      if (tm * tn > 0x7fffffffL / 16) continue;
+      tf_variant_desc v;
+      memset(&v, 0, sizeof(v));
+      v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n; v.waves_k = 1;
+      v.stages = k.stages; v.split_k = 1; v.direct_to_lds = 1; v.trans_a = k.trans_a; v.xcd_swizzle = 1;
+      v.group_m = (int32_t)std::min<long>(tm, 8);
+      v.threads = k.threads; v.lds_bytes = k.lds_bytes;
+      v.grid = (int32_t)(tm * tn * batch);
+      v.workspace_bytes = k.trans_a ? 0 : (int64_t)batch * d.M * d.K * 2;
+      VariantImpl im;
+      im.lds_index = i; im.ktiles_per_split = (int)cdivl(d.K, 64); im.tiles_m = (int)tm; im.tiles_n = (int)tn; im.counter_bytes = 0;
+      snprintf(v.name, sizeof(v.name), "bgemm_%dx%dx%d_w%dx%d_s%d_%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n, k.stages,
+               k.trans_a ? "ldstrans" : "pretrans");
+      add_variant(p, v, im);
+    }
+  }
+}
+
 void build_family(tf_problem* p) {
   const tf_problem_desc& d = p->desc;
   p->family.clear();
   p->impl.clear();
   if (d.op == TF_OP_BATCHED_VECMAT) { build_vecmat_family(p); return; }
+  if (d.op == TF_OP_BATCHED_GEMM_TN) { build_bgemm_family(p); return; }
   {
     tf_variant_desc v;
     memset(&v, 0, sizeof(v));
@@ -141,6 +192,7 @@ void build_family(tf_problem* p) {
   const long ktiles = cdivl(d.K, 64);
   for (int i = 0; i < tf::lds_kernel_count(); ++i) {
     const tf::LdsKernelInfo& k = tab[i];
+    if (k.trans_a) continue;                               // kernels of the transposed-operand product
     if (k.direct_to_lds && d.K % 64 != 0) continue;        // no zero fill on the direct path
     if (k.bm > 32 && k.bm / 2 >= d.M) continue;            // tile more than twice the problem
     if (k.bn > 64 && k.bn / 2 >= d.N) continue;
@@ -222,7 +274,7 @@ void build_family(tf_problem* p) {
     int tail_index = -1;
     for (int i = 0; i < tf::lds_kernel_count(); ++i) {
       const tf::LdsKernelInfo& k = tab[i];
-      if (k.bm == 128 && k.bn == 128 && k.waves_m == 2 && k.waves_n == 4 && k.waves_k == 1 && k.stages == 3 && k.direct_to_lds) tail_index = i;
+      if (k.bm == 128 && k.bn == 128 && k.waves_m == 2 && k.waves_n == 4 && k.waves_k == 1 && k.stages == 3 && k.direct_to_lds && !k.trans_a) tail_index = i;
     }
     const size_t n_before = p->family.size();
     for (size_t i = 0; tail_index >= 0 && i < n_before; ++i) {
@@ -276,6 +328,15 @@ tf_status check_ptrs(const tf_problem* p, const tf_variant_desc& v, const void* 
     if ((uintptr_t)Y & 3u) return fail(TF_E_UNSUPPORTED, "Y must be 4-byte aligned");
     return TF_OK;
   }
+  if (d.op == TF_OP_BATCHED_GEMM_TN) {
+    if (d.batch == 0) return TF_OK;
+    if (!Y) return fail(TF_E_INVALID, "null Y pointer");
+    if (d.K > 0 && (!A || !B)) return fail(TF_E_INVALID, "null A or B pointer");
+    if (v.kind == TF_KIND_MFMA_LDS && (((uintptr_t)A | (uintptr_t)B | (uintptr_t)Y) & 15u))
+      return fail(TF_E_UNSUPPORTED, "variant %s needs 16-byte aligned A, B and Y", v.name);
+    if ((uintptr_t)Y & 3u) return fail(TF_E_UNSUPPORTED, "Y must be 4-byte aligned");
+    return TF_OK;
+  }
   if (!Y || !bias) return fail(TF_E_INVALID, "null Y or bias pointer");
   if (d.K > 0 && (!A || !B)) return fail(TF_E_INVALID, "null A or B pointer");
   if (v.kind == TF_KIND_MFMA_LDS || v.kind == TF_KIND_MFMA_STREAM) {
@@ -297,8 +358,46 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
   memset(&g, 0, sizeof(g));
   g.A = (const uint16_t*)A; g.B = (const uint16_t*)B; g.bias = (const uint16_t*)bias; g.Y = Y;
   g.M = d.M; g.N = d.N; g.K = d.K; g.lda = d.lda; g.ldb = d.ldb; g.ldy = d.ldy;
+  if (d.op == TF_OP_BATCHED_GEMM_TN) {
+    if (d.batch == 0) return TF_OK;
+    g.bias = nullptr;
+    g.stride_a = d.stride_a; g.stride_b = d.stride_b; g.stride_y = d.stride_y;
+  }
   g.epi = d.epi; g.split_k = v.split_k; g.fused_reduce = v.fused_reduce; g.group_m = v.group_m > 0 ? v.group_m : 1; g.xcd_swizzle = v.xcd_swizzle;
-  if (v.kind == TF_KIND_VECMAT_NAIVE) {
+  if (v.kind == TF_KIND_BGEMM_TN_NAIVE) {
+    if (cdivl(d.M, 4) > 65535) return fail(TF_E_UNSUPPORTED, "naive variant: M too large for the grid");
+    tf::launch_bgemm_tn_naive(g, d.batch, stream);
+  } else if (d.op == TF_OP_BATCHED_GEMM_TN) {
+    // tile kernels of the transposed-operand product: grid.y = batch items
+    const tf::LdsKernelInfo& k = tf::lds_kernel_table()[im.lds_index];
+    g.tiles_m = im.tiles_m; g.tiles_n = im.tiles_n; g.ktiles_per_split = im.ktiles_per_split;
+    if (!v.trans_a) {
+      // separate pass: A^T of every item into the workspace, which then is the A operand
+      if (!ws) {
+        if (p->own_ws_bytes < (size_t)v.workspace_bytes) {
+          if (p->own_ws) { (void)hipFree(p->own_ws); p->own_ws = nullptr; p->own_ws_bytes = 0; }
+          size_t need = 0;
+          for (const tf_variant_desc& f : p->family) need = std::max(need, (size_t)f.workspace_bytes);
+          if (hipMalloc(&p->own_ws, need) != hipSuccess) {
+            p->own_ws = nullptr;
+            return fail(TF_E_NOMEM, "cannot allocate %zu bytes for the transposed operand", need);
+          }
+          p->own_ws_bytes = need;
+        }
+        ws = p->own_ws; ws_bytes = p->own_ws_bytes;
+      }
+      if (ws_bytes < (size_t)v.workspace_bytes)
+        return fail(TF_E_UNSUPPORTED, "workspace of %zu bytes, variant %s needs %lld", ws_bytes, v.name, (long long)v.workspace_bytes);
+      if ((uintptr_t)ws & 255u) return fail(TF_E_UNSUPPORTED, "workspace must be 256-byte aligned");
+      tf::launch_transpose(g.A, (uint16_t*)ws, d.K, d.M, d.lda, d.stride_a, d.K, (long)d.M * d.K, d.batch, stream);
+      g.A = (const uint16_t*)ws; g.lda = d.K; g.stride_a = (long)d.M * d.K;
+    }
+    if (!p->attr_done[im.lds_index]) {
+      TF_HIP(hipFuncSetAttribute(k.func, hipFuncAttributeMaxDynamicSharedMemorySize, k.lds_bytes));
+      p->attr_done[im.lds_index] = 1;
+    }
+    k.launch(g, dim3((unsigned)(im.tiles_m * im.tiles_n), (unsigned)d.batch), stream);
+  } else if (v.kind == TF_KIND_VECMAT_NAIVE) {
     if (d.M > 65535) return fail(TF_E_UNSUPPORTED, "naive variant: M too large for the grid");
     tf::launch_vecmat_naive(g, stream);
   } else if (v.kind == TF_KIND_VECMAT_STREAM) {
@@ -378,7 +477,8 @@ void fill_static(tf_problem* p, int id, tf_report* r) {
   const tf_variant_desc& v = p->family[id];
   const void* func = nullptr;
   int dyn = 0;
-  if (v.kind == TF_KIND_VECMAT_NAIVE) func = tf::vecmat_naive_func();
+  if (v.kind == TF_KIND_BGEMM_TN_NAIVE) func = tf::bgemm_tn_naive_func();
+  else if (v.kind == TF_KIND_VECMAT_NAIVE) func = tf::vecmat_naive_func();
   else if (v.kind == TF_KIND_VECMAT_STREAM) func = tf::vecmat_kernel_table()[p->impl[id].lds_index].func;
   else if (v.kind == TF_KIND_NAIVE) func = tf::naive_func();
   else if (v.kind == TF_KIND_MFMA_DIRECT) func = tf::mfma_direct_func();
@@ -466,7 +566,12 @@ tf_status tune_profile(void* user, int32_t id, tf_report* out) {
     tf::launch_fill_u32(c->bad, 1, 0u, c->stream);
     const size_t total = (size_t)p->desc.M * p->desc.N;
     const unsigned blocks = (unsigned)((total + 255) / 256);
-    if (p->desc.epi == TF_EPI_NONE_F32)
+    if (p->desc.op == TF_OP_BATCHED_GEMM_TN) {
+      for (int b = 0; b < p->desc.batch; ++b)     // item by item: the items may lie apart
+        hipLaunchKernelGGL(compare_kernel<float>, dim3(blocks), dim3(256), 0, c->stream,
+                           (const float*)c->Y + (size_t)b * p->desc.stride_y, (const float*)c->yref + (size_t)b * p->desc.stride_y,
+                           (size_t)p->desc.M, p->desc.N, (long)p->desc.ldy, c->bad);
+    } else if (p->desc.epi == TF_EPI_NONE_F32)
       hipLaunchKernelGGL(compare_kernel<float>, dim3(blocks), dim3(256), 0, c->stream, (const float*)c->Y,
                          (const float*)c->yref, (size_t)p->desc.M, p->desc.N, (long)p->desc.ldy, c->bad);
     else
@@ -520,10 +625,18 @@ tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, cons
   };
   double t = 0.0;
   for (int w = 0; w < warmup && st == TF_OK; ++w) st = timed(1, &t);
+  // The variant loop (rot != null) times what a caller running the kernel continuously would see:
+  // clocks and memory settle over milliseconds, so the warm-up goes on until 3 ms have been
+  // spent and every timed batch lasts about 3 ms. Otherwise batches of about a millisecond, so
+  // that one launch's overhead does not dominate short kernels.
+  const double batch_us = rot ? 3000.0 : 1000.0;
+  if (st == TF_OK && rot) {
+    double spent = 0.0;
+    for (int w = 0; w < 4000 && spent < 3000.0 && st == TF_OK; ++w) { st = timed(1, &t); spent += t > 0.0 ? t : 1.0; }
+  }
   if (st == TF_OK && lpi == 0) {
     st = timed(1, &t);
-    // batches of about a millisecond, so that one launch's overhead does not dominate short kernels
-    lpi = t > 0.0 ? (int)ceil(1000.0 / t) : 1000;
+    lpi = t > 0.0 ? (int)ceil(batch_us / t) : 1000;
     lpi = std::max(1, std::min(lpi, 2000));
   }
   std::vector<double> ts;
@@ -543,9 +656,12 @@ tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, cons
   for (double x : ts) sum += x;
   out->t_mean_us = sum / ts.size();
   const tf_problem_desc& d = p->desc;
-  const double flops = 2.0 * d.M * (double)d.N * d.K;
+  const double items = d.op == TF_OP_BATCHED_GEMM_TN ? (double)d.batch : 1.0;
+  const double flops = 2.0 * d.M * (double)d.N * d.K * items;
   const double bytes = d.op == TF_OP_BATCHED_VECMAT
                            ? 2.0 * ((double)d.M * d.K + (double)d.M * d.N * d.K) + 4.0 * (double)d.M * d.N
+                       : d.op == TF_OP_BATCHED_GEMM_TN
+                           ? items * (2.0 * (double)d.K * ((double)d.M + d.N) + 4.0 * (double)d.M * d.N)
                            : 2.0 * ((double)d.M * d.K + (double)d.K * d.N + (double)d.M * d.N + d.N);
   out->arithmetic_intensity = bytes > 0 ? flops / bytes : 0.0;
   if (out->t_med_us > 0.0) {
@@ -668,11 +784,17 @@ extern "C" tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem**
   if (!desc || !out) return fail(TF_E_INVALID, "null argument");
   *out = nullptr;
   if (desc->M < 0 || desc->N < 0 || desc->K < 0) return fail(TF_E_INVALID, "negative dimension");
-  if (desc->op != TF_OP_GEMM_EPILOGUE && desc->op != TF_OP_BATCHED_VECMAT) return fail(TF_E_INVALID, "unknown operation %d", desc->op);
-  const bool vecmat = desc->op == TF_OP_BATCHED_VECMAT;
-  if (desc->lda < desc->K || desc->ldb < (vecmat ? desc->K : desc->N) || desc->ldy < desc->N)
+  if (desc->op != TF_OP_GEMM_EPILOGUE && desc->op != TF_OP_BATCHED_VECMAT && desc->op != TF_OP_BATCHED_GEMM_TN) return fail(TF_E_INVALID, "unknown operation %d", desc->op);
+  const bool vecmat = desc->op == TF_OP_BATCHED_VECMAT, bgemm = desc->op == TF_OP_BATCHED_GEMM_TN;
+  if (desc->lda < (bgemm ? desc->M : desc->K) || desc->ldb < (vecmat ? desc->K : desc->N) || desc->ldy < desc->N)
     return fail(TF_E_INVALID, "leading dimension smaller than the row length");
-  if (vecmat && desc->epi != TF_EPI_NONE_F32) return fail(TF_E_INVALID, "the batched vector-matrix product writes fp32 (TF_EPI_NONE_F32)");
+  if ((vecmat || bgemm) && desc->epi != TF_EPI_NONE_F32) return fail(TF_E_INVALID, "this operation writes fp32 (TF_EPI_NONE_F32)");
+  if (bgemm) {
+    if (desc->batch < 0 || desc->batch > 65535) return fail(TF_E_INVALID, "batch must be in 0 .. 65535");
+    if (desc->stride_a < (int64_t)desc->K * desc->lda || desc->stride_b < (int64_t)desc->K * desc->ldb ||
+        desc->stride_y < (int64_t)desc->M * desc->ldy)
+      return fail(TF_E_INVALID, "batch stride smaller than one item");
+  }
   if (desc->epi != TF_EPI_BIAS_GELU_ERF && desc->epi != TF_EPI_NONE_F32) return fail(TF_E_INVALID, "unknown epilogue %d", desc->epi);
   tf_problem* p = new (std::nothrow) tf_problem();
   if (!p) return fail(TF_E_NOMEM, "out of host memory");
@@ -822,17 +944,24 @@ extern "C" tf_status tf_tune(tf_problem* p, const void* A, const void* B, const 
   c.stream = (hipStream_t)hip_stream; c.parity = parity; c.parity_user = parity_user;
   const size_t esz = p->desc.epi == TF_EPI_NONE_F32 ? 4 : 2;
   c.ybytes = p->desc.M > 0 ? ((size_t)(p->desc.M - 1) * p->desc.ldy + p->desc.N) * esz : 0;
+  if (p->desc.op == TF_OP_BATCHED_GEMM_TN)
+    c.ybytes = p->desc.batch > 0 && p->desc.M > 0 ? c.ybytes + (size_t)(p->desc.batch - 1) * p->desc.stride_y * esz : 0;
   if (!parity) {
     if (hipMalloc(&c.yref, std::max<size_t>(c.ybytes, 16)) != hipSuccess) return fail(TF_E_NOMEM, "cannot allocate the reference output");
     if (hipMalloc((void**)&c.bad, 256) != hipSuccess) { (void)hipFree(c.yref); return fail(TF_E_NOMEM, "cannot allocate the mismatch counter"); }
   }
   Rotation rot;
-  if (th.cold_bytes > 0 && p->desc.M > 0 && p->desc.N > 0 && p->desc.K > 0) {
+  if (th.cold_bytes > 0 && p->desc.M > 0 && p->desc.N > 0 && p->desc.K > 0 &&
+      (p->desc.op != TF_OP_BATCHED_GEMM_TN || p->desc.batch > 0)) {
     const tf_problem_desc& d = p->desc;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-    const size_t araw = ((size_t)(d.M - 1) * d.lda + d.K) * 2;
-    const size_t braw = d.op == TF_OP_BATCHED_VECMAT ? (((size_t)d.M * d.N - 1) * d.ldb + d.K) * 2
-                                                     : ((size_t)(d.K - 1) * d.ldb + d.N) * 2;
+    size_t araw = ((size_t)(d.M - 1) * d.lda + d.K) * 2;
+    size_t braw = d.op == TF_OP_BATCHED_VECMAT ? (((size_t)d.M * d.N - 1) * d.ldb + d.K) * 2
+                                               : ((size_t)(d.K - 1) * d.ldb + d.N) * 2;
+    if (d.op == TF_OP_BATCHED_GEMM_TN) {
+      araw = ((size_t)(d.batch - 1) * d.stride_a + (size_t)(d.K - 1) * d.lda + d.M) * 2;
+      braw = ((size_t)(d.batch - 1) * d.stride_b + (size_t)(d.K - 1) * d.ldb + d.N) * 2;
+    }
     const size_t abytes = up(araw), bbytes = up(braw);
     const size_t ybytes = up(c.ybytes), set = abytes + bbytes + ybytes;
     const size_t n = std::min<size_t>((size_t)th.cold_bytes / set + 2, 256);

@@ -22,8 +22,15 @@
 
 namespace tf {
 
-template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool DIRECT_, bool ABYPASS_ = false, int WK_ = 1>
+template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool DIRECT_, bool ABYPASS_ = false, int WK_ = 1, bool TRANSA_ = false>
 struct LdsCfg {
+  // TRANSA: A is given transposed, [K][lda] with m contiguous (the dO^T A product of the paper's
+  // Case Study 3). Its tile is then staged exactly like the B tile, [64][BM] row-major with the
+  // same 64-byte piece swizzle, and its MFMA operands come from the transposing LDS read too:
+  // the loads from memory stay fully coalesced and nothing is transposed by ALU code or by a
+  // separate pass.
+  static constexpr bool TRANSA = TRANSA_;
+  static constexpr int A_ROW_BYTES = BM_ * 2, A_PIECES = A_ROW_BYTES / 64, A_ROWS_PER_INSTR = 1024 / A_ROW_BYTES;
   static constexpr int BM = BM_, BN = BN_, BK = 64, WM = WM_, WN = WN_, STAGES = STAGES_;
   // WK: wave groups along k. With WK = 2 a second set of WM x WN waves works on the same
   // BM x BN tile but takes the other half of every 64-wide K step; the two sets add their
@@ -59,6 +66,7 @@ struct LdsCfg {
   static_assert(BN == 32 || BN == 64 || BN == 128 || BN == 256, "B row must be 64, 128, 256 or 512 bytes");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
   static_assert(WK == 1 || (WK == 2 && TM % 2 == 0 && DIRECT && !ABYPASS), "k groups: two, each keeps half of the row blocks");
+  static_assert(!TRANSA || (DIRECT && !ABYPASS && (BM == 32 || BM == 64 || BM == 128 || BM == 256)), "transposed A: direct staging, A row of 64 to 512 bytes");
   static_assert(WK == 1 || RING_BYTES >= NWAVES * (TM / 2) * TN * 4096, "the accumulator exchange reuses the tile buffers");
   static constexpr int TM_OUT = TM / WK;                   // row blocks a wave writes out
   // The in-kernel split-K reduction is only compiled for wave tiles of at most 64 accumulator
@@ -92,14 +100,27 @@ struct TileLoader {
 #pragma unroll
     for (int q = 0; q < C::A_PER_WAVE; ++q) {
       const int ia = wave + C::NWAVES * q;
-      const int row = 8 * ia + (lane >> 3);
-      const int slot = lane & 7;
-      const int c = slot ^ ((row >> 1) & 7);
-      int m = m0 + row;
-      a_ok[q] = m < p.M;
-      if (m >= p.M) m = p.M - 1;
-      a_src[q] = ((unsigned)m * (unsigned)p.lda + 8u * c) * 2u;
-      a_k[q] = 8 * c;
+      if constexpr (C::TRANSA) {
+        // rows of the tile are k, columns m: the scheme of the B tile with m in place of n
+        constexpr int LPR = 64 / C::A_ROWS_PER_INSTR;
+        const int krow = C::A_ROWS_PER_INSTR * ia + lane / LPR;
+        const int s16 = lane % LPR;
+        const int piece = (s16 >> 2) ^ b_swz<C::A_PIECES>(krow);
+        int m = m0 + 32 * piece + 8 * (s16 & 3);
+        a_ok[q] = m < p.M;
+        if (m >= p.M) m = 0;
+        a_src[q] = ((unsigned)krow * (unsigned)p.lda + (unsigned)m) * 2u;
+        a_k[q] = krow;
+      } else {
+        const int row = 8 * ia + (lane >> 3);
+        const int slot = lane & 7;
+        const int c = slot ^ ((row >> 1) & 7);
+        int m = m0 + row;
+        a_ok[q] = m < p.M;
+        if (m >= p.M) m = p.M - 1;
+        a_src[q] = ((unsigned)m * (unsigned)p.lda + 8u * c) * 2u;
+        a_k[q] = 8 * c;
+      }
     }
 #pragma unroll
     for (int q = 0; q < C::B_PER_WAVE; ++q) {
@@ -332,8 +353,15 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[C::TM][C::TN], cons
 }
 
 template <class C>
-__global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParams p) {
+__global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParams p_in) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  // batched problems: blockIdx.y is the batch item, whose operands are a stride away
+  GemmParams p = p_in;
+  if (gridDim.y > 1) {
+    p.A += (size_t)blockIdx.y * p.stride_a;
+    p.B += (size_t)blockIdx.y * p.stride_b;
+    p.Y = (char*)p.Y + (size_t)blockIdx.y * p.stride_y * (p.epi == TF_EPI_NONE_F32 ? 4 : 2);
+  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_k = wave / (C::WM * C::WN), wave_mn = wave % (C::WM * C::WN);
   const int wave_m = wave_mn / C::WN, wave_n = wave_mn % C::WN;
@@ -355,6 +383,30 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) a_off[kk] = r * 128 + ((((2 * (wave_k * C::KS + kk) + g) & 7) ^ sw) << 4);   // kk < KS used
   }
+  int a_toff[C::TRANSA ? C::TM : 1];     // transposed A: offsets for the transposing read, as for B
+  if constexpr (C::TRANSA) {
+    const int b = lane >> 4, s = lane & 15;
+    const int krow = 8 * (b >> 1) + (s >> 2);
+    const int within = (16 * (b & 1) + 4 * (s & 3)) * 2;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) {
+      const int j = (wave_m * C::WTM) / 32 + i;
+      const int piece = j ^ b_swz<C::A_PIECES>(krow);
+      a_toff[i] = (krow + wave_k * C::KS * 16) * C::A_ROW_BYTES + piece * 64 + within;
+    }
+  }
+  // one A operand of k16-step kk (relative to the wave's first step), row block i
+  auto read_a = [&](const char* stage, int kk, int i) -> bf16x8 {
+    if constexpr (C::TRANSA) {
+      const char* ap = stage + a_toff[i] + (16 * kk) * C::A_ROW_BYTES;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(ap));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(ap + 4 * C::A_ROW_BYTES));
+      const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, v);
+    } else {
+      return *(const bf16x8*)(stage + a_off[kk] + i * 32 * 128);
+    }
+  };
   int b_off[C::TN];
   {
     const int b = lane >> 4, s = lane & 15;
@@ -386,7 +438,9 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       const int c = 128 * r + 2 * lane;                 // column inside the tile
       if (c < C::BN) {
         const int n = n0 + c;
-        if constexpr (C::DIRECT) {
+        if (p.bias == nullptr) {
+          *(unsigned*)(smem + C::BIAS_OFF + c * 2) = 0u;      // no bias: the epilogue adds zeros
+        } else if constexpr (C::DIRECT) {
           TileLoader<C>::gload_lds4(__builtin_amdgcn_readfirstlane((unsigned)(size_t)smem + C::BIAS_OFF + 256 * r),
                                     n < p.N ? (unsigned)n * 2u : 0u, p.bias);
         } else {
@@ -397,7 +451,8 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       }
     }
   }
-  const uint16_t* Ak = p.A + (long)kt_begin * C::BK;
+  const long a_step = C::TRANSA ? (long)C::BK * p.lda : (long)C::BK;     // one K tile further in A
+  const uint16_t* Ak = p.A + (long)kt_begin * a_step;
   const uint16_t* Bk = p.B + (long)kt_begin * C::BK * p.ldb;
   const long b_step = (long)C::BK * p.ldb;
 
@@ -411,7 +466,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   auto read_frags = [&](const char* stage, int kk, int set) {
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
-      af[set][i] = *(const bf16x8*)(stage + a_off[kk] + i * 32 * 128);
+      af[set][i] = read_a(stage, kk, i);
 #pragma unroll
     for (int t = 0; t < C::TN; ++t) {
       const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
@@ -459,7 +514,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       if (m >= p.M) m = p.M - 1;
       a_goff[i] = ((unsigned)m * (unsigned)p.lda + 8u * (lane >> 5)) * 2u;
     }
-    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * C::BK; };
+    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * a_step; };
     auto tile_b = [&](int t) { return Bk + (long)(t < last ? t : last) * b_step; };
     auto load_a = [&](u32x4 (&dst)[C::TM][4], const uint16_t* base) {
 #pragma unroll
@@ -550,14 +605,14 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     constexpr int PER_TILE = C::A_PER_WAVE + C::B_PER_WAVE;
     static_assert((D - 1) * PER_TILE < 64, "vmcnt range");
     const unsigned lds0 = (unsigned)(size_t)smem;
-    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * C::BK; };
+    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * a_step; };
     auto tile_b = [&](int t) { return Bk + (long)(t < last ? t : last) * b_step; };
     bf16x8 fa[2][C::KS][C::TM], fb[2][C::KS][C::TN];
     auto read_tile = [&](const char* stage, bf16x8 (&a)[C::KS][C::TM], bf16x8 (&b)[C::KS][C::TN]) {
 #pragma unroll
       for (int kk = 0; kk < C::KS; ++kk) {
 #pragma unroll
-        for (int i = 0; i < C::TM; ++i) a[kk][i] = *(const bf16x8*)(stage + a_off[kk] + i * 32 * 128);
+        for (int i = 0; i < C::TM; ++i) a[kk][i] = read_a(stage, kk, i);
 #pragma unroll
         for (int t = 0; t < C::TN; ++t) {
           const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
@@ -615,7 +670,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     constexpr int PER_TILE = C::A_PER_WAVE + C::B_PER_WAVE;   // transfers per wave per tile
     static_assert((D - 1) * PER_TILE < 64, "vmcnt range");
     const unsigned lds0 = (unsigned)(size_t)smem;
-    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * C::BK; };
+    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * a_step; };
     auto tile_b = [&](int t) { return Bk + (long)(t < last ? t : last) * b_step; };
     // A wave issues in order: a burst of transfers right after the barrier would hold back the
     // MFMAs behind it for as long as the load unit takes to accept the burst (the four waves of a
@@ -629,7 +684,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       const int nx = which == 1 ? C::A_PER_WAVE : C::B_PER_WAVE;
 #pragma unroll
       for (int x = 0; x < (NR > 8 ? NR : 8); ++x) {
-        if (x < C::TM) af[set][x] = *(const bf16x8*)(stage + a_off[kk] + x * 32 * 128);
+        if (x < C::TM) af[set][x] = read_a(stage, kk, x);
         else if (x < NR) {
           const int t = x - C::TM;
           const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
@@ -702,7 +757,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     const int kbase = kt_begin * C::BK;
     auto load_tile = [&](int t) {
       const int tt = t < last ? t : last;
-      ld.load_regs(Ak + (long)tt * C::BK, Bk + (long)tt * b_step, kbase + tt * C::BK, p.K, ra, rb);
+      ld.load_regs(Ak + (long)tt * a_step, Bk + (long)tt * b_step, kbase + tt * C::BK, p.K, ra, rb);
     };
     if (nkt > 0) {
       load_tile(0);
@@ -868,7 +923,7 @@ template <class C>
 static LdsKernelInfo make_info() {
   LdsKernelInfo k;
   k.bm = C::BM; k.bn = C::BN; k.bk = C::BK; k.waves_m = C::WM; k.waves_n = C::WN; k.waves_k = C::WK;
-  k.stages = C::STAGES; k.direct_to_lds = C::DIRECT ? 1 : 0; k.a_bypass_lds = C::ABYPASS ? 1 : 0;
+  k.stages = C::STAGES; k.direct_to_lds = C::DIRECT ? 1 : 0; k.a_bypass_lds = C::ABYPASS ? 1 : 0; k.trans_a = C::TRANSA ? 1 : 0;
   k.threads = C::THREADS; k.lds_bytes = C::LDS_BYTES; k.fused_ok = C::FUSED_OK ? 1 : 0;
   k.func = (const void*)tf_gemm_lds_kernel<C>;
   k.launch = launch_lds<C>;
@@ -899,6 +954,19 @@ using K256x256_ab = LdsCfg<256, 256, 4, 1, 2, true, true>;
 using K128x256_ab = LdsCfg<128, 256, 4, 1, 2, true, true>;
 using K128x128_k2a = LdsCfg<128, 128, 2, 2, 3, true, false, 2>;   // two k groups of 2x2 waves
 using K128x128_k2b = LdsCfg<128, 128, 2, 2, 4, true, false, 2>;
+// first operand transposed in memory ([K][M])
+using T128x128_w8  = LdsCfg<128, 128, 2, 4, 3, true, false, 1, true>;
+using T128x128_d3  = LdsCfg<128, 128, 2, 2, 3, true, false, 1, true>;
+using T128x128_d2  = LdsCfg<128, 128, 2, 2, 2, true, false, 1, true>;
+using T256x256_w8  = LdsCfg<256, 256, 4, 2, 2, true, false, 1, true>;
+using T256x128_d2  = LdsCfg<256, 128, 2, 2, 2, true, false, 1, true>;
+using T64x64_d3    = LdsCfg< 64,  64, 2, 2, 3, true, false, 1, true>;
+// two buffers only: short K (a chunk) means few K steps per tile, and several work-groups per CU
+// cover each other's start-up better than a deeper ring in one
+using T128x128_w8s2 = LdsCfg<128, 128, 2, 4, 2, true, false, 1, true>;
+using T128x64_d2   = LdsCfg<128,  64, 2, 2, 2, true, false, 1, true>;
+using T64x128_d2   = LdsCfg< 64, 128, 2, 2, 2, true, false, 1, true>;
+using T64x64_d2    = LdsCfg< 64,  64, 2, 2, 2, true, false, 1, true>;
 using K256x256_w8a = LdsCfg<256, 256, 2, 4, 2, true>;   // eight waves on the big tile: 128x64 or 64x128 per wave
 using K256x256_w8b = LdsCfg<256, 256, 4, 2, 2, true>;
 
@@ -911,6 +979,9 @@ static LdsKernelInfo g_table[] = {
     make_info<K32x256_d4>(),  make_info<K32x32_d4>(),   make_info<K32x32_d8>(),
     make_info<K128x128_w8a>(), make_info<K128x128_w8b>(), make_info<K128x128_w8c>(),
     make_info<K128x128_k2a>(), make_info<K128x128_k2b>(),
+    make_info<T128x128_w8>(), make_info<T128x128_d3>(), make_info<T128x128_d2>(), make_info<T256x256_w8>(),
+    make_info<T256x128_d2>(), make_info<T64x64_d3>(),
+    make_info<T128x128_w8s2>(), make_info<T128x64_d2>(), make_info<T64x128_d2>(), make_info<T64x64_d2>(),
     make_info<K256x256_w8a>(), make_info<K256x256_w8b>(),
 };
 

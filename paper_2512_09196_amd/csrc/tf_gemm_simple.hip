@@ -112,6 +112,47 @@ void launch_calib_read(const void* src, size_t bytes, unsigned* sink, int wgs, h
   hipLaunchKernelGGL(tf_calib_read_kernel, dim3((unsigned)wgs), dim3(256), 0, s, (const u32x4*)src, bytes / 16, sink);
 }
 
+// Batched product with the first operand transposed in memory (C[b] = A[b]^T B[b], A[b] = [K][lda]):
+// the baseline kernel, one thread per output element, scalar loop over k.
+__global__ void __launch_bounds__(256) tf_bgemm_tn_naive_kernel(const GemmParams p) {
+  const int n = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int m = blockIdx.y * 4 + (threadIdx.x >> 6);
+  if (m >= p.M || n >= p.N) return;
+  const uint16_t* a = p.A + (size_t)blockIdx.z * p.stride_a + m;
+  const uint16_t* b = p.B + (size_t)blockIdx.z * p.stride_b + n;
+  float acc = 0.0f;
+  for (int k = 0; k < p.K; ++k)
+    acc = __builtin_fmaf(bf16_bits_to_f32(a[(size_t)k * p.lda]), bf16_bits_to_f32(b[(size_t)k * p.ldb]), acc);
+  ((float*)p.Y)[(size_t)blockIdx.z * p.stride_y + (size_t)m * p.ldy + n] = acc;
+}
+
+// The separate-pass alternative to staging A transposed: At[b][m][k] = A[b][k][m], 64 x 64 tiles
+// through LDS (padded rows), reads and writes both coalesced.
+__global__ void __launch_bounds__(256) tf_transpose_kernel(const uint16_t* A, uint16_t* At, int K, int M, long lda,
+                                                           long stride_a, long ldt, long stride_t) {
+  __shared__ uint16_t tile[64][66];
+  const uint16_t* a = A + (size_t)blockIdx.z * stride_a;
+  uint16_t* t = At + (size_t)blockIdx.z * stride_t;
+  const int m0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+  const int c = threadIdx.x & 63, r0 = threadIdx.x >> 6;
+  for (int r = r0; r < 64; r += 4)
+    if (k0 + r < K && m0 + c < M) tile[r][c] = a[(size_t)(k0 + r) * lda + m0 + c];
+  __syncthreads();
+  for (int r = r0; r < 64; r += 4)
+    if (m0 + r < M && k0 + c < K) t[(size_t)(m0 + r) * ldt + k0 + c] = tile[c][r];
+}
+
+void launch_bgemm_tn_naive(const GemmParams& p, int batch, hipStream_t s) {
+  dim3 grid((p.N + 63) / 64, (p.M + 3) / 4, batch);
+  hipLaunchKernelGGL(tf_bgemm_tn_naive_kernel, grid, dim3(256), 0, s, p);
+}
+const void* bgemm_tn_naive_func() { return (const void*)tf_bgemm_tn_naive_kernel; }
+void launch_transpose(const uint16_t* A, uint16_t* At, int K, int M, long lda, long stride_a, long ldt, long stride_t,
+                      int batch, hipStream_t s) {
+  dim3 grid((M + 63) / 64, (K + 63) / 64, batch);
+  hipLaunchKernelGGL(tf_transpose_kernel, grid, dim3(256), 0, s, A, At, K, M, lda, stride_a, ldt, stride_t);
+}
+
 __global__ void tf_fill_u32_kernel(unsigned* p, size_t n, unsigned v) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

@@ -17,6 +17,7 @@ struct GemmParams {
   unsigned* counters;     // one 8-byte arrival counter per output tile, zero between launches
   int M, N, K;
   long lda, ldb, ldy;     // in elements
+  long stride_a, stride_b, stride_y;   // batched problems (grid.y = batch items): elements between consecutive items
   int tiles_m, tiles_n;
   int split_k;            // number of K slices
   int fused_reduce;       // split-K: 1 = the last slice to arrive reduces inside the GEMM kernel; 0 = a second kernel does
@@ -29,6 +30,7 @@ struct GemmParams {
 // One compiled kernel of the LDS-staged MFMA family.
 struct LdsKernelInfo {
   int bm, bn, bk, waves_m, waves_n, waves_k, stages, direct_to_lds, a_bypass_lds;
+  int trans_a;            // 1: A is [K][lda] with m contiguous (staged and read like the B tile)
   int threads, lds_bytes;
   int fused_ok;           // 1: the kernel contains the in-kernel split-K reduction (fused_reduce 1 and 2)
   const void* func;       // kernel symbol, for hipFuncGetAttributes / occupancy queries
@@ -63,6 +65,10 @@ const VecmatKernelInfo* vecmat_kernel_table();
 void launch_vecmat_naive(const GemmParams&, hipStream_t);
 const void* vecmat_naive_func();
 
+void launch_bgemm_tn_naive(const GemmParams&, int batch, hipStream_t);      // C[b] = A[b]^T B[b], one thread per element
+const void* bgemm_tn_naive_func();
+void launch_transpose(const uint16_t* A, uint16_t* At, int K, int M, long lda, long stride_a, long ldt, long stride_t,
+                      int batch, hipStream_t);                              // At[b][m][k] = A[b][k][m]
 void launch_naive(const GemmParams&, hipStream_t);
 void launch_mfma_direct(const GemmParams&, hipStream_t);
 const void* naive_func();

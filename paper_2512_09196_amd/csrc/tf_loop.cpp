@@ -116,6 +116,27 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   const double flops = 2.0 * pr->M * (double)pr->N * pr->K;
   const double bytes = 2.0 * ((double)pr->M * pr->K + (double)pr->K * pr->N + (double)pr->M * pr->N + pr->N);
   const double hbm_us = bytes / (hw->hbm_gbs_peak * 1e3);
+  if (pr->op == TF_OP_BATCHED_GEMM_TN) {
+    // C[b] = A[b]^T B[b]: the tile model on one item with the whole grid, an HBM floor that counts the
+    // fp32 output, and the transposing pass where the variant has one
+    const double items = pr->batch > 0 ? (double)pr->batch : 1.0;
+    const double tbytes = items * (2.0 * (double)pr->K * ((double)pr->M + pr->N) + 4.0 * (double)pr->M * pr->N);
+    const double floor_us = tbytes / (0.75 * hw->hbm_gbs_peak * 1e3);
+    if (v->kind == TF_KIND_BGEMM_TN_NAIVE) return items * 2.0 * pr->M * (double)pr->N * pr->K / (0.004 * hw->bf16_tflops_peak * 1e6) + 3.0;
+    tf_problem_desc one = *pr;
+    one.op = TF_OP_GEMM_EPILOGUE;
+    tf_variant_desc v1 = *v;
+    v1.trans_a = 0;
+    double us = fmax(tf_predict_us(&one, hw, &v1), floor_us + 4.0);
+    // with few K steps per tile a work-group is a short read - multiply - write sequence; alone on its CU
+    // it leaves memory idle while it multiplies and the matrix pipes idle while it writes (measured 1.4-1.6x)
+    const long slots_one = (long)hw->cus * tf_resident_wgs(hw, v);
+    long co = cdiv(v->grid, hw->cus);
+    if (co > slots_one / hw->cus) co = slots_one / hw->cus;
+    if (co < 2) us *= 1.5;
+    if (!v->trans_a) us += 3.0 + items * 4.0 * (double)pr->K * pr->M / (0.6 * hw->hbm_gbs_peak * 1e3);
+    return us;
+  }
   if (v->kind == TF_KIND_VECMAT_NAIVE || v->kind == TF_KIND_VECMAT_STREAM) {
     // C[m][n] = sum_k A[m][k] B[m][n][k]: B is read once; everything else is small
     const double vbytes = 2.0 * ((double)pr->M * pr->K + (double)pr->M * pr->N * pr->K) + 4.0 * (double)pr->M * pr->N;
@@ -197,14 +218,16 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   // per tile: pipeline fill (first tiles from memory), then bias + GELU + pack at about 22 VALU
   // issue slots per element, or the fp32 partial tile at 32 B/clk when a second kernel reduces
   const double fill = 2500.0 / (double)co_resident;
-  double tile_end = v->bm * (double)v->bn * 22.0 / 64.0;
+  // (the raw fp32 output has no activation to evaluate: 16-byte stores at about 64 B/clk)
+  double tile_end = pr->epi == TF_EPI_NONE_F32 ? v->bm * (double)v->bn * 4.0 / 64.0 : v->bm * (double)v->bn * 22.0 / 64.0;
   if (v->waves_k > 1) tile_end += v->bm * (double)v->bn * 4.0 * (1.0 / 85.0 + 1.0 / 256.0) / 2.0 * v->waves_k;   // accumulator exchange
   double reduce_us = 0.0, fused_tail_us = 0.0;
   const double mhz = hw->clock_mhz < 1650.0 ? hw->clock_mhz : 1650.0;
   if (v->split_k > 1) {
     if (v->fused_reduce == 2) {
       // partial tiles stay in the L2 the slices share: 16-byte stores and loads, one round of tickets
-      fused_tail_us = 1.5 + v->bm * (double)v->bn * 4.0 * (1.0 + v->split_k) / 64.0 / mhz;
+      // ... but the last slice of a tile still sums all slices and runs the epilogue alone, on one CU
+      fused_tail_us = 2.0 + v->bm * (double)v->bn * 4.0 * (1.0 + 2.0 * v->split_k) / 64.0 / mhz;
     } else if (v->fused_reduce) {
       // partial tiles go out and come back through device-scope scalar accesses at about
       // 2 B/clk, and the last slice of a tile reads all of them alone
