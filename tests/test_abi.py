@@ -94,6 +94,49 @@ def test_enumerate_respects_alignment_and_ragged_k():
         assert [v.kind for v in p.variants()] == [tf.TF_KIND_NAIVE]
 
 
+def test_enumerate_the_other_operations_without_gpu():
+    hw = tf.hw_nominal()
+    # batched vector-matrix product: naive first, then the streaming family at several grid sizes
+    with tf.Problem(32, 4096, 4096, op=tf.TF_OP_BATCHED_VECMAT) as p:
+        vs = p.variants()
+        assert p.desc.ldb == 4096 and p.desc.epi == tf.TF_EPI_NONE_F32
+        assert vs[0].kind == tf.TF_KIND_VECMAT_NAIVE
+        st = [v for v in vs if v.kind == tf.TF_KIND_VECMAT_STREAM]
+        assert len(st) >= 9 and all(v.workspace_bytes == 0 and v.lds_bytes == 0 for v in st)
+        for v in st:
+            groups = -(-4096 // v.bm) * 32
+            full = -(-groups // v.waves_k)
+            assert v.grid == (full if v.group_m == 0 else min(full, v.group_m * hw.cus))
+        pred = {v.name.decode(): tf.predict_us(p.desc, hw, v) for v in vs}
+        assert min(pred.values()) >= 2 * 32 * 4096 * 4096 / 8e12 * 1e6           # never below the HBM roof
+        assert pred["vecmat_naive_1elem_per_thread"] > 5 * min(pred.values())
+    with tf.Problem(4, 33, 1001, op=tf.TF_OP_BATCHED_VECMAT) as p:          # K not a multiple of 8
+        assert [v.kind for v in p.variants()] == [tf.TF_KIND_VECMAT_NAIVE]
+    # batched transposed-operand product: transposed staging and the separate-pass alternative
+    with tf.Problem(1024, 1024, 256, op=tf.TF_OP_BATCHED_GEMM_TN, batch=32) as p:
+        vs = p.variants()
+        assert p.desc.lda == 1024 and p.desc.stride_a == 256 * 1024 and p.desc.stride_y == 1024 * 1024
+        assert vs[0].kind == tf.TF_KIND_BGEMM_TN_NAIVE
+        tiles = [v for v in vs if v.kind == tf.TF_KIND_MFMA_LDS]
+        assert any(v.trans_a for v in tiles) and any(not v.trans_a for v in tiles)
+        for v in tiles:
+            assert v.split_k == 1 and v.direct_to_lds == 1
+            assert v.grid == -(-1024 // v.bm) * -(-1024 // v.bn) * 32
+            assert v.workspace_bytes == (0 if v.trans_a else 32 * 1024 * 256 * 2)
+        pred = {v.name.decode(): tf.predict_us(p.desc, hw, v) for v in vs}
+        best = min(pred, key=pred.get)
+        assert best.endswith("ldstrans")                                       # the extra pass is never predicted to pay
+    with tf.Problem(40, 24, 96, op=tf.TF_OP_BATCHED_GEMM_TN, batch=2) as p:  # K not a multiple of 64
+        assert [v.kind for v in p.variants()] == [tf.TF_KIND_BGEMM_TN_NAIVE]
+    # the GEMM never lists kernels of the transposed-operand product
+    with tf.Problem(2048, 2048, 2048) as p:
+        assert all(v.trans_a == 0 for v in p.variants())
+    for bad in (dict(ldb=8, op=tf.TF_OP_BATCHED_VECMAT), dict(lda=8, op=tf.TF_OP_BATCHED_GEMM_TN, batch=1),
+                dict(op=tf.TF_OP_BATCHED_GEMM_TN, batch=2, stride_b=10), dict(op=7)):
+        with pytest.raises(tf.TfError):
+            tf.Problem(16, 16, 64, **bad)
+
+
 def test_bad_problem_is_rejected():
     with pytest.raises(tf.TfError) as e:
         tf.Problem(-1, 8, 8)
