@@ -129,8 +129,6 @@ typedef struct {
   int32_t trans_a;         /* TF_OP_BATCHED_GEMM_TN, tile kernels: 1 = the A tile is staged as it lies in memory
                               ([k][m]) and transposed by the LDS read; 0 = a separate pass first writes A^T
                               into the workspace and the tile kernel reads that                        */
-  int32_t tail_cols;       /* > 0: column split. This kernel covers the first N - tail_cols columns in whole rounds of
-                              work-groups; a second launch with 128x128 tiles covers the last tail_cols columns */
   int32_t xcd_swizzle;     /* 1: work-group ids renumbered so that neighbouring tiles share an XCD L2 */
   int32_t group_m;         /* tile rows per group in the tile order */
   int32_t threads;         /* work-group size */

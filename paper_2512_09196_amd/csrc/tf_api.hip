@@ -35,9 +35,6 @@ struct VariantImpl {
   int ktiles_per_split;
   int tiles_m, tiles_n;
   size_t counter_bytes;   // leading part of the workspace
-  // column split (tail_cols > 0): the kernel above covers the first N - tail_cols columns in whole rounds of
-  // work-groups, a second launch of LDS kernel tail_index with smaller tiles covers the rest
-  int tail_index = -1, tail_cols = 0, tail_tiles_m = 0, tail_tiles_n = 0;
 };
 
 }  // namespace
@@ -267,42 +264,6 @@ void build_family(tf_problem* p) {
       }
     }
   }
-  // Column split for big tiles whose last round of work-groups is badly filled: the big tiles take
-  // the largest leading block of columns that fills whole rounds, a second launch with 128x128
-  // tiles (eight waves) takes the remaining columns, whose smaller work-groups quantise better.
-  {
-    int tail_index = -1;
-    for (int i = 0; i < tf::lds_kernel_count(); ++i) {
-      const tf::LdsKernelInfo& k = tab[i];
-      if (k.bm == 128 && k.bn == 128 && k.waves_m == 2 && k.waves_n == 4 && k.waves_k == 1 && k.stages == 3 && k.direct_to_lds && !k.trans_a) tail_index = i;
-    }
-    const size_t n_before = p->family.size();
-    for (size_t i = 0; tail_index >= 0 && i < n_before; ++i) {
-      const tf_variant_desc v0 = p->family[i];
-      const VariantImpl im0 = p->impl[i];
-      if (v0.kind != TF_KIND_MFMA_LDS || v0.split_k != 1 || !v0.direct_to_lds || v0.a_bypass_lds) continue;
-      if ((long)v0.bm * v0.bn < 256L * 256L) continue;
-      const long tiles = (long)im0.tiles_m * im0.tiles_n;
-      if (tiles <= cus || tiles % cus == 0) continue;
-      if ((double)(tiles % cus) / cus > 0.85) continue;             // the last round is nearly full anyway
-      long tn1 = 0;
-      for (long t = im0.tiles_n - 1; t >= 1; --t)
-        if ((im0.tiles_m * t) % cus == 0) { tn1 = t; break; }
-      if (tn1 == 0) continue;
-      const long n1 = tn1 * v0.bn, tail_cols = d.N - n1;
-      if (tail_cols < 128) continue;
-      tf_variant_desc v = v0;
-      VariantImpl im = im0;
-      im.tiles_n = (int)tn1;
-      im.tail_index = tail_index; im.tail_cols = (int)tail_cols;
-      im.tail_tiles_m = (int)cdivl(d.M, 128); im.tail_tiles_n = (int)cdivl(tail_cols, 128);
-      v.grid = (int32_t)(im.tiles_m * tn1);
-      v.tail_cols = (int32_t)tail_cols;
-      v.lds_bytes = std::max(v0.lds_bytes, tab[tail_index].lds_bytes);
-      snprintf(v.name, sizeof(v.name), "%.*s+tail", (int)sizeof(v.name) - 8, v0.name);
-      add_variant(p, v, im);
-    }
-  }
   // One counter area for the whole family, so that the partial sums of one variant never
   // land on the counters of another: [counters | partial sums].
   size_t maxc = 0;
@@ -447,24 +408,6 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
       p->attr_done[slot] = 1;
     }
     if (streaming) tf::stream_kernel_table()[im.lds_index].launch(g, dim3((unsigned)v.grid), stream);
-    else if (im.tail_cols > 0) {
-      // two launches: the leading columns with this kernel, the remaining ones with the tail kernel
-      const tf::LdsKernelInfo& tk = tf::lds_kernel_table()[im.tail_index];
-      if (!p->attr_done[im.tail_index]) {
-        TF_HIP(hipFuncSetAttribute(tk.func, hipFuncAttributeMaxDynamicSharedMemorySize, tk.lds_bytes));
-        p->attr_done[im.tail_index] = 1;
-      }
-      tf::GemmParams g1 = g, g2 = g;
-      const long n1 = (long)d.N - im.tail_cols;
-      g1.N = (int)n1;
-      tf::lds_kernel_table()[im.lds_index].launch(g1, dim3((unsigned)v.grid), stream);
-      g2.B = g.B + n1; g2.bias = g.bias + n1;
-      g2.Y = (char*)g.Y + (size_t)n1 * (d.epi == TF_EPI_NONE_F32 ? 4 : 2);
-      g2.N = im.tail_cols; g2.tiles_m = im.tail_tiles_m; g2.tiles_n = im.tail_tiles_n;
-      g2.ktiles_per_split = (int)cdivl(d.K, 64);
-      g2.group_m = std::min(im.tail_tiles_m, 8);
-      tk.launch(g2, dim3((unsigned)(im.tail_tiles_m * im.tail_tiles_n)), stream);
-    }
     else tf::lds_kernel_table()[im.lds_index].launch(g, dim3((unsigned)v.grid), stream);
     if (v.split_k > 1 && !v.fused_reduce) tf::launch_splitk_reduce(g, stream);
   }

@@ -174,19 +174,6 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
     if (v->split_k > 1) us += (v->fused_reduce == 2 ? 2.0 : (v->fused_reduce ? 5.5 : 4.5)) + 2.0 * v->split_k * 4.0 * pr->M * (double)pr->N / (hw->hbm_gbs_peak * 1e3);
     return us;
   }
-  if (v->tail_cols > 0 && v->tail_cols < pr->N) {
-    // column split: this kernel on the leading columns, then 128x128 tiles (2x4 waves, three buffers) on the rest
-    tf_problem_desc p1 = *pr, p2 = *pr;
-    p1.N = pr->N - v->tail_cols;
-    p2.N = v->tail_cols;
-    tf_variant_desc v1 = *v, v2 = *v;
-    v1.tail_cols = 0;
-    v2.tail_cols = 0;
-    v2.bm = 128; v2.bn = 128; v2.waves_m = 2; v2.waves_n = 4; v2.waves_k = 1; v2.stages = 3; v2.direct_to_lds = 1;
-    v2.a_bypass_lds = 0; v2.lds_bytes = 3 * 32768 + 512; v2.threads = 512;
-    v2.grid = (int32_t)(cdiv(pr->M, 128) * cdiv(p2.N, 128));
-    return tf_predict_us(&p1, hw, &v1) + tf_predict_us(&p2, hw, &v2) - 1.5;   // the second launch finds A in cache
-  }
   const int resident = tf_resident_wgs(hw, v);
   const long slots = (long)hw->cus * resident;
   const long ktiles = cdiv(cdiv(pr->K, 64), v->split_k);
