@@ -62,6 +62,8 @@ def _load():
             lib.tfo_batched_gemm_tn.argtypes = [
                 ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long, ctypes.c_long,
                 u16p, ctypes.c_long, ctypes.c_long, f64p, f64p]
+            lib.tfo_sin_f32.restype = ctypes.c_int
+            lib.tfo_sin_f32.argtypes = [ctypes.c_long, ctypes.POINTER(ctypes.c_float), f64p]
             lib.tfo_gemm_bias_gelu_at.restype = ctypes.c_int
             lib.tfo_gemm_bias_gelu_at.argtypes = [
                 ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long,
@@ -175,3 +177,15 @@ def batched_gemm_tn(A, B):
     if rc != 0:
         raise RuntimeError(f"tfo_batched_gemm_tn failed with {rc}")
     return c, s
+
+
+def sin_f32(x):
+    """y = sin(x) in double for binary32 inputs (the paper's Case Study 1). x: float32 array; returns float64."""
+    x = np.ascontiguousarray(x)
+    if x.dtype != np.float32 or x.ndim != 1:
+        raise ValueError("x must be a 1-D float32 array")
+    y = np.empty(x.shape[0], np.float64)
+    rc = _load().tfo_sin_f32(x.shape[0], _ptr(x, ctypes.c_float), _ptr(y, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError(f"tfo_sin_f32 failed with {rc}")
+    return y

@@ -1,7 +1,8 @@
 /*
  * CPU oracle for the fused tile kernel  Y = GELU_erf(A.B + bias), and (last two functions of
- * the file) for the batched vector-matrix product of the paper's Case Study 2 and the batched
- * transposed-operand product of its Case Study 3.
+ * the file but one) for the batched vector-matrix product of the paper's Case Study 2 and the
+ * batched transposed-operand product of its Case Study 3, and (last) for the element-wise sine of
+ * its Case Study 1.
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
  * GPU kernels are checked against.  It is single-threaded, has no blocking,
@@ -213,5 +214,20 @@ int tfo_batched_gemm_tn(int batch, int M, int N, int K,
             }
         }
     }
+    return 0;
+}
+
+/*
+ * Element-wise sine of the paper's Case Study 1 (a kernel whose only tuning axis is the launch
+ * shape):  y[i] = sin(x[i]),  x given as IEEE binary32 values, evaluated in double by libm.
+ * Pinned by tests/test_oracle_sin.py: exact rational Taylor sums of the binary32 inputs, odd
+ * symmetry, exact zeros, the bound |y| <= 1, and multiples of pi rounded to binary32 against
+ * the first-order expansion around the true multiple.
+ */
+int tfo_sin_f32(long n, const float *x, double *y)
+{
+    if (n < 0) return -1;
+    if (n > 0 && (!x || !y)) return -1;
+    for (long i = 0; i < n; ++i) y[i] = sin((double)x[i]);
     return 0;
 }

@@ -232,3 +232,34 @@ def make_bgemm(batch, M, N, K, seed):
     A = normal_bf16(seed, 0, (batch, K, M), 1.0)
     B = uniform_bf16(seed, 1, (batch, K, N), max(K, 1) ** -0.5)
     return A, B
+
+
+# ---- element-wise sine (the paper's Case Study 1): y[i] = sin(x[i]), binary32 in and out.
+# The paper gives no size; E1 is the small ragged case, E2 moves 512 MB per launch.
+@dataclass(frozen=True)
+class SinWorkload:
+    name: str
+    n: int
+    seed: int
+
+    @property
+    def flops(self) -> int:
+        return self.n            # one function evaluation per element
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        return 8 * self.n        # x read, y written, 4 bytes each
+
+
+SIN_WORKLOADS = {"E1": SinWorkload("E1", 100003, 30), "E2": SinWorkload("E2", 1 << 26, 31)}
+
+
+def make_sin_input(n, seed, sigma=10.0):
+    """x ~ N(0, sigma) as float32 (same counter-based generator, rounded once from double)."""
+    out = np.empty(n, np.float32)
+    for s in range(0, n, _CHUNK):
+        c = min(_CHUNK, n - s)
+        u = unit_uniform(seed, 0, 2 * s, 2 * c)
+        u1, u2 = u[0::2], u[1::2]
+        out[s:s + c] = (sigma * np.sqrt(-2.0 * np.log1p(-u1)) * np.cos(2.0 * np.pi * u2)).astype(np.float32)
+    return out
