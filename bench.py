@@ -87,14 +87,28 @@ def cpu_baseline_bgemm(w, A, B, budget_s=12.0):
             "sample": "first %d of %d items of %s (%.2f GMAC) in %.2f s" % (items, w.batch, w.name, flops / 2e9, dt)}
 
 
+def cpu_baseline_sin(w, x, budget_s=12.0):
+    """The sine oracle as it stands, single thread, on the first elements."""
+    from oracle import gemm_oracle as orc
+    t0 = time.perf_counter()
+    orc.sin_f32(x[:1 << 20])
+    dt = time.perf_counter() - t0
+    n = int(max(1, min(w.n, (1 << 20) * budget_s / max(dt, 1e-6))))
+    t0 = time.perf_counter()
+    orc.sin_f32(x[:n])
+    dt = time.perf_counter() - t0
+    return {"value": n / dt * 1e-9, "unit": "Gelement/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d of %d elements of %s in %.2f s" % (n, w.n, w.name, dt)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "V1", "V2", "T1", "T2"],
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "V1", "V2", "T1", "T2", "E1", "E2"],
                     help="C1..C5: Y = GELU_erf(A.B + bias); V1, V2: batched vector-matrix product C[m,n] = sum_k A[m,k] B[m,n,k]; "
-                         "T1, T2: batched transposed-operand product C[b] = A[b]^T B[b]")
+                         "T1, T2: batched transposed-operand product C[b] = A[b]^T B[b]; E1, E2: element-wise sine y = sin(x), fp32")
     ap.add_argument("--variant", default=None, help="time this variant instead of the loop's choice")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-tune", action="store_true", help="skip the loop (needs --variant)")
@@ -128,10 +142,18 @@ def main():
         return
     vecmat = args.workload.startswith("V")
     bgemm = args.workload.startswith("T")
+    sin = args.workload.startswith("E")
     w = (wl.VECMAT_WORKLOADS[args.workload] if vecmat else wl.BGEMM_WORKLOADS[args.workload] if bgemm
-         else wl.WORKLOADS[args.workload])
-    log("generating %s (M=%d N=%d K=%d, seed %d)" % (w.name, w.M, w.N, w.K, w.seed))
-    if vecmat:
+         else wl.SIN_WORKLOADS[args.workload] if sin else wl.WORKLOADS[args.workload])
+    if sin:
+        log("generating %s (n=%d, seed %d)" % (w.name, w.n, w.seed))
+        A = wl.make_sin_input(w.n, w.seed).view(np.int16)       # carried as raw 16-bit halves like the other operands
+        B, bias = np.zeros(8, np.int16), None
+    else:
+        log("generating %s (M=%d N=%d K=%d, seed %d)" % (w.name, w.M, w.N, w.K, w.seed))
+    if sin:
+        pass
+    elif vecmat:
         A, B = wl.make_vecmat(w.M, w.N, w.K, w.seed)
         bias = None
     elif bgemm:
@@ -144,14 +166,16 @@ def main():
     log("buffer sets: %d x %.1f MB" % (nbuf, set_bytes / 1e6))
     dA = [torch.from_numpy(A.view(np.int16)).cuda() for _ in range(nbuf)]
     dB = [torch.from_numpy(B.view(np.int16)).cuda() for _ in range(nbuf)]
-    nobias = vecmat or bgemm
+    nobias = vecmat or bgemm or sin
     db = [None if nobias else torch.from_numpy(bias.view(np.int16)).cuda() for _ in range(nbuf)]
-    yshape = (w.batch, w.M, w.N) if bgemm else (w.M, w.N)
+    yshape = (w.batch, w.M, w.N) if bgemm else (w.n,) if sin else (w.M, w.N)
     dY = [torch.empty(yshape, dtype=torch.float32 if nobias else torch.bfloat16, device="cuda") for _ in range(nbuf)]
     stream = torch.cuda.current_stream()
     bound_kind = "hbm" if nobias else w.bound      # T2: 179 flop/byte with the fp32 output counted, below the ridge
 
-    if bgemm:
+    if sin:
+        prob = tf.Problem(1, w.n, 0, op=tf.TF_OP_ELEMENTWISE_SIN)
+    elif bgemm:
         prob = tf.Problem(w.M, w.N, w.K, op=tf.TF_OP_BATCHED_GEMM_TN, batch=w.batch)
     else:
         prob = tf.Problem(w.M, w.N, w.K, op=tf.TF_OP_BATCHED_VECMAT if vecmat else tf.TF_OP_GEMM_EPILOGUE)
@@ -232,14 +256,19 @@ def main():
     roof["measured_achievable"] = {"mfma_tflops": mfma_meas, "hbm_read_gbs": hbm_meas,
                                    "frac_of_measured": roof["achieved"] / (hbm_meas if bound_kind == "hbm" else mfma_meas)}
 
+    if sin:
+        workload = "%s: n=%d fp32, N(0, 10) inputs, seed %d" % (w.name, w.n, w.seed)
+    else:
+        workload = "%s: %sM=%d N=%d K=%d bf16, seed %d" % (w.name, "batch=%d " % w.batch if bgemm else "", w.M, w.N, w.K, w.seed)
     out = {
-        "metric": ("batched vector-matrix product TFLOP/s (C[m,n] = sum_k A[m,k] B[m,n,k], bf16 in, fp32 out)" if vecmat
+        "metric": ("element-wise sine Gelement/s (y = sin(x), fp32 in and out)" if sin else
+                   "batched vector-matrix product TFLOP/s (C[m,n] = sum_k A[m,k] B[m,n,k], bf16 in, fp32 out)" if vecmat
                    else "batched transposed-operand product TFLOP/s (C[b] = A[b]^T B[b], bf16 in, fp32 out)" if bgemm
                    else "GEMM+epilogue TFLOP/s (bf16 GELU_erf(A.B+bias), fp32 accumulate)"),
-        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": w.n / (ms_per_step * 1e-3) * 1e-9 if sin else tflops, "unit": "Gelement/s" if sin else "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if vecmat else "bf16", "data": "synthetic",
-        "config": {"workload": "%s: %sM=%d N=%d K=%d bf16, seed %d" % (w.name, "batch=%d " % w.batch if bgemm else "", w.M, w.N, w.K, w.seed),
+        "dtype": "f32" if vecmat or sin else "bf16", "data": "synthetic",
+        "config": {"workload": workload,
                    "variant": names[vid], "grid": v.grid, "split_k": v.split_k, "buffer_sets": nbuf},
         "pct_bf16_mfma_peak": 100.0 * tflops / BF16_PEAK_TFLOPS,
         "hbm_gbs_algorithmic": w.algorithmic_bytes / (ms_per_step * 1e-3) * 1e-9,
@@ -248,7 +277,7 @@ def main():
     }
     if not args.no_cpu:
         log("timing the CPU oracle on a bounded sample ...")
-        out["cpu_baseline"] = (cpu_baseline_vecmat(w, A, B) if vecmat else cpu_baseline_bgemm(w, A, B) if bgemm
+        out["cpu_baseline"] = (cpu_baseline_sin(w, A.view(np.float32)) if sin else cpu_baseline_vecmat(w, A, B) if vecmat else cpu_baseline_bgemm(w, A, B) if bgemm
                                else cpu_baseline(w, A, B, bias))
     else:
         out["cpu_baseline"] = None

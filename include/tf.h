@@ -63,8 +63,13 @@ typedef enum {
                                stages = k chunks in flight per row, waves_k = waves per work-group,
                                group_m = work-groups per compute unit the grid is cut to (0 = one wave
                                per row group)                                                          */
-  TF_KIND_BGEMM_TN_NAIVE = 6 /* TF_OP_BATCHED_GEMM_TN baseline: one thread per output element (its tile kernels
+  TF_KIND_BGEMM_TN_NAIVE = 6,/* TF_OP_BATCHED_GEMM_TN baseline: one thread per output element (its tile kernels
                                are TF_KIND_MFMA_LDS, see trans_a)                                       */
+  TF_KIND_SIN = 7            /* TF_OP_ELEMENTWISE_SIN: one arithmetic, many launch shapes. Descriptor fields: threads,
+                               bn = elements per work-group and pass (the paper's BLOCK_SIZE; variant 0 has 4),
+                               bk = consecutive elements per thread, stages = passes per work-group,
+                               group_m = work-groups per compute unit of a grid-stride launch (0 = one
+                               work-group per block of elements)                                        */
 } tf_kind;
 
 /* Bottleneck classes produced by tf_refine_hint (Sec. 3.3 "Targeted-Refinement-Hint":
@@ -88,12 +93,15 @@ typedef enum {
                                A [M][lda] bf16 (lda >= K); B [M][N][ldb] bf16, k contiguous (ldb >= K),
                                matrix m starting N * ldb elements after matrix m - 1; Y = C as fp32
                                [M][ldy] (epi must be TF_EPI_NONE_F32); bias is not read (may be NULL) */
-  TF_OP_BATCHED_GEMM_TN = 2 /* Case Study 3 of the paper (Sec. 5), dB = dO^T A per chunk:
+  TF_OP_BATCHED_GEMM_TN = 2,/* Case Study 3 of the paper (Sec. 5), dB = dO^T A per chunk:
                                C[b][m][n] = sum_k A[b][k][m] B[b][k][n], b < batch.
                                A [batch][K][lda] bf16 with m contiguous (lda >= M), B [batch][K][ldb] bf16
                                (ldb >= N), Y = C as fp32 [batch][M][ldy] (epi must be TF_EPI_NONE_F32);
                                consecutive items are stride_a / stride_b / stride_y elements apart;
                                bias is not read (may be NULL) */
+  TF_OP_ELEMENTWISE_SIN = 3 /* Case Study 1 of the paper (Sec. 5): Y[i] = sin(A[i]), i < N, A and Y fp32 (binary32)
+                               arrays of N elements (M = 1, K = 0; epi must be TF_EPI_NONE_F32); B and bias
+                               are not read (may be NULL)                                               */
 } tf_op;
 
 /* The problem: shapes and strides of one call of the tile kernel. */
@@ -113,7 +121,10 @@ typedef struct {
 typedef struct {
   int32_t id;              /* index for tf_variant_run; 0 is always the naive baseline */
   int32_t kind;            /* tf_kind */
-  int32_t bm, bn, bk;      /* macro tile */
+  int32_t bm, bn, bk;      /* macro tile; TF_KIND_SIN: bn = elements per work-group and pass of its grid stride (the
+                              case's BLOCK_SIZE), bk = consecutive elements per lane and access, stages = accesses
+                              per lane and pass, group_m = work-groups per CU of a grid-stride launch (0: one
+                              work-group per bn elements) */
   int32_t waves_m, waves_n;/* wave grid inside the work-group (64-lane waves) */
   int32_t waves_k;         /* wave groups along k: each takes 1/waves_k of every K step of the same tile, the groups
                               add their accumulators through LDS before the epilogue (1 = none) */
@@ -129,6 +140,7 @@ typedef struct {
   int32_t trans_a;         /* TF_OP_BATCHED_GEMM_TN, tile kernels: 1 = the A tile is staged as it lies in memory
                               ([k][m]) and transposed by the LDS read; 0 = a separate pass first writes A^T
                               into the workspace and the tile kernel reads that                        */
+  int32_t nontemporal;     /* TF_KIND_SIN: 1 = loads and stores marked non-temporal (each element is touched once) */
   int32_t xcd_swizzle;     /* 1: work-group ids renumbered so that neighbouring tiles share an XCD L2 */
   int32_t group_m;         /* tile rows per group in the tile order */
   int32_t threads;         /* work-group size */

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtf_gfx950.so")
-SOURCES = ["tf_gemm_lds.hip", "tf_gemm_stream.hip", "tf_vecmat.hip", "tf_gemm_simple.hip", "tf_api.hip", "tf_loop.cpp"]
+SOURCES = ["tf_gemm_lds.hip", "tf_gemm_stream.hip", "tf_vecmat.hip", "tf_sin.hip", "tf_gemm_simple.hip", "tf_api.hip", "tf_loop.cpp"]
 HEADERS = ["tf_internal.h", "tf_device.h", "tf_loop.h"]
 
 # -packed-fp32-ops off: hipcc must not form v_pk_*_f32 from scalar float code on this target.

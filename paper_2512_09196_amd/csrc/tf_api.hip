@@ -153,10 +153,47 @@ void build_bgemm_family(tf_problem* p) {
   }
 }
 
+// Y[i] = sin(A[i]): the same arithmetic at many launch shapes. Variant 0 is the baseline of the paper's case
+// (four elements per work-group); vector loads need 16-byte aligned pointers, checked at launch.
+void build_sin_family(tf_problem* p) {
+  const tf_problem_desc& d = p->desc;
+  const long n = d.N;
+  {
+    tf_variant_desc v;
+    memset(&v, 0, sizeof(v));
+    v.kind = TF_KIND_SIN; v.bm = 1; v.bn = 4; v.bk = 1; v.waves_m = 1; v.waves_n = 1; v.waves_k = 1; v.stages = 1;
+    v.split_k = 1; v.threads = 64;
+    v.grid = (int32_t)std::min<long>(cdivl(n, 4), 0x7fffffffL);
+    snprintf(v.name, sizeof(v.name), "sin_block4_t64");
+    add_variant(p, v, VariantImpl{-1, 0, 0, 0, 0});
+  }
+  if (n <= 0 || cdivl(n, 4) > 0x7fffffffL) return;
+  const int cus = p->hw.cus > 0 ? p->hw.cus : 256;
+  const tf::SinKernelInfo* tab = tf::sin_kernel_table();
+  for (int i = 0; i < tf::sin_kernel_count(); ++i) {
+    const tf::SinKernelInfo& k = tab[i];
+    const long full = cdivl(n, k.block);
+    static const int per_cu[] = {0, 8};          // 0: one work-group per block of elements; else a grid-stride launch
+    for (int g : per_cu) {
+      const long grid = g == 0 ? full : std::min<long>(full, (long)g * cus);
+      if (g != 0 && grid == full) continue;
+      tf_variant_desc v;
+      memset(&v, 0, sizeof(v));
+      v.kind = TF_KIND_SIN; v.bm = 1; v.bn = k.block; v.bk = k.vec; v.waves_m = k.threads / 64; v.waves_n = 1; v.waves_k = 1;
+      v.stages = k.iters; v.split_k = 1; v.threads = k.threads; v.group_m = g;
+      v.grid = (int32_t)grid;
+      v.nontemporal = k.nontemporal;
+      snprintf(v.name, sizeof(v.name), "sin_b%d_t%d_v%d_g%d%s", k.block, k.threads, k.vec, g, k.nontemporal ? "_nt" : "");
+      add_variant(p, v, VariantImpl{i, 0, 0, 0, 0});
+    }
+  }
+}
+
 void build_family(tf_problem* p) {
   const tf_problem_desc& d = p->desc;
   p->family.clear();
   p->impl.clear();
+  if (d.op == TF_OP_ELEMENTWISE_SIN) { build_sin_family(p); return; }
   if (d.op == TF_OP_BATCHED_VECMAT) { build_vecmat_family(p); return; }
   if (d.op == TF_OP_BATCHED_GEMM_TN) { build_bgemm_family(p); return; }
   {
@@ -281,6 +318,13 @@ tf_status check_ptrs(const tf_problem* p, const tf_variant_desc& v, const void* 
                      void* Y) {
   const tf_problem_desc& d = p->desc;
   if (d.M == 0 || d.N == 0) return TF_OK;
+  if (d.op == TF_OP_ELEMENTWISE_SIN) {
+    if (!A || !Y) return fail(TF_E_INVALID, "null A or Y pointer");
+    const unsigned need = v.bk > 1 ? (unsigned)(4 * v.bk - 1) : 3u;
+    if (((uintptr_t)A | (uintptr_t)Y) & need)
+      return fail(TF_E_UNSUPPORTED, "variant %s needs %u-byte aligned A and Y", v.name, need + 1);
+    return TF_OK;
+  }
   if (d.op == TF_OP_BATCHED_VECMAT) {
     if (!Y) return fail(TF_E_INVALID, "null Y pointer");
     if (d.K > 0 && (!A || !B)) return fail(TF_E_INVALID, "null A or B pointer");
@@ -325,7 +369,13 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
     g.stride_a = d.stride_a; g.stride_b = d.stride_b; g.stride_y = d.stride_y;
   }
   g.epi = d.epi; g.split_k = v.split_k; g.fused_reduce = v.fused_reduce; g.group_m = v.group_m > 0 ? v.group_m : 1; g.xcd_swizzle = v.xcd_swizzle;
-  if (v.kind == TF_KIND_BGEMM_TN_NAIVE) {
+  if (v.kind == TF_KIND_SIN) {
+    if (im.lds_index < 0) {
+      // grid size times work-group size must stay below 2^32
+      if (cdivl(d.N, 4) * 64 >= (1L << 32)) return fail(TF_E_UNSUPPORTED, "baseline sine variant: too many elements for one launch");
+      tf::launch_sin_block4((const float*)A, (float*)Y, (size_t)d.N, stream);
+    } else tf::sin_kernel_table()[im.lds_index].launch((const float*)A, (float*)Y, (size_t)d.N, (unsigned)v.grid, stream);
+  } else if (v.kind == TF_KIND_BGEMM_TN_NAIVE) {
     if (cdivl(d.M, 4) > 65535) return fail(TF_E_UNSUPPORTED, "naive variant: M too large for the grid");
     tf::launch_bgemm_tn_naive(g, d.batch, stream);
   } else if (d.op == TF_OP_BATCHED_GEMM_TN) {
@@ -420,7 +470,8 @@ void fill_static(tf_problem* p, int id, tf_report* r) {
   const tf_variant_desc& v = p->family[id];
   const void* func = nullptr;
   int dyn = 0;
-  if (v.kind == TF_KIND_BGEMM_TN_NAIVE) func = tf::bgemm_tn_naive_func();
+  if (v.kind == TF_KIND_SIN) func = p->impl[id].lds_index < 0 ? tf::sin_block4_func() : tf::sin_kernel_table()[p->impl[id].lds_index].func;
+  else if (v.kind == TF_KIND_BGEMM_TN_NAIVE) func = tf::bgemm_tn_naive_func();
   else if (v.kind == TF_KIND_VECMAT_NAIVE) func = tf::vecmat_naive_func();
   else if (v.kind == TF_KIND_VECMAT_STREAM) func = tf::vecmat_kernel_table()[p->impl[id].lds_index].func;
   else if (v.kind == TF_KIND_NAIVE) func = tf::naive_func();
@@ -600,9 +651,10 @@ tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, cons
   out->t_mean_us = sum / ts.size();
   const tf_problem_desc& d = p->desc;
   const double items = d.op == TF_OP_BATCHED_GEMM_TN ? (double)d.batch : 1.0;
-  const double flops = 2.0 * d.M * (double)d.N * d.K * items;
+  const double flops = d.op == TF_OP_ELEMENTWISE_SIN ? (double)d.N : 2.0 * d.M * (double)d.N * d.K * items;
   const double bytes = d.op == TF_OP_BATCHED_VECMAT
                            ? 2.0 * ((double)d.M * d.K + (double)d.M * d.N * d.K) + 4.0 * (double)d.M * d.N
+                       : d.op == TF_OP_ELEMENTWISE_SIN ? 8.0 * (double)d.N
                        : d.op == TF_OP_BATCHED_GEMM_TN
                            ? items * (2.0 * (double)d.K * ((double)d.M + d.N) + 4.0 * (double)d.M * d.N)
                            : 2.0 * ((double)d.M * d.K + (double)d.K * d.N + (double)d.M * d.N + d.N);
@@ -727,6 +779,21 @@ extern "C" tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem**
   if (!desc || !out) return fail(TF_E_INVALID, "null argument");
   *out = nullptr;
   if (desc->M < 0 || desc->N < 0 || desc->K < 0) return fail(TF_E_INVALID, "negative dimension");
+  if (desc->op == TF_OP_ELEMENTWISE_SIN) {
+    if (desc->N < 0) return fail(TF_E_INVALID, "negative element count");
+    if (desc->epi != TF_EPI_NONE_F32) return fail(TF_E_INVALID, "the element-wise sine writes fp32 (TF_EPI_NONE_F32)");
+    tf_problem* ps = new (std::nothrow) tf_problem();
+    if (!ps) return fail(TF_E_NOMEM, "out of host memory");
+    ps->desc = *desc;
+    ps->desc.M = 1; ps->desc.K = 0;
+    ps->own_ws = nullptr; ps->own_ws_bytes = 0; ps->zeroed_ws = nullptr; ps->zeroed_bytes = 0;
+    ps->have_hw = tf_hw_query(desc->device, &ps->hw) == TF_OK;
+    if (!ps->have_hw) { tf_hw_nominal(&ps->hw); g_err[0] = 0; }
+    ps->attr_done.assign(tf::lds_kernel_count() + tf::stream_kernel_count(), 0);
+    build_family(ps);
+    *out = ps;
+    return TF_OK;
+  }
   if (desc->op != TF_OP_GEMM_EPILOGUE && desc->op != TF_OP_BATCHED_VECMAT && desc->op != TF_OP_BATCHED_GEMM_TN) return fail(TF_E_INVALID, "unknown operation %d", desc->op);
   const bool vecmat = desc->op == TF_OP_BATCHED_VECMAT, bgemm = desc->op == TF_OP_BATCHED_GEMM_TN;
   if (desc->lda < (bgemm ? desc->M : desc->K) || desc->ldb < (vecmat ? desc->K : desc->N) || desc->ldy < desc->N)
@@ -894,13 +961,14 @@ extern "C" tf_status tf_tune(tf_problem* p, const void* A, const void* B, const 
     if (hipMalloc((void**)&c.bad, 256) != hipSuccess) { (void)hipFree(c.yref); return fail(TF_E_NOMEM, "cannot allocate the mismatch counter"); }
   }
   Rotation rot;
-  if (th.cold_bytes > 0 && p->desc.M > 0 && p->desc.N > 0 && p->desc.K > 0 &&
+  if (th.cold_bytes > 0 && p->desc.M > 0 && p->desc.N > 0 && (p->desc.K > 0 || p->desc.op == TF_OP_ELEMENTWISE_SIN) &&
       (p->desc.op != TF_OP_BATCHED_GEMM_TN || p->desc.batch > 0)) {
     const tf_problem_desc& d = p->desc;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     size_t araw = ((size_t)(d.M - 1) * d.lda + d.K) * 2;
     size_t braw = d.op == TF_OP_BATCHED_VECMAT ? (((size_t)d.M * d.N - 1) * d.ldb + d.K) * 2
                                                : ((size_t)(d.K - 1) * d.ldb + d.N) * 2;
+    if (d.op == TF_OP_ELEMENTWISE_SIN) { araw = (size_t)d.N * 4; braw = 0; }
     if (d.op == TF_OP_BATCHED_GEMM_TN) {
       araw = ((size_t)(d.batch - 1) * d.stride_a + (size_t)(d.K - 1) * d.lda + d.M) * 2;
       braw = ((size_t)(d.batch - 1) * d.stride_b + (size_t)(d.K - 1) * d.ldb + d.N) * 2;
@@ -917,7 +985,7 @@ extern "C" tf_status tf_tune(tf_problem* p, const void* A, const void* B, const 
     for (size_t i = 0; i < n && st == TF_OK; ++i) {
       char* a = (char*)rot.base + i * set;
       if (hipMemcpyAsync(a, A, araw, hipMemcpyDeviceToDevice, c.stream) != hipSuccess ||
-          hipMemcpyAsync(a + abytes, B, braw, hipMemcpyDeviceToDevice, c.stream) != hipSuccess)
+          (braw > 0 && hipMemcpyAsync(a + abytes, B, braw, hipMemcpyDeviceToDevice, c.stream) != hipSuccess))
         st = fail(TF_E_LAUNCH, "copying the operands failed");
       rot.A.push_back(a); rot.B.push_back(a + abytes); rot.Y.push_back(a + abytes + bbytes);
     }

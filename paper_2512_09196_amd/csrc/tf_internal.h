@@ -65,6 +65,17 @@ const VecmatKernelInfo* vecmat_kernel_table();
 void launch_vecmat_naive(const GemmParams&, hipStream_t);
 const void* vecmat_naive_func();
 
+// One compiled kernel of the element-wise sine: `block` = threads * vec * iters elements per work-group and pass.
+struct SinKernelInfo {
+  int threads, vec, iters, block, nontemporal;
+  const void* func;
+  void (*launch)(const float* x, float* y, size_t n, unsigned grid, hipStream_t);
+};
+int sin_kernel_count();
+const SinKernelInfo* sin_kernel_table();
+void launch_sin_block4(const float* x, float* y, size_t n, hipStream_t);     // the baseline: four elements per work-group
+const void* sin_block4_func();
+
 void launch_bgemm_tn_naive(const GemmParams&, int batch, hipStream_t);      // C[b] = A[b]^T B[b], one thread per element
 const void* bgemm_tn_naive_func();
 void launch_transpose(const uint16_t* A, uint16_t* At, int K, int M, long lda, long stride_a, long ldt, long stride_t,

@@ -116,6 +116,18 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   const double flops = 2.0 * pr->M * (double)pr->N * pr->K;
   const double bytes = 2.0 * ((double)pr->M * pr->K + (double)pr->K * pr->N + (double)pr->M * pr->N + pr->N);
   const double hbm_us = bytes / (hw->hbm_gbs_peak * 1e3);
+  if (v->kind == TF_KIND_SIN) {
+    // 8 bytes per element through HBM; a work-group costs about 0.45 us of one of the CU's slots to start and
+    // retire whatever it does (few elements per work-group: that is all there is), and one- or two-element
+    // accesses per lane reach about half the rate of 16-byte ones
+    const double floor_us = 8.0 * (double)pr->N / (0.75 * hw->hbm_gbs_peak * 1e3);
+    const double wg_us = (double)v->grid * 0.45 / ((double)hw->cus * 8.0);
+    const double width = v->bk >= 4 ? 1.0 : (v->bk == 2 ? 0.9 : 0.55);
+    // many passes per work-group hold many registers and leave few waves per SIMD; a grid-stride launch of
+    // few work-groups loses the hardware's own balancing of the tail
+    const double shape = 1.0 + 0.02 * (v->stages - 1) + (v->group_m ? 0.03 : 0.0) - (v->nontemporal ? 0.01 : 0.0);
+    return fmax(floor_us / width * shape, wg_us) + 3.0;
+  }
   if (pr->op == TF_OP_BATCHED_GEMM_TN) {
     // C[b] = A[b]^T B[b]: the tile model on one item with the whole grid, an HBM floor that counts the
     // fp32 output, and the transposing pass where the variant has one

@@ -16,8 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libtf_gfx950.so")
 TF_OK, TF_E_INVALID, TF_E_UNSUPPORTED, TF_E_LAUNCH, TF_E_NOMEM, TF_E_RANGE, TF_E_PROFILER = 0, -1, -2, -3, -4, -5, -6
 TF_EPI_BIAS_GELU_ERF, TF_EPI_NONE_F32 = 0, 1
 TF_KIND_NAIVE, TF_KIND_MFMA_DIRECT, TF_KIND_MFMA_LDS, TF_KIND_MFMA_STREAM = 0, 1, 2, 3
-TF_KIND_VECMAT_NAIVE, TF_KIND_VECMAT_STREAM, TF_KIND_BGEMM_TN_NAIVE = 4, 5, 6
-TF_OP_GEMM_EPILOGUE, TF_OP_BATCHED_VECMAT, TF_OP_BATCHED_GEMM_TN = 0, 1, 2
+TF_KIND_VECMAT_NAIVE, TF_KIND_VECMAT_STREAM, TF_KIND_BGEMM_TN_NAIVE, TF_KIND_SIN = 4, 5, 6, 7
+TF_OP_GEMM_EPILOGUE, TF_OP_BATCHED_VECMAT, TF_OP_BATCHED_GEMM_TN, TF_OP_ELEMENTWISE_SIN = 0, 1, 2, 3
 TF_BN_UNKNOWN, TF_BN_UNDERFILLED, TF_BN_HBM, TF_BN_MFMA, TF_BN_LDS_CONFLICT, TF_BN_OCCUPANCY, TF_BN_LATENCY = range(7)
 TF_DEC_CONTINUE, TF_DEC_ACCEPT, TF_DEC_FINISH = 0, 1, 2
 BOTTLENECK_NAMES = ["unknown", "underfilled", "hbm", "mfma", "lds_conflict", "occupancy", "latency"]
@@ -42,7 +42,7 @@ class ProblemDesc(_Struct):
 class VariantDesc(_Struct):
     _fields_ = [("id", C.c_int32), ("kind", C.c_int32), ("bm", C.c_int32), ("bn", C.c_int32), ("bk", C.c_int32),
                 ("waves_m", C.c_int32), ("waves_n", C.c_int32), ("waves_k", C.c_int32), ("stages", C.c_int32), ("split_k", C.c_int32), ("fused_reduce", C.c_int32),
-                ("direct_to_lds", C.c_int32), ("a_bypass_lds", C.c_int32), ("trans_a", C.c_int32), ("xcd_swizzle", C.c_int32), ("group_m", C.c_int32),
+                ("direct_to_lds", C.c_int32), ("a_bypass_lds", C.c_int32), ("trans_a", C.c_int32), ("nontemporal", C.c_int32), ("xcd_swizzle", C.c_int32), ("group_m", C.c_int32),
                 ("threads", C.c_int32), ("lds_bytes", C.c_int32), ("grid", C.c_int32),
                 ("workspace_bytes", C.c_int64), ("name", C.c_char * 64)]
 
@@ -265,6 +265,9 @@ class Problem:
         if op == TF_OP_BATCHED_VECMAT:
             # C[m, n] = sum_k A[m, k] B[m, n, k]: B rows are K long, the output is fp32
             ldb_default, epi = K, TF_EPI_NONE_F32
+        elif op == TF_OP_ELEMENTWISE_SIN:
+            # Y[i] = sin(A[i]), i < N: fp32 in and out
+            epi = TF_EPI_NONE_F32
         elif op == TF_OP_BATCHED_GEMM_TN:
             # C[b, m, n] = sum_k A[b, k, m] B[b, k, n]: A rows are M long, the output is fp32
             lda_default, epi = M, TF_EPI_NONE_F32

@@ -128,6 +128,25 @@ def test_enumerate_the_other_operations_without_gpu():
         assert best.endswith("ldstrans")                                       # the extra pass is never predicted to pay
     with tf.Problem(40, 24, 96, op=tf.TF_OP_BATCHED_GEMM_TN, batch=2) as p:  # K not a multiple of 64
         assert [v.kind for v in p.variants()] == [tf.TF_KIND_BGEMM_TN_NAIVE]
+    # element-wise sine: the four-element baseline first, then one kernel per launch shape, also as a grid-stride launch
+    n = 1 << 26
+    with tf.Problem(1, n, 0, op=tf.TF_OP_ELEMENTWISE_SIN) as p:
+        vs = p.variants()
+        assert p.desc.epi == tf.TF_EPI_NONE_F32 and p.desc.N == n
+        assert vs[0].name == b"sin_block4_t64" and vs[0].grid == n // 4 and all(v.kind == tf.TF_KIND_SIN for v in vs)
+        assert len(vs) >= 15 and len({v.name for v in vs}) == len(vs)
+        for v in vs[1:]:
+            assert v.bn == v.threads * v.bk * v.stages and v.workspace_bytes == 0 and v.lds_bytes == 0
+            full = -(-n // v.bn)
+            assert v.grid == (full if v.group_m == 0 else min(full, v.group_m * hw.cus))
+        pred = {v.name.decode(): tf.predict_us(p.desc, hw, v) for v in vs}
+        assert min(pred.values()) >= 8 * n / 8e12 * 1e6                           # never below the HBM roof
+        assert pred["sin_block4_t64"] > 20 * min(pred.values())
+        assert min(pred, key=pred.get).split("_")[3] == "v4"
+    with tf.Problem(1, 0, 0, op=tf.TF_OP_ELEMENTWISE_SIN) as p:
+        assert len(p.variants()) == 1
+    with pytest.raises(tf.TfError):
+        tf.Problem(1, -1, 0, op=tf.TF_OP_ELEMENTWISE_SIN)
     # the GEMM never lists kernels of the transposed-operand product
     with tf.Problem(2048, 2048, 2048) as p:
         assert all(v.trans_a == 0 for v in p.variants())
