@@ -73,6 +73,9 @@ struct LdsCfg {
   // registers: behind bigger ones its code makes the compiler spill, and the scratch memory
   // that reserves per wave slows every launch of the kernel, split or not.
   static constexpr bool FUSED_OK = TM * TN <= 4;
+  // 32-row tiles serve problems of few rows, where every B element is read by one work-group only: its
+  // loads are marked non-temporal
+  static constexpr bool B_NT = BM <= 32;
 };
 
 // Slot permutation of the 64-byte pieces of B row k (see header).
@@ -144,6 +147,7 @@ struct TileLoader {
   // that publishes a tile, so the compiler needs no knowledge of them (given the builtin, it
   // would make every later LDS read wait for all transfers in flight, including the tiles
   // prefetched for later steps). Nothing else in these kernels uses M0.
+  template <bool NT = false>
   __device__ __forceinline__ static void gload_lds16(unsigned lds_addr, unsigned voff, const void* base) {
     // the base is the same for every lane; say so, or it may be handed over in vector registers
     const unsigned long long b = (unsigned long long)base;
@@ -152,8 +156,12 @@ struct TileLoader {
     const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
     const unsigned long long sb = (unsigned long long)lo | ((unsigned long long)hi << 32);
     const void* sbase = (const void*)sb;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+    if constexpr (NT)      // non-temporal: data that no other work-group reads again need not stay in the caches
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                   :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+    else
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                   :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
   }
   // same, four bytes per lane (lane l lands at M0 + 4 l; lanes switched off transfer nothing)
   __device__ __forceinline__ static void gload_lds4(unsigned lds_addr, unsigned voff, const void* base) {
@@ -174,7 +182,7 @@ struct TileLoader {
 #pragma unroll
     for (int q = 0; q < C::B_PER_WAVE; ++q) {
       const int ib = wave + C::NWAVES * q;
-      gload_lds16(__builtin_amdgcn_readfirstlane(stage_lds + C::A_BYTES + ib * 1024), b_src[q], Bk);
+      gload_lds16<C::B_NT>(__builtin_amdgcn_readfirstlane(stage_lds + C::A_BYTES + ib * 1024), b_src[q], Bk);
     }
   }
 
@@ -184,7 +192,7 @@ struct TileLoader {
   }
   __device__ __forceinline__ void issue_b_one(int q, const uint16_t* Bk, unsigned stage_lds, int wave) const {
     const int ib = wave + C::NWAVES * q;
-    gload_lds16(__builtin_amdgcn_readfirstlane(stage_lds + C::A_BYTES + ib * 1024), b_src[q], Bk);
+    gload_lds16<C::B_NT>(__builtin_amdgcn_readfirstlane(stage_lds + C::A_BYTES + ib * 1024), b_src[q], Bk);
   }
   __device__ __forceinline__ void issue_a_all(const uint16_t* Ak, unsigned stage_lds, int wave) const {
 #pragma unroll
@@ -194,7 +202,7 @@ struct TileLoader {
 #pragma unroll
     for (int q = 0; q < C::B_PER_WAVE; ++q) {
       const int ib = wave + C::NWAVES * q;
-      gload_lds16(__builtin_amdgcn_readfirstlane(stage_lds + C::A_BYTES + ib * 1024), b_src[q], Bk);
+      gload_lds16<C::B_NT>(__builtin_amdgcn_readfirstlane(stage_lds + C::A_BYTES + ib * 1024), b_src[q], Bk);
     }
   }
 

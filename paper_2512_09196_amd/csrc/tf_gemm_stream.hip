@@ -89,7 +89,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_stream_kernel(const GemmPa
   auto load = [&](Block& blk, int rel) {       // K block wb0 + rel of this wave
     const char* bp = bptr + (size_t)rel * 32 * b_row;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) blk.b[e] = *(const bvec*)(bp + e * b_row);
+    for (int e = 0; e < 8; ++e) blk.b[e] = __builtin_nontemporal_load((const bvec*)(bp + e * b_row));   // read once by one wave
 #pragma unroll
     for (int i = 0; i < C::TMB; ++i) blk.a[i] = *(const u32x4*)(aptr[i] + (size_t)rel * 64);
   };

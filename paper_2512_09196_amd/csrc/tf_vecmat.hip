@@ -72,7 +72,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_vecmat_stream_kernel(const Gemm
         const size_t off = (size_t)(c0 + u) * 1024;
         av[u] = in ? *(const u32x4*)(arow + off) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int r = 0; r < C::R; ++r) bv[r][u] = in ? *(const u32x4*)(brow[r] + off) : u32x4{0u, 0u, 0u, 0u};
+        for (int r = 0; r < C::R; ++r) bv[r][u] = in ? __builtin_nontemporal_load((const u32x4*)(brow[r] + off)) : u32x4{0u, 0u, 0u, 0u};
       }
 #pragma unroll
       for (int u = 0; u < C::U; ++u)
