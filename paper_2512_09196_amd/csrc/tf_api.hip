@@ -368,6 +368,12 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
     g.bias = nullptr;
     g.stride_a = d.stride_a; g.stride_b = d.stride_b; g.stride_y = d.stride_y;
   }
+  {
+    const size_t esz = d.epi == TF_EPI_NONE_F32 ? 4 : 2;
+    g.y_vec16 = ((uintptr_t)Y % 16 == 0) && ((size_t)d.ldy * esz % 16 == 0) &&
+                (d.op != TF_OP_BATCHED_GEMM_TN || (size_t)d.stride_y * esz % 16 == 0);
+  }
+  g.slice_major = v.split_k > 1 && v.fused_reduce == 0 && v.kind == TF_KIND_MFMA_LDS;
   g.epi = d.epi; g.split_k = v.split_k; g.fused_reduce = v.fused_reduce; g.group_m = v.group_m > 0 ? v.group_m : 1; g.xcd_swizzle = v.xcd_swizzle;
   if (v.kind == TF_KIND_SIN) {
     if (im.lds_index < 0) {

@@ -81,8 +81,17 @@ __device__ __forceinline__ TileCoord map_tile(const GemmParams& p, int wg) {
     id = xcd * base + (xcd < rem ? xcd : rem) + local;
   }
   TileCoord c;
-  c.ks = id % p.split_k;          // slices of one tile are neighbours: they finish together
-  const int t = id / p.split_k;
+  int t;
+  if (p.slice_major) {
+    // all tiles of K slice 0, then all of slice 1, ...: work-groups that share an XCD's L2 work on the same K range
+    // of neighbouring tiles and re-use each other's A and B panels (the slices of a tile need not meet: a second
+    // kernel sums them)
+    c.ks = id / tiles;
+    t = id - c.ks * tiles;
+  } else {
+    c.ks = id % p.split_k;        // slices of one tile are neighbours: they finish together
+    t = id / p.split_k;
+  }
   const int gsz = p.group_m * p.tiles_n;
   const int g = t / gsz;
   const int first_m = g * p.group_m;

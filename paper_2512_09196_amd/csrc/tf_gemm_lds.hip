@@ -73,6 +73,11 @@ struct LdsCfg {
   // registers: behind bigger ones its code makes the compiler spill, and the scratch memory
   // that reserves per wave slows every launch of the kernel, split or not.
   static constexpr bool FUSED_OK = TM * TN <= 4;
+  // Output staging (see epilogue_staged): each pass moves 32 rows per wave row (and k group) through the tile
+  // ring, rows padded by 16 bytes; used for an output type when one pass fits into the ring.
+  static constexpr int ST_ROWS = 32 * WM * WK_;
+  // (not behind wave tiles of 256 accumulator registers: the extra code makes the compiler spill there)
+  static constexpr bool stage_ok(int esz) { return TM * TN <= 8 && ST_ROWS * (BN * esz + 16) <= RING_BYTES; }
   // 32-row tiles serve problems of few rows, where every B element is read by one work-group only: its
   // loads are marked non-temporal
   static constexpr bool B_NT = BM <= 32;
@@ -356,6 +361,60 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[C::TM][C::TN], cons
           }
         }
       }
+    }
+  }
+}
+
+// The same epilogue for whole tiles with 16-byte aligned output rows, with the stores coalesced through LDS.
+// Written straight from the accumulators, a store instruction touches 32 rows with 16 or 32 bytes each, and
+// the memory side handles every such piece as a request of its own: that, not the byte count, bounds the
+// write-back. Here the work-group lays 32 rows per wave row out in LDS (the tile ring is free by now),
+// and reads them back so that consecutive lanes hold consecutive 16-byte pieces of a row: a store
+// instruction then writes whole rows of the tile, 64 x 16 bytes contiguous per BN * esz bytes.
+// Every wave of the work-group must call it (barriers inside).
+template <class C, int EPI>
+__device__ __forceinline__ void epilogue_staged(const f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, char* smem, int m0,
+                                                int n0, int tid, int wave_m, int wave_n, int wave_k, int lane_m, int lane_g) {
+  constexpr int ESZ = EPI == TF_EPI_NONE_F32 ? 4 : 2;
+  constexpr int ROWB = C::BN * ESZ + 16;                 // staged row, padded: the 32 rows a store hits spread over the banks
+  constexpr int CPR = C::BN * ESZ / 16;                  // 16-byte pieces per row
+  constexpr int PER_THREAD = C::ST_ROWS * CPR / C::THREADS;
+  static_assert(C::ST_ROWS * CPR % C::THREADS == 0, "pieces divide over the threads");
+  const char* bias_lds = smem + C::BIAS_OFF + (wave_n * C::WTN + 4 * lane_g) * 2;
+  char* wr = smem + ((wave_m * C::WK + wave_k) * 32 + lane_m) * ROWB + (wave_n * C::WTN + 4 * lane_g) * ESZ;
+  wait_vmcnt<0>();          // no transfer into the ring is in flight any more (the clamped tail prefetches)
+  barrier_lds();            // and nobody reads tile fragments any more
+#pragma unroll
+  for (int i = 0; i < C::TM_OUT; ++i) {
+    if (i) barrier_lds();   // the previous pass has been read back
+#pragma unroll
+    for (int t = 0; t < C::TN; ++t)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const u32x2 braw = *(const u32x2*)(bias_lds + (32 * t + 8 * q) * 2);
+        const float z0 = acc[i][t][4 * q] + __builtin_bit_cast(float, braw[0] << 16);
+        const float z1 = acc[i][t][4 * q + 1] + __builtin_bit_cast(float, braw[0] & 0xffff0000u);
+        const float z2 = acc[i][t][4 * q + 2] + __builtin_bit_cast(float, braw[1] << 16);
+        const float z3 = acc[i][t][4 * q + 3] + __builtin_bit_cast(float, braw[1] & 0xffff0000u);
+        if (EPI == TF_EPI_NONE_F32) {
+          const f32x4 v = {z0, z1, z2, z3};
+          *(f32x4*)(wr + (32 * t + 8 * q) * 4) = v;
+        } else {
+          u32x2 o;
+          o[0] = pack_bf16x2(gelu_erf(z0), gelu_erf(z1));
+          o[1] = pack_bf16x2(gelu_erf(z2), gelu_erf(z3));
+          *(u32x2*)(wr + (32 * t + 8 * q) * 2) = o;
+        }
+      }
+    barrier_lds();
+#pragma unroll
+    for (int j = 0; j < PER_THREAD; ++j) {
+      const int c = tid + C::THREADS * j;
+      const int rs = c / CPR, cc = c % CPR;
+      const int g = rs >> 5;                               // wave row and k group the staged row came from
+      const int m = m0 + (g / C::WK) * C::WTM + (g % C::WK) * 32 * (C::TM / 2) + 32 * i + (rs & 31);
+      const u32x4 v = *(const u32x4*)(smem + rs * ROWB + cc * 16);
+      *(u32x4*)((char*)p.Y + ((size_t)m * p.ldy + n0) * ESZ + cc * 16) = v;
     }
   }
 }
@@ -913,11 +972,16 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     __syncthreads();
   }
   const char* bias_lds = smem + C::BIAS_OFF + (wave_n * C::WTN + 4 * lane_g) * 2;
+  const bool staged = full && p.y_vec16;      // the same for every wave of the work-group
   if (p.epi == TF_EPI_NONE_F32) {
-    if (full) epilogue<C, true, TF_EPI_NONE_F32>(acc, p, wm0, wn0, bias_lds);
+    if (C::stage_ok(4) && staged) {
+      if constexpr (C::stage_ok(4)) epilogue_staged<C, TF_EPI_NONE_F32>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g);
+    } else if (full) epilogue<C, true, TF_EPI_NONE_F32>(acc, p, wm0, wn0, bias_lds);
     else epilogue<C, false, TF_EPI_NONE_F32>(acc, p, wm0, wn0, bias_lds);
   } else {
-    if (full) epilogue<C, true, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0, bias_lds);
+    if (C::stage_ok(2) && staged) {
+      if constexpr (C::stage_ok(2)) epilogue_staged<C, TF_EPI_BIAS_GELU_ERF>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g);
+    } else if (full) epilogue<C, true, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0, bias_lds);
     else epilogue<C, false, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0, bias_lds);
   }
 }

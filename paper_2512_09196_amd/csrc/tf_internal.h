@@ -25,6 +25,8 @@ struct GemmParams {
   int epi;                // tf_epilogue
   int group_m;            // tile rows per L2 group in the tile order (>= 1)
   int xcd_swizzle;        // 1: remap work-group ids so that neighbouring tiles share an XCD
+  int slice_major;        // split-K tile order: 1 = slice by slice (two-kernel reduction), 0 = the slices of a tile side by side
+  int y_vec16;            // 1: every row of Y (of every batch item) starts on a 16-byte boundary
 };
 
 // One compiled kernel of the LDS-staged MFMA family.
