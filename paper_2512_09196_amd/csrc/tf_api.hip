@@ -455,6 +455,7 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
       }
       g.counters = (unsigned*)ws;
       g.ws = (float*)((char*)ws + im.counter_bytes);
+      g.ws_vec16 = ((uintptr_t)g.ws % 16 == 0) && (d.N % 4 == 0);
     }
     const bool streaming = v.kind == TF_KIND_MFMA_STREAM;
     const int slot = streaming ? tf::lds_kernel_count() + im.lds_index : im.lds_index;

@@ -371,10 +371,15 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[C::TM][C::TN], cons
 // write-back. Here the work-group lays 32 rows per wave row out in LDS (the tile ring is free by now),
 // and reads them back so that consecutive lanes hold consecutive 16-byte pieces of a row: a store
 // instruction then writes whole rows of the tile, 64 x 16 bytes contiguous per BN * esz bytes.
+// The lines go out complete, so the stores are marked non-temporal: nothing is left in the L2 for the
+// write-back at the end of the kernel. PARTIAL: the raw accumulators (no bias) go to `dst`, a split-K slice of
+// the workspace with rows of `ld` floats, instead of Y.
 // Every wave of the work-group must call it (barriers inside).
-template <class C, int EPI>
+template <class C, int EPI, bool PARTIAL = false>
 __device__ __forceinline__ void epilogue_staged(const f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, char* smem, int m0,
-                                                int n0, int tid, int wave_m, int wave_n, int wave_k, int lane_m, int lane_g) {
+                                                int n0, int tid, int wave_m, int wave_n, int wave_k, int lane_m, int lane_g,
+                                                char* dst, size_t ld) {
+  static_assert(!PARTIAL || EPI == TF_EPI_NONE_F32, "partial sums are fp32");
   constexpr int ESZ = EPI == TF_EPI_NONE_F32 ? 4 : 2;
   constexpr int ROWB = C::BN * ESZ + 16;                 // staged row, padded: the 32 rows a store hits spread over the banks
   constexpr int CPR = C::BN * ESZ / 16;                  // 16-byte pieces per row
@@ -391,11 +396,14 @@ __device__ __forceinline__ void epilogue_staged(const f32x16 (&acc)[C::TM][C::TN
     for (int t = 0; t < C::TN; ++t)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const u32x2 braw = *(const u32x2*)(bias_lds + (32 * t + 8 * q) * 2);
-        const float z0 = acc[i][t][4 * q] + __builtin_bit_cast(float, braw[0] << 16);
-        const float z1 = acc[i][t][4 * q + 1] + __builtin_bit_cast(float, braw[0] & 0xffff0000u);
-        const float z2 = acc[i][t][4 * q + 2] + __builtin_bit_cast(float, braw[1] << 16);
-        const float z3 = acc[i][t][4 * q + 3] + __builtin_bit_cast(float, braw[1] & 0xffff0000u);
+        float z0 = acc[i][t][4 * q], z1 = acc[i][t][4 * q + 1], z2 = acc[i][t][4 * q + 2], z3 = acc[i][t][4 * q + 3];
+        if (!PARTIAL) {
+          const u32x2 braw = *(const u32x2*)(bias_lds + (32 * t + 8 * q) * 2);
+          z0 += __builtin_bit_cast(float, braw[0] << 16);
+          z1 += __builtin_bit_cast(float, braw[0] & 0xffff0000u);
+          z2 += __builtin_bit_cast(float, braw[1] << 16);
+          z3 += __builtin_bit_cast(float, braw[1] & 0xffff0000u);
+        }
         if (EPI == TF_EPI_NONE_F32) {
           const f32x4 v = {z0, z1, z2, z3};
           *(f32x4*)(wr + (32 * t + 8 * q) * 4) = v;
@@ -414,7 +422,7 @@ __device__ __forceinline__ void epilogue_staged(const f32x16 (&acc)[C::TM][C::TN
       const int g = rs >> 5;                               // wave row and k group the staged row came from
       const int m = m0 + (g / C::WK) * C::WTM + (g % C::WK) * 32 * (C::TM / 2) + 32 * i + (rs & 31);
       const u32x4 v = *(const u32x4*)(smem + rs * ROWB + cc * 16);
-      *(u32x4*)((char*)p.Y + ((size_t)m * p.ldy + n0) * ESZ + cc * 16) = v;
+      __builtin_nontemporal_store(v, (u32x4*)(dst + ((size_t)m * ld + n0) * ESZ + cc * 16));
     }
   }
 }
@@ -912,7 +920,10 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     if (!C::FUSED_OK || !p.fused_reduce) {
       // two-kernel split-K: plain stores; a reduce kernel launched behind this one sums the
       // slices in slice order and applies the epilogue (the kernel boundary orders the two)
-      if (full) store_partial<C, true, false>(acc, wsk, p, wm0, wn0);
+      if (C::stage_ok(4) && full && p.ws_vec16) {
+        if constexpr (C::stage_ok(4))
+          epilogue_staged<C, TF_EPI_NONE_F32, true>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g, (char*)wsk, (size_t)p.N);
+      } else if (full) store_partial<C, true, false>(acc, wsk, p, wm0, wn0);
       else store_partial<C, false, false>(acc, wsk, p, wm0, wn0);
       return;
     }
@@ -975,12 +986,12 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   const bool staged = full && p.y_vec16;      // the same for every wave of the work-group
   if (p.epi == TF_EPI_NONE_F32) {
     if (C::stage_ok(4) && staged) {
-      if constexpr (C::stage_ok(4)) epilogue_staged<C, TF_EPI_NONE_F32>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g);
+      if constexpr (C::stage_ok(4)) epilogue_staged<C, TF_EPI_NONE_F32>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g, (char*)p.Y, (size_t)p.ldy);
     } else if (full) epilogue<C, true, TF_EPI_NONE_F32>(acc, p, wm0, wn0, bias_lds);
     else epilogue<C, false, TF_EPI_NONE_F32>(acc, p, wm0, wn0, bias_lds);
   } else {
     if (C::stage_ok(2) && staged) {
-      if constexpr (C::stage_ok(2)) epilogue_staged<C, TF_EPI_BIAS_GELU_ERF>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g);
+      if constexpr (C::stage_ok(2)) epilogue_staged<C, TF_EPI_BIAS_GELU_ERF>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g, (char*)p.Y, (size_t)p.ldy);
     } else if (full) epilogue<C, true, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0, bias_lds);
     else epilogue<C, false, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0, bias_lds);
   }

@@ -169,7 +169,8 @@ __global__ void __launch_bounds__(256) tf_splitk_reduce_kernel(const GemmParams 
   const size_t slice = (size_t)p.M * p.N;
   const float* src = p.ws + m * p.N + n;
   f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-  for (int s = 0; s < p.split_k; ++s) sum += *(const f32x4*)(src + (size_t)s * slice);
+  // the partial sums are read once and the output written once: neither needs to stay in the caches
+  for (int s = 0; s < p.split_k; ++s) sum += __builtin_nontemporal_load((const f32x4*)(src + (size_t)s * slice));
   const u32x2 braw = *(const u32x2*)(p.bias + n);
   const float z0 = sum[0] + __builtin_bit_cast(float, braw[0] << 16);
   const float z1 = sum[1] + __builtin_bit_cast(float, braw[0] & 0xffff0000u);
@@ -177,12 +178,12 @@ __global__ void __launch_bounds__(256) tf_splitk_reduce_kernel(const GemmParams 
   const float z3 = sum[3] + __builtin_bit_cast(float, braw[1] & 0xffff0000u);
   if (p.epi == TF_EPI_NONE_F32) {
     const f32x4 v = {z0, z1, z2, z3};
-    *(f32x4*)((float*)p.Y + m * p.ldy + n) = v;
+    __builtin_nontemporal_store(v, (f32x4*)((float*)p.Y + m * p.ldy + n));
   } else {
     u32x2 o;
     o[0] = pack_bf16x2(gelu_erf(z0), gelu_erf(z1));
     o[1] = pack_bf16x2(gelu_erf(z2), gelu_erf(z3));
-    *(u32x2*)((uint16_t*)p.Y + m * p.ldy + n) = o;
+    __builtin_nontemporal_store(o, (u32x2*)((uint16_t*)p.Y + m * p.ldy + n));
   }
 }
 
