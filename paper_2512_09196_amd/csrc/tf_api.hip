@@ -413,6 +413,7 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
       TF_HIP(hipFuncSetAttribute(k.func, hipFuncAttributeMaxDynamicSharedMemorySize, k.lds_bytes));
       p->attr_done[im.lds_index] = 1;
     }
+    g.batch_xcd = d.batch % 8 == 0 && (double)im.tiles_m * im.tiles_n * d.batch < 4294967296.0;
     k.launch(g, dim3((unsigned)(im.tiles_m * im.tiles_n), (unsigned)d.batch), stream);
   } else if (v.kind == TF_KIND_VECMAT_NAIVE) {
     if (d.M > 65535) return fail(TF_E_UNSUPPORTED, "naive variant: M too large for the grid");

@@ -432,16 +432,27 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   // batched problems: blockIdx.y is the batch item, whose operands are a stride away
   GemmParams p = p_in;
+  int tile_id = blockIdx.x;
   if (gridDim.y > 1) {
-    p.A += (size_t)blockIdx.y * p.stride_a;
-    p.B += (size_t)blockIdx.y * p.stride_b;
-    p.Y = (char*)p.Y + (size_t)blockIdx.y * p.stride_y * (p.epi == TF_EPI_NONE_F32 ? 4 : 2);
+    int item = blockIdx.y;
+    if (p.batch_xcd) {
+      // Work-groups go to the eight XCDs in turn, in launch order (x fastest). Renumber them so that all tiles
+      // of a batch item run on one XCD, whose L2 then fetches the item's operands once, not once per XCD:
+      // XCD x takes items x, x + 8, ... (the host sets the flag only for a batch that is a multiple of 8).
+      const unsigned launch_id = blockIdx.y * gridDim.x + blockIdx.x;
+      const unsigned local = launch_id >> 3;
+      item = (int)((launch_id & 7u) + 8u * (local / gridDim.x));
+      tile_id = (int)(local % gridDim.x);
+    }
+    p.A += (size_t)item * p.stride_a;
+    p.B += (size_t)item * p.stride_b;
+    p.Y = (char*)p.Y + (size_t)item * p.stride_y * (p.epi == TF_EPI_NONE_F32 ? 4 : 2);
   }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_k = wave / (C::WM * C::WN), wave_mn = wave % (C::WM * C::WN);
   const int wave_m = wave_mn / C::WN, wave_n = wave_mn % C::WN;
 
-  const TileCoord tc = map_tile(p, blockIdx.x);
+  const TileCoord tc = map_tile(p, tile_id);
   const int m0 = tc.tm * C::BM, n0 = tc.tn * C::BN;
   const int ktiles_total = (p.K + C::BK - 1) / C::BK;
   const int kt_begin = tc.ks * p.ktiles_per_split;

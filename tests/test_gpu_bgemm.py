@@ -68,7 +68,8 @@ def test_t1_every_variant():
     assert any(n.endswith("ldstrans") for n in ran) and any(n.endswith("pretrans") for n in ran)
 
 
-@pytest.mark.parametrize("shape", [(1, 264, 520, 192), (5, 72, 40, 64), (2, 520, 136, 320), (3, 40, 48, 64), (2, 1032, 264, 128)])
+@pytest.mark.parametrize("shape", [(1, 264, 520, 192), (5, 72, 40, 64), (2, 520, 136, 320), (3, 40, 48, 64), (2, 1032, 264, 128),
+                                   (8, 72, 136, 64), (16, 40, 200, 128)])     # batches of 8: items pinned to XCDs
 def test_ragged_tiles(shape):
     nb, M, N, K = shape
     A, B = wl.make_bgemm(nb, M, N, K, seed=200 + M)
