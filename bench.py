@@ -30,10 +30,10 @@ MALL_BYTES = 256 << 20
 # A 256 MiB device copy reads FETCH_SIZE 131086 and WRITE_SIZE 262144 KiB, hence the scale factors.
 FETCH_SCALE, WRITE_SCALE = 262144.0 / 131086.4, 1.0
 HBM_TRAFFIC_KIB = {
-    ("C2", "lds_128x128x64_w2x4_s3_direct_sk1"): (24675.1, 8192.0),
-    ("C2", "lds_128x128x64_w4x2_s3_direct_sk1"): (24678.4, 8192.0),
-    ("C2", "lds_128x128x64_w2x4_s4_direct_sk1"): (24672.0, 8192.0),
-    ("C2", "lds_128x128x64_w2x2_s3_direct_sk1"): (24712.0, 8192.0),
+    ("C2", "lds_128x128x64_w2x4_s3_direct_sk1"): (24691.0, 8192.0),
+    ("C2", "lds_128x128x64_w4x2_s3_direct_sk1"): (24690.6, 8192.0),
+    ("C2", "lds_128x128x64_w2x4_s4_direct_sk1"): (24694.9, 8192.0),
+    ("C2", "lds_128x128x64_w2x2x2_s3_direct_sk1"): (24690.5, 8192.0),
 }
 
 
