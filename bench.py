@@ -28,7 +28,7 @@ MALL_BYTES = 256 << 20
 
 # rocprofv3 --pmc readings (KiB per dispatch) of the C2 kernels the loop ends on: (FETCH_SIZE, WRITE_SIZE).
 # A 256 MiB device copy reads FETCH_SIZE 131086 and WRITE_SIZE 262144 KiB, hence the scale factors.
-FETCH_SCALE, WRITE_SCALE = 262144.0 / 131086.4, 1.0
+FETCH_SCALE, WRITE_SCALE = 262144.0 / 131084.9, 1.0
 HBM_TRAFFIC_KIB = {
     ("C2", "lds_128x128x64_w2x4_s3_direct_sk1"): (24691.0, 8192.0),
     ("C2", "lds_128x128x64_w4x2_s3_direct_sk1"): (24690.6, 8192.0),

@@ -50,6 +50,10 @@ def _load():
             lib.tfo_bf16_to_double.argtypes = [ctypes.c_uint16]
             lib.tfo_gelu.restype = ctypes.c_double
             lib.tfo_gelu.argtypes = [ctypes.c_double]
+            lib.tfo_gelu_tanh.restype = ctypes.c_double
+            lib.tfo_gelu_tanh.argtypes = [ctypes.c_double]
+            lib.tfo_gelu_tanh_array.restype = ctypes.c_int
+            lib.tfo_gelu_tanh_array.argtypes = [ctypes.c_long, f64p, f64p]
             lib.tfo_gemm_bias_gelu.restype = ctypes.c_int
             lib.tfo_gemm_bias_gelu.argtypes = [
                 ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long,
@@ -90,6 +94,18 @@ def bf16_to_double(bits: int) -> float:
 
 def gelu(z: float) -> float:
     return float(_load().tfo_gelu(float(z)))
+
+
+def gelu_tanh(z):
+    """The tanh form of GELU, 1/2 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))), of a float or a float64 array."""
+    if np.isscalar(z):
+        return float(_load().tfo_gelu_tanh(float(z)))
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    y = np.empty_like(z)
+    rc = _load().tfo_gelu_tanh_array(z.size, _ptr(z, ctypes.c_double), _ptr(y, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError(f"tfo_gelu_tanh_array failed with {rc}")
+    return y
 
 
 def gemm_bias_gelu(A, B, bias):

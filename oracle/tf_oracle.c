@@ -2,7 +2,7 @@
  * CPU oracle for the fused tile kernel  Y = GELU_erf(A.B + bias), and (last two functions of
  * the file but one) for the batched vector-matrix product of the paper's Case Study 2 and the
  * batched transposed-operand product of its Case Study 3, and (last) for the element-wise sine of
- * its Case Study 1.
+ * its Case Study 1.  tfo_gelu_tanh is the activation of the kernel's second bf16 epilogue.
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
  * GPU kernels are checked against.  It is single-threaded, has no blocking,
@@ -54,6 +54,26 @@ double tfo_gelu(double z)
     if (z < 0.0)
         return 0.5 * z * erfc(-z * inv_sqrt2);
     return 0.5 * z * (1.0 + erf(z * inv_sqrt2));
+}
+
+/* The tanh form of GELU (Hendrycks and Gimpel's approximation, the other activation the epilogue
+ * offers):  1/2 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))), written out with libm's tanh.
+ * Pinned by tests/test_oracle_gemm.py: 50-digit decimal evaluation through exp, the odd-part
+ * identity, limits, and its known distance from the erf form. */
+double tfo_gelu_tanh(double z)
+{
+    const double c = 0.79788456080286535588; /* sqrt(2/pi) */
+    return 0.5 * z * (1.0 + tanh(c * (z + 0.044715 * z * z * z)));
+}
+
+/* y[i] = tfo_gelu_tanh(z[i]) for i < n.  Returns 0, or -1 on a bad argument. */
+int tfo_gelu_tanh_array(long n, const double *z, double *y)
+{
+    if (n < 0 || (n > 0 && (!z || !y)))
+        return -1;
+    for (long i = 0; i < n; ++i)
+        y[i] = tfo_gelu_tanh(z[i]);
+    return 0;
 }
 
 /*

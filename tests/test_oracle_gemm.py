@@ -101,6 +101,39 @@ def test_gelu_is_erf_form_not_tanh_form():
     assert abs(orc.gelu(x) - float(Decimal(x) * phi_decimal(x))) < 1e-14
 
 
+def gelu_tanh_decimal(x: float) -> Decimal:
+    """1/2 x (1 + tanh u) with tanh u = (e^{2u} - 1) / (e^{2u} + 1), 50 digits; sqrt(2/pi) from a 50-digit pi."""
+    getcontext().prec = 60
+    pi = Decimal("3.14159265358979323846264338327950288419716939937510")
+    xd = Decimal(x)
+    u = (Decimal(2) / pi).sqrt() * (xd + Decimal("0.044715") * xd ** 3)
+    e = (2 * u).exp()
+    return xd / 2 * (1 + (e - 1) / (e + 1))
+
+
+@pytest.mark.parametrize("x", [-9.0, -5.0, -3.0, -1.5, -0.75, -1e-3, 1e-6, 0.3, 1.0, 2.0, 3.5, 6.0, 12.0])
+def test_gelu_tanh_against_decimal_evaluation(x):
+    want = gelu_tanh_decimal(x)
+    got = orc.gelu_tanh(x)
+    # 1 + tanh cancels on the negative side: allow the absolute error of tanh (one ulp of 1) times |x| / 2
+    assert abs(Decimal(got) - want) <= abs(want) * Decimal(1e-15) + Decimal(abs(x) * 1.2e-16)
+
+
+def test_gelu_tanh_identities_limits_and_distance_from_the_erf_form():
+    xs = np.linspace(-9, 9, 361)
+    y = orc.gelu_tanh(xs)
+    # tanh is odd: GELU_tanh(x) - GELU_tanh(-x) = x
+    assert np.allclose(y - orc.gelu_tanh(-xs), xs, rtol=0, atol=4e-15 * 9)
+    assert orc.gelu_tanh(0.0) == 0.0 and orc.gelu_tanh(40.0) == 40.0 and abs(orc.gelu_tanh(-40.0)) == 0.0
+    assert np.array_equal(y, np.array([orc.gelu_tanh(float(x)) for x in xs]))      # array and scalar entry agree
+    # an approximation of x Phi(x): within 5e-4 everywhere, and not equal to it
+    d = np.abs(y - np.array([orc.gelu(float(x)) for x in xs]))
+    assert d.max() < 5e-4 and d.max() > 1e-4
+    # slope 1/2 at the origin
+    h = 1e-6
+    assert (orc.gelu_tanh(h) - orc.gelu_tanh(-h)) / (2 * h) == pytest.approx(0.5, abs=1e-9)
+
+
 def test_gelu_minimum_and_limits():
     xs = np.linspace(-2, 0, 20001)
     ys = np.array([orc.gelu(x) for x in xs])
