@@ -109,6 +109,8 @@ def main():
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "V1", "V2", "T1", "T2", "E1", "E2"],
                     help="C1..C5: Y = GELU_erf(A.B + bias); V1, V2: batched vector-matrix product C[m,n] = sum_k A[m,k] B[m,n,k]; "
                          "T1, T2: batched transposed-operand product C[b] = A[b]^T B[b]; E1, E2: element-wise sine y = sin(x), fp32")
+    ap.add_argument("--epilogue", default="gelu_erf", choices=["gelu_erf", "gelu_tanh", "bias"],
+                    help="C1..C5 only: the bf16 epilogue (the headline metric is gelu_erf)")
     ap.add_argument("--variant", default=None, help="time this variant instead of the loop's choice")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-tune", action="store_true", help="skip the loop (needs --variant)")
@@ -178,7 +180,9 @@ def main():
     elif bgemm:
         prob = tf.Problem(w.M, w.N, w.K, op=tf.TF_OP_BATCHED_GEMM_TN, batch=w.batch)
     else:
-        prob = tf.Problem(w.M, w.N, w.K, op=tf.TF_OP_BATCHED_VECMAT if vecmat else tf.TF_OP_GEMM_EPILOGUE)
+        epi = {"gelu_erf": tf.TF_EPI_BIAS_GELU_ERF, "gelu_tanh": tf.TF_EPI_BIAS_GELU_TANH, "bias": tf.TF_EPI_BIAS}[args.epilogue]
+        prob = tf.Problem(w.M, w.N, w.K, op=tf.TF_OP_BATCHED_VECMAT if vecmat else tf.TF_OP_GEMM_EPILOGUE,
+                          epi=tf.TF_EPI_NONE_F32 if vecmat else epi)
     variants = prob.variants()
     names = [v.name.decode() for v in variants]
     tune = None
@@ -264,7 +268,8 @@ def main():
         "metric": ("element-wise sine Gelement/s (y = sin(x), fp32 in and out)" if sin else
                    "batched vector-matrix product TFLOP/s (C[m,n] = sum_k A[m,k] B[m,n,k], bf16 in, fp32 out)" if vecmat
                    else "batched transposed-operand product TFLOP/s (C[b] = A[b]^T B[b], bf16 in, fp32 out)" if bgemm
-                   else "GEMM+epilogue TFLOP/s (bf16 GELU_erf(A.B+bias), fp32 accumulate)"),
+                   else "GEMM+epilogue TFLOP/s (bf16 %s, fp32 accumulate)"
+                   % {"gelu_erf": "GELU_erf(A.B+bias)", "gelu_tanh": "GELU_tanh(A.B+bias)", "bias": "A.B+bias"}[args.epilogue]),
         "value": w.n / (ms_per_step * 1e-3) * 1e-9 if sin else tflops, "unit": "Gelement/s" if sin else "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if vecmat or sin else "bf16", "data": "synthetic",

@@ -48,7 +48,10 @@ typedef enum {
 
 typedef enum {
   TF_EPI_BIAS_GELU_ERF = 0, /* Y (bf16) = round_nearest_even(GELU_erf(A.B + bias))                  */
-  TF_EPI_NONE_F32 = 1       /* Y (float) = A.B + bias, the fp32 pre-activation; used by exactness tests */
+  TF_EPI_NONE_F32 = 1,      /* Y (float) = A.B + bias, the fp32 pre-activation; used by exactness tests */
+  TF_EPI_BIAS = 2,          /* Y (bf16) = round_nearest_even(A.B + bias): bias only, no activation         */
+  TF_EPI_BIAS_GELU_TANH = 3 /* Y (bf16) = round_nearest_even(GELU_tanh(A.B + bias)),
+                               GELU_tanh(z) = z/2 (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3)))               */
 } tf_epilogue;
 
 typedef enum {

@@ -813,7 +813,7 @@ extern "C" tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem**
         desc->stride_y < (int64_t)desc->M * desc->ldy)
       return fail(TF_E_INVALID, "batch stride smaller than one item");
   }
-  if (desc->epi != TF_EPI_BIAS_GELU_ERF && desc->epi != TF_EPI_NONE_F32) return fail(TF_E_INVALID, "unknown epilogue %d", desc->epi);
+  if (desc->epi < TF_EPI_BIAS_GELU_ERF || desc->epi > TF_EPI_BIAS_GELU_TANH) return fail(TF_E_INVALID, "unknown epilogue %d", desc->epi);
   tf_problem* p = new (std::nothrow) tf_problem();
   if (!p) return fail(TF_E_NOMEM, "out of host memory");
   p->desc = *desc;

@@ -60,6 +60,29 @@ __device__ __forceinline__ float gelu_erf(float z) {
   return __builtin_fmaf(0.5f, z + u, -tail);
 }
 
+// The tanh form of GELU, z/2 (1 + tanh u) with u = sqrt(2/pi) (z + 0.044715 z^3), written as
+// z * sigmoid(2u) = z / (1 + 2^(-2u log2 e)): one exp2 and one reciprocal. z is clamped below for the
+// product only, so that -inf gives -0 rather than inf * 0 (the true value is below 1e-38 long before);
+// a NaN propagates through u. |error| <= 4e-7 |z| against the double-precision definition.
+__device__ __forceinline__ float gelu_tanh(float z) {
+  const float u = 0.7978845608f * __builtin_fmaf(0.044715f * z * z, z, z);
+  const float e = __builtin_amdgcn_exp2f(-2.885390082f * u);
+  return __builtin_fmaxf(z, -1.0e4f) * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+// The activation of a bf16 epilogue, chosen at compile time (tile kernels) or at run time (the small kernels).
+template <int EPI>
+__device__ __forceinline__ float activate(float z) {
+  if (EPI == TF_EPI_BIAS_GELU_ERF) return gelu_erf(z);
+  if (EPI == TF_EPI_BIAS_GELU_TANH) return gelu_tanh(z);
+  return z;
+}
+__device__ __forceinline__ float activate(float z, int epi) {
+  if (epi == TF_EPI_BIAS_GELU_ERF) return gelu_erf(z);
+  if (epi == TF_EPI_BIAS_GELU_TANH) return gelu_tanh(z);
+  return z;
+}
+
 // Work-group id -> position in the tile order.
 //  * The hardware deals consecutive work-group ids round-robin over the 8 XCDs, each with
 //    its own L2. With xcd_swizzle the ids are renumbered so that each XCD owns one

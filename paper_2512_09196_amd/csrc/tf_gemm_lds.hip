@@ -331,6 +331,8 @@ __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const 
   }
 }
 
+template <int E> struct EpiTag { static constexpr int value = E; };
+
 // bias_lds: this lane's first four bias values in LDS (columns wn0 .. wn0 + 3 of the tile's copy)
 template <class C, bool FULL, int EPI>
 __device__ __forceinline__ void epilogue(const f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0,
@@ -355,8 +357,8 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[C::TM][C::TN], cons
             *(f32x4*)((float*)p.Y + (size_t)m * p.ldy + n) = v;
           } else {
             u32x2 o;
-            o[0] = pack_bf16x2(gelu_erf(z0), gelu_erf(z1));
-            o[1] = pack_bf16x2(gelu_erf(z2), gelu_erf(z3));
+            o[0] = pack_bf16x2(activate<EPI>(z0), activate<EPI>(z1));
+            o[1] = pack_bf16x2(activate<EPI>(z2), activate<EPI>(z3));
             *(u32x2*)((uint16_t*)p.Y + (size_t)m * p.ldy + n) = o;
           }
         }
@@ -409,8 +411,8 @@ __device__ __forceinline__ void epilogue_staged(const f32x16 (&acc)[C::TM][C::TN
           *(f32x4*)(wr + (32 * t + 8 * q) * 4) = v;
         } else {
           u32x2 o;
-          o[0] = pack_bf16x2(gelu_erf(z0), gelu_erf(z1));
-          o[1] = pack_bf16x2(gelu_erf(z2), gelu_erf(z3));
+          o[0] = pack_bf16x2(activate<EPI>(z0), activate<EPI>(z1));
+          o[1] = pack_bf16x2(activate<EPI>(z2), activate<EPI>(z3));
           *(u32x2*)(wr + (32 * t + 8 * q) * 2) = o;
         }
       }
@@ -995,17 +997,19 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   }
   const char* bias_lds = smem + C::BIAS_OFF + (wave_n * C::WTN + 4 * lane_g) * 2;
   const bool staged = full && p.y_vec16;      // the same for every wave of the work-group
-  if (p.epi == TF_EPI_NONE_F32) {
-    if (C::stage_ok(4) && staged) {
-      if constexpr (C::stage_ok(4)) epilogue_staged<C, TF_EPI_NONE_F32>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g, (char*)p.Y, (size_t)p.ldy);
-    } else if (full) epilogue<C, true, TF_EPI_NONE_F32>(acc, p, wm0, wn0, bias_lds);
-    else epilogue<C, false, TF_EPI_NONE_F32>(acc, p, wm0, wn0, bias_lds);
-  } else {
-    if (C::stage_ok(2) && staged) {
-      if constexpr (C::stage_ok(2)) epilogue_staged<C, TF_EPI_BIAS_GELU_ERF>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g, (char*)p.Y, (size_t)p.ldy);
-    } else if (full) epilogue<C, true, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0, bias_lds);
-    else epilogue<C, false, TF_EPI_BIAS_GELU_ERF>(acc, p, wm0, wn0, bias_lds);
-  }
+  auto finish = [&](auto tag) {
+    constexpr int EPI = decltype(tag)::value;
+    constexpr int ESZ = EPI == TF_EPI_NONE_F32 ? 4 : 2;
+    if (C::stage_ok(ESZ) && staged) {
+      if constexpr (C::stage_ok(ESZ))
+        epilogue_staged<C, EPI>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g, (char*)p.Y, (size_t)p.ldy);
+    } else if (full) epilogue<C, true, EPI>(acc, p, wm0, wn0, bias_lds);
+    else epilogue<C, false, EPI>(acc, p, wm0, wn0, bias_lds);
+  };
+  if (p.epi == TF_EPI_BIAS_GELU_ERF) finish(EpiTag<TF_EPI_BIAS_GELU_ERF>{});
+  else if (p.epi == TF_EPI_NONE_F32) finish(EpiTag<TF_EPI_NONE_F32>{});
+  else if (p.epi == TF_EPI_BIAS) finish(EpiTag<TF_EPI_BIAS>{});
+  else finish(EpiTag<TF_EPI_BIAS_GELU_TANH>{});
 }
 
 template <class C>
@@ -1025,7 +1029,6 @@ static LdsKernelInfo make_info() {
 }
 
 //                         BM   BN  WM WN ST  direct
-using K256x256_d2 = LdsCfg<256, 256, 2, 2, 2, true>;
 using K256x128_d2 = LdsCfg<256, 128, 2, 2, 2, true>;
 using K128x256_d2 = LdsCfg<128, 256, 2, 2, 2, true>;
 using K128x128_d2 = LdsCfg<128, 128, 2, 2, 2, true>;
@@ -1044,7 +1047,6 @@ using K32x32_d8   = LdsCfg< 32,  32, 1, 1, 8, true>;
 using K128x128_w8a = LdsCfg<128, 128, 2, 4, 3, true>;   // eight waves: two per SIMD cover each other's overheads
 using K128x128_w8b = LdsCfg<128, 128, 4, 2, 3, true>;
 using K128x128_w8c = LdsCfg<128, 128, 2, 4, 4, true>;
-using K256x256_ab = LdsCfg<256, 256, 4, 1, 2, true, true>;
 using K128x256_ab = LdsCfg<128, 256, 4, 1, 2, true, true>;
 using K128x128_k2a = LdsCfg<128, 128, 2, 2, 3, true, false, 2>;   // two k groups of 2x2 waves
 using K128x128_k2b = LdsCfg<128, 128, 2, 2, 4, true, false, 2>;
@@ -1065,11 +1067,11 @@ using K256x256_w8a = LdsCfg<256, 256, 2, 4, 2, true>;   // eight waves on the bi
 using K256x256_w8b = LdsCfg<256, 256, 4, 2, 2, true>;
 
 static LdsKernelInfo g_table[] = {
-    make_info<K256x256_d2>(), make_info<K256x128_d2>(), make_info<K128x256_d2>(),
+    make_info<K256x128_d2>(), make_info<K128x256_d2>(),
     make_info<K128x128_d2>(), make_info<K128x128_d3>(), make_info<K128x128_r2>(),
     make_info<K64x64_r2>(),   make_info<K64x64_d3>(),   make_info<K32x128_d3>(),
-    make_info<K32x64_d4>(),   make_info<K32x128_r2>(),  make_info<K256x256_ab>(),
-    make_info<K128x256_ab>(),  make_info<K32x128_d6>(),  make_info<K32x64_d8>(),
+    make_info<K32x64_d4>(),   make_info<K32x128_r2>(),  make_info<K128x256_ab>(),
+     make_info<K32x128_d6>(),  make_info<K32x64_d8>(),
     make_info<K32x256_d4>(),  make_info<K32x32_d4>(),   make_info<K32x32_d8>(),
     make_info<K128x128_w8a>(), make_info<K128x128_w8b>(), make_info<K128x128_w8c>(),
     make_info<K128x128_k2a>(), make_info<K128x128_k2b>(),

@@ -20,7 +20,7 @@ __global__ void __launch_bounds__(256) tf_gemm_naive_kernel(const GemmParams p) 
     acc = __builtin_fmaf(bf16_bits_to_f32(a[k]), bf16_bits_to_f32(b[(size_t)k * p.ldb]), acc);
   const float z = acc + bf16_bits_to_f32(p.bias[n]);
   if (p.epi == TF_EPI_NONE_F32) ((float*)p.Y)[(size_t)m * p.ldy + n] = z;
-  else ((uint16_t*)p.Y)[(size_t)m * p.ldy + n] = f32_to_bf16_bits(gelu_erf(z));
+  else ((uint16_t*)p.Y)[(size_t)m * p.ldy + n] = f32_to_bf16_bits(activate(z, p.epi));
 }
 
 __global__ void __launch_bounds__(64) tf_gemm_mfma_direct_kernel(const GemmParams p) {
@@ -54,7 +54,7 @@ __global__ void __launch_bounds__(64) tf_gemm_mfma_direct_kernel(const GemmParam
     if (m < p.M) {
       const float z = acc[i] + bias;
       if (p.epi == TF_EPI_NONE_F32) ((float*)p.Y)[(size_t)m * p.ldy + n] = z;
-      else ((uint16_t*)p.Y)[(size_t)m * p.ldy + n] = f32_to_bf16_bits(gelu_erf(z));
+      else ((uint16_t*)p.Y)[(size_t)m * p.ldy + n] = f32_to_bf16_bits(activate(z, p.epi));
     }
   }
 }
@@ -181,8 +181,8 @@ __global__ void __launch_bounds__(256) tf_splitk_reduce_kernel(const GemmParams 
     __builtin_nontemporal_store(v, (f32x4*)((float*)p.Y + m * p.ldy + n));
   } else {
     u32x2 o;
-    o[0] = pack_bf16x2(gelu_erf(z0), gelu_erf(z1));
-    o[1] = pack_bf16x2(gelu_erf(z2), gelu_erf(z3));
+    o[0] = pack_bf16x2(activate(z0, p.epi), activate(z1, p.epi));
+    o[1] = pack_bf16x2(activate(z2, p.epi), activate(z3, p.epi));
     __builtin_nontemporal_store(o, (u32x2*)((uint16_t*)p.Y + m * p.ldy + n));
   }
 }

@@ -230,7 +230,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_stream_kernel(const GemmPa
       if (m >= p.M) continue;
       const float z = sum[o][r] + bias;
       if (p.epi == TF_EPI_NONE_F32) ((float*)p.Y)[(size_t)m * p.ldy + n] = z;
-      else ((uint16_t*)p.Y)[(size_t)m * p.ldy + n] = f32_to_bf16_bits(gelu_erf(z));
+      else ((uint16_t*)p.Y)[(size_t)m * p.ldy + n] = f32_to_bf16_bits(activate(z, p.epi));
     }
   }
 }

@@ -218,7 +218,9 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   // issue slots per element, or the fp32 partial tile at 32 B/clk when a second kernel reduces
   const double fill = 2500.0 / (double)co_resident;
   // (the raw fp32 output has no activation to evaluate: 16-byte stores at about 64 B/clk)
-  double tile_end = pr->epi == TF_EPI_NONE_F32 ? v->bm * (double)v->bn * 4.0 / 64.0 : v->bm * (double)v->bn * 22.0 / 64.0;
+  // VALU instructions per output element of the epilogue: erf-GELU 22, tanh-GELU 14, plain conversions 4
+  const double epi_valu = pr->epi == TF_EPI_BIAS_GELU_ERF ? 22.0 : pr->epi == TF_EPI_BIAS_GELU_TANH ? 14.0 : 4.0;
+  double tile_end = v->bm * (double)v->bn * epi_valu / 64.0;
   if (v->waves_k > 1) tile_end += v->bm * (double)v->bn * 4.0 * (1.0 / 85.0 + 1.0 / 256.0) / 2.0 * v->waves_k;   // accumulator exchange
   double reduce_us = 0.0, fused_tail_us = 0.0;
   const double mhz = hw->clock_mhz < 1650.0 ? hw->clock_mhz : 1650.0;

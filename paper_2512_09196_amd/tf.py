@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtf_gfx950.so")
 
 TF_OK, TF_E_INVALID, TF_E_UNSUPPORTED, TF_E_LAUNCH, TF_E_NOMEM, TF_E_RANGE, TF_E_PROFILER = 0, -1, -2, -3, -4, -5, -6
-TF_EPI_BIAS_GELU_ERF, TF_EPI_NONE_F32 = 0, 1
+TF_EPI_BIAS_GELU_ERF, TF_EPI_NONE_F32, TF_EPI_BIAS, TF_EPI_BIAS_GELU_TANH = 0, 1, 2, 3
 TF_KIND_NAIVE, TF_KIND_MFMA_DIRECT, TF_KIND_MFMA_LDS, TF_KIND_MFMA_STREAM = 0, 1, 2, 3
 TF_KIND_VECMAT_NAIVE, TF_KIND_VECMAT_STREAM, TF_KIND_BGEMM_TN_NAIVE, TF_KIND_SIN = 4, 5, 6, 7
 TF_OP_GEMM_EPILOGUE, TF_OP_BATCHED_VECMAT, TF_OP_BATCHED_GEMM_TN, TF_OP_ELEMENTWISE_SIN = 0, 1, 2, 3

@@ -147,6 +147,14 @@ def test_enumerate_the_other_operations_without_gpu():
         assert len(p.variants()) == 1
     with pytest.raises(tf.TfError):
         tf.Problem(1, -1, 0, op=tf.TF_OP_ELEMENTWISE_SIN)
+    # every epilogue of the GEMM lists the same family; only the GEMM takes the bf16 ones
+    with tf.Problem(2048, 2048, 2048) as p0:
+        names = [v.name for v in p0.variants()]
+        t_erf = tf.predict_us(p0.desc, hw, p0.variants()[5])
+        for epi in (tf.TF_EPI_NONE_F32, tf.TF_EPI_BIAS, tf.TF_EPI_BIAS_GELU_TANH):
+            with tf.Problem(2048, 2048, 2048, epi=epi) as p:
+                assert [v.name for v in p.variants()] == names
+                assert tf.predict_us(p.desc, hw, p.variants()[5]) <= t_erf     # cheaper epilogues are never predicted slower
     # the GEMM never lists kernels of the transposed-operand product
     with tf.Problem(2048, 2048, 2048) as p:
         assert all(v.trans_a == 0 for v in p.variants())

@@ -124,6 +124,51 @@ def test_leading_dimensions_and_padding_columns():
     check_all_variants(M, N, K, A, B, bias, lda=K + 24, ldb=N + 8, ldy=N + 16)
 
 
+@pytest.mark.parametrize("shape", [(256, 256, 256), (300, 520, 448), (16, 512, 2048), (40, 33, 7), (1024, 1024, 4096)])
+def test_bias_only_and_tanh_gelu_epilogues(shape):
+    # every variant with the two further bf16 epilogues: Y = bf16(z) and Y = bf16(GELU_tanh(z)), z = A.B + bias
+    M, N, K = shape
+    A, B, bias = wl.make_custom(M, N, K, seed=91 + M)
+    _, z, s = orc.gemm_bias_gelu(A, B, bias)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    for epi, want in ((tf.TF_EPI_BIAS, z), (tf.TF_EPI_BIAS_GELU_TANH, orc.gelu_tanh(z.ravel()).reshape(z.shape))):
+        out = gu.OutBuf(M, N)
+        kinds = set()
+        with tf.Problem(M, N, K, epi=epi) as prob:
+            for v in prob.variants():
+                if M >= 1024 and v.kind in (tf.TF_KIND_NAIVE, tf.TF_KIND_MFMA_DIRECT):
+                    continue
+                name = v.name.decode()
+                print("case", shape, "epi", epi, "variant", name, flush=True)
+                got, intact, _ = gu.run_variant(prob, v.id, dA, dB, dbias, out)
+                assert intact, "%s wrote outside Y" % name
+                assert not np.isnan(got).any(), "%s left elements unwritten" % name
+                assert gu.official_ok(got, want), name
+                err = np.abs(got - want)
+                bound = gu.strict_bound(want, z, s, K)      # slope of either function <= 1.13
+                assert np.all(err <= bound), "%s: worst excess %g" % (name, (err - bound).max())
+                kinds.add(v.kind)
+        assert tf.TF_KIND_NAIVE in kinds or M >= 1024
+
+
+def test_epilogues_differ_where_they_should():
+    # guards against an epilogue silently running another one's code
+    M, N, K = 128, 128, 64
+    A, B, bias = wl.make_custom(M, N, K, seed=5)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    res = {}
+    for epi in (tf.TF_EPI_BIAS_GELU_ERF, tf.TF_EPI_BIAS, tf.TF_EPI_BIAS_GELU_TANH):
+        out = gu.OutBuf(M, N)
+        with tf.Problem(M, N, K, epi=epi) as prob:
+            v = [v for v in prob.variants() if v.kind == tf.TF_KIND_MFMA_LDS][0]
+            res[epi], _, _ = gu.run_variant(prob, v.id, dA, dB, dbias, out)
+    z = res[tf.TF_EPI_BIAS]
+    assert np.any(z < -0.5) and np.all(res[tf.TF_EPI_BIAS_GELU_ERF][z < -0.5] > z[z < -0.5])
+    d = np.abs(res[tf.TF_EPI_BIAS_GELU_ERF] - res[tf.TF_EPI_BIAS_GELU_TANH])
+    assert d.max() <= 5e-4 + 2.0 ** -7 * np.abs(z).max()          # the two GELUs are close, up to one bf16 step
+    assert np.any(d > 0)
+
+
 def test_degenerate_sizes():
     torch = gu.torch_mod()
     # K = 0: Y = GELU(bias) on every row
