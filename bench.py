@@ -34,6 +34,15 @@ HBM_TRAFFIC_KIB = {
     ("C2", "lds_128x128x64_w4x2_s3_direct_sk1"): (24690.6, 8192.0),
     ("C2", "lds_128x128x64_w2x4_s4_direct_sk1"): (24694.9, 8192.0),
     ("C2", "lds_128x128x64_w2x2x2_s3_direct_sk1"): (24690.5, 8192.0),
+    ("C3", "lds_256x256x64_w2x4_s2_direct_sk1"): (314016.0, 88064.9),
+    ("C4", "lds_32x64x64_w1x2_s4_direct_sk2l"): (67568.4, 1290.9),
+    ("C4", "lds_32x64x64_w1x2_s4_direct_sk2r"): (66466.8 + 546.0, 1024.0 + 256.0),      # GEMM kernel + reduce kernel
+    ("V2", "vecmat_r1_u4_w4_g0"): (525341.2, 1024.1),
+    ("V2", "vecmat_r1_u8_w4_g0"): (525349.2, 1024.0),
+    ("T2", "bgemm_128x128x64_w2x2_s2_ldstrans"): (16516.6, 131878.9),
+    ("T2", "bgemm_128x128x64_w2x4_s2_ldstrans"): (16486.7, 131239.7),
+    ("E2", "sin_b1024_t256_v4_g0_nt"): (131091.8, 262147.1),
+    ("E2", "sin_b2048_t256_v4_g0_nt"): (131101.2, 262145.1),
 }
 
 
