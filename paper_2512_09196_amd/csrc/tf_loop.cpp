@@ -213,7 +213,13 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   if (cu_waves >= 8) chain *= v->waves_k > 1 ? 0.7 : 0.3;       // k groups: half the MFMAs per wave and step to hide it behind
   if (!v->direct_to_lds) chain += 300.0;
   if (v->a_bypass_lds) chain += 400.0;
-  const double ktile = fmax(fmax(mfma, lds_w + lds_r), ta) + chain;
+  double ktile = fmax(fmax(mfma, lds_w + lds_r), ta) + chain;
+  // the in-kernel reductions keep the slices of a tile side by side, so the work-groups of an XCD work on
+  // different K ranges and share fewer operand panels in its L2 than in the slice-by-slice order of the
+  // two-kernel reduction (measured: about a quarter more time per K step)
+  // (big tiles; the skinny tiles' operands are read once anyway)
+  const double big = fmin(1.0, v->bm * (double)v->bn / 16384.0);
+  if (v->split_k > 1 && v->fused_reduce) ktile *= 1.0 + 0.25 * big;
   // per tile: pipeline fill (first tiles from memory), then bias + GELU + pack at about 22 VALU
   // issue slots per element, or the fp32 partial tile at 32 B/clk when a second kernel reduces
   const double fill = 2500.0 / (double)co_resident;
@@ -228,7 +234,7 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
     if (v->fused_reduce == 2) {
       // partial tiles stay in the L2 the slices share: 16-byte stores and loads, one round of tickets
       // ... but the last slice of a tile still sums all slices and runs the epilogue alone, on one CU
-      fused_tail_us = 2.0 + v->bm * (double)v->bn * 4.0 * (1.0 + 2.0 * v->split_k) / 64.0 / mhz;
+      fused_tail_us = 2.0 + 3.0 * big + v->bm * (double)v->bn * 4.0 * (1.0 + 2.0 * v->split_k) / 64.0 / mhz;
     } else if (v->fused_reduce) {
       // partial tiles go out and come back through device-scope scalar accesses at about
       // 2 B/clk, and the last slice of a tile reads all of them alone
