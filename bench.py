@@ -113,8 +113,9 @@ def cpu_baseline_sin(w, x, budget_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    # a timed region of tens of milliseconds: shorter ones read a few per cent low and scatter more (clock ramp)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "V1", "V2", "T1", "T2", "E1", "E2"],
                     help="C1..C5: Y = GELU_erf(A.B + bias); V1, V2: batched vector-matrix product C[m,n] = sum_k A[m,k] B[m,n,k]; "
                          "T1, T2: batched transposed-operand product C[b] = A[b]^T B[b]; E1, E2: element-wise sine y = sin(x), fp32")
