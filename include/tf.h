@@ -5,8 +5,9 @@
  *
  *      Y = GELU_erf(A . B + bias)          A[M,K], B[K,N], bias[N], Y[M,N], bf16, fp32 accumulate
  *
- * and the profiling-guided variant loop of the paper (Sec. 3.3, Algorithm 1) over that
- * family.  The paper's objects map as follows:
+ * (further epilogues: tf_epilogue) and the profiling-guided variant loop of the paper (Sec. 3.3,
+ * Algorithm 1) over that family; behind the same calls, the operations of the paper's three case
+ * studies (Sec. 5; tf_op).  The paper's objects map as follows:
  *   hardware profile H ............ tf_hw            (tf_hw_query)
  *   kernel K, candidates K' ....... tf_variant_desc  (tf_variant_enumerate; id 0 is the baseline kernel)
  *   BuildRun(K') .................. tf_variant_run   (a non-OK status is the paper's "res = fail")
