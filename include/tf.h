@@ -144,6 +144,9 @@ typedef struct {
   int32_t trans_a;         /* TF_OP_BATCHED_GEMM_TN, tile kernels: 1 = the A tile is staged as it lies in memory
                               ([k][m]) and transposed by the LDS read; 0 = a separate pass first writes A^T
                               into the workspace and the tile kernel reads that                        */
+  int32_t persistent;      /* TF_OP_BATCHED_GEMM_TN tile kernels: 1 = one work-group per CU walks through many output
+                              tiles and fetches the next tile's K steps while the current one multiplies and
+                              writes out (whole tiles, at least stages - 1 K steps per tile); grid = work-groups */
   int32_t nontemporal;     /* TF_KIND_SIN: 1 = loads and stores marked non-temporal (each element is touched once) */
   int32_t xcd_swizzle;     /* 1: work-group ids renumbered so that neighbouring tiles share an XCD L2 */
   int32_t group_m;         /* tile rows per group in the tile order */

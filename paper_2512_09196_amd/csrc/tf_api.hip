@@ -130,6 +130,8 @@ void build_bgemm_family(tf_problem* p) {
       const tf::LdsKernelInfo& k = tab[i];
       if (!k.direct_to_lds || k.a_bypass_lds || k.waves_k != 1) continue;
       if (pass == 0 && !k.trans_a) continue;
+      // the persistent kernel: whole tiles, enough K steps to keep its ring busy across a tile's output
+      if (k.persistent && (pass == 1 || d.M % k.bm || d.N % k.bn || d.K / 64 < k.stages - 1)) continue;
       if (pass == 1 && (k.trans_a || k.bm < 64 || k.bn < 64 || (k.bm == 128 && k.bn == 128 && k.waves_m * k.waves_n == 4 && k.stages == 2))) continue;
       if (k.bm > 32 && k.bm / 2 >= d.M) continue;
       if (k.bn > 64 && k.bn / 2 >= d.N) continue;
@@ -143,11 +145,17 @@ void build_bgemm_family(tf_problem* p) {
       v.group_m = (int32_t)std::min<long>(tm, 8);
       v.threads = k.threads; v.lds_bytes = k.lds_bytes;
       v.grid = (int32_t)(tm * tn * batch);
+      if (k.persistent) {
+        // one work-group per CU, a multiple of 8 (work-group w runs on XCD w mod 8), no more than the busiest XCD has tiles
+        const long busiest = cdivl(batch, 8) * tm * tn;
+        v.persistent = 1;
+        v.grid = (int32_t)(8 * std::max<long>(1, std::min<long>(std::max(p->hw.cus, 8) / 8, busiest)));
+      }
       v.workspace_bytes = k.trans_a ? 0 : (int64_t)batch * d.M * d.K * 2;
       VariantImpl im;
       im.lds_index = i; im.ktiles_per_split = (int)cdivl(d.K, 64); im.tiles_m = (int)tm; im.tiles_n = (int)tn; im.counter_bytes = 0;
       snprintf(v.name, sizeof(v.name), "bgemm_%dx%dx%d_w%dx%d_s%d_%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n, k.stages,
-               k.trans_a ? "ldstrans" : "pretrans");
+               k.persistent ? "persist" : k.trans_a ? "ldstrans" : "pretrans");
       add_variant(p, v, im);
     }
   }
@@ -414,7 +422,9 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
       p->attr_done[im.lds_index] = 1;
     }
     g.batch_xcd = d.batch % 8 == 0 && (double)im.tiles_m * im.tiles_n * d.batch < 4294967296.0;
-    k.launch(g, dim3((unsigned)(im.tiles_m * im.tiles_n), (unsigned)d.batch), stream);
+    g.batch = d.batch;
+    if (v.persistent) k.launch(g, dim3((unsigned)v.grid), stream);
+    else k.launch(g, dim3((unsigned)(im.tiles_m * im.tiles_n), (unsigned)d.batch), stream);
   } else if (v.kind == TF_KIND_VECMAT_NAIVE) {
     if (d.M > 65535) return fail(TF_E_UNSUPPORTED, "naive variant: M too large for the grid");
     tf::launch_vecmat_naive(g, stream);

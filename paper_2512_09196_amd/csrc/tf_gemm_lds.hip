@@ -77,6 +77,8 @@ struct LdsCfg {
   // ring, rows padded by 16 bytes; used for an output type when one pass fits into the ring.
   static constexpr int ST_ROWS = 32 * WM * WK_;
   // (not behind wave tiles of 256 accumulator registers: the extra code makes the compiler spill there)
+  // the persistent kernel's fp32 staging area lies behind the ring
+  static constexpr int PERSIST_LDS_BYTES = RING_BYTES + ST_ROWS * (BN * 4 + 16);
   static constexpr bool stage_ok(int esz) { return TM * TN <= 8 && ST_ROWS * (BN * esz + 16) <= RING_BYTES; }
   // 32-row tiles serve problems of few rows, where every B element is read by one work-group only: its
   // loads are marked non-temporal
@@ -1012,6 +1014,185 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   else finish(EpiTag<TF_EPI_BIAS_GELU_TANH>{});
 }
 
+// Persistent kernel for the batched transposed-operand product with few K steps per tile
+// (C[b] = A[b]^T B[b], whole tiles only). With four K steps a work-group spends most of its life waiting for
+// its first tiles and for the end of its stores; here one work-group per CU walks through many output tiles
+// and the ring never drains: the transfers of the next tile's K steps are issued while the current tile still
+// multiplies and writes out. The output goes through a staging area of its own behind the ring, so the ring
+// stays free for those transfers.
+//   * work-group w runs on XCD w mod 8; XCD x takes the batch items x, x + 8, ..., so an item's operands are
+//     fetched into one L2; the work-groups of an XCD deal that XCD's tiles out among themselves in turn.
+//   * one "flat step" = one K step of one tile. At flat step f the transfers of step f + D (D = STAGES - 1)
+//     are issued into the buffer that step f - 1 has just left. Past the end the last step is fetched again
+//     (into a buffer nobody reads), which keeps the number of transfers in flight, and so the vmcnt waits,
+//     constant.
+//   * vector-memory operations of a wave complete in issue order, stores included, so a transfer issued
+//     behind a tile's stores would only count as landed once those stores (a trip to memory) are done. The
+//     waves therefore split the memory work: the first half of the waves issue all transfers into the ring,
+//     the second half all stores of the output; every wave multiplies.
+//   * tried and dropped: setting the finished tile's accumulators aside and writing them out pass by pass
+//     during the next tile's first K steps (T2: 49 us against 39 us; every later transfer then completes
+//     behind those stores), and a fourth buffer with half-size output passes (43 us).
+template <class C>
+__global__ void __launch_bounds__(C::THREADS) tf_bgemm_persist_kernel(const GemmParams p) {
+  static_assert(C::TRANSA && C::DIRECT && C::WK == 1 && !C::ABYPASS && C::STAGES >= 3, "transposed staging, direct, three buffers or more");
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  constexpr int D = C::STAGES - 1;
+  // the loading half of the waves moves the tiles exactly as a work-group of half as many wave columns would
+  static_assert(C::WN % 2 == 0, "an even number of wave columns");
+  using CL = LdsCfg<C::BM, C::BN, C::WM, C::WN / 2, C::STAGES, true, false, 1, true>;
+  constexpr int LW = CL::NWAVES, STORE_THREADS = C::THREADS - LW * 64;
+  static_assert(CL::STAGE_BYTES == C::STAGE_BYTES && CL::A_BYTES == C::A_BYTES, "same ring layout");
+  constexpr int PER_TILE = CL::A_PER_WAVE + CL::B_PER_WAVE;
+  constexpr int ROWB = C::BN * 4 + 16, CPR = C::BN * 4 / 16;
+  constexpr int PER_THREAD = C::ST_ROWS * CPR / STORE_THREADS;
+  static_assert(C::ST_ROWS * CPR % STORE_THREADS == 0, "pieces divide over the storing threads");
+  static_assert((D - 1) * PER_TILE < 64, "vmcnt range");
+  static_assert(C::PERSIST_LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
+  char* const staging = smem + C::RING_BYTES;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave / C::WN, wave_n = wave % C::WN;
+  const int lane_m = lane & 31, lane_g = lane >> 5;
+
+  // ---- this work-group's tiles
+  const int tiles = p.tiles_m * p.tiles_n;                       // per batch item
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3, per_xcd = gridDim.x >> 3;
+  const int items_x = (p.batch - xcd + 7) / 8;                   // items x, x + 8, ... < batch
+  const int n_flat = items_x * tiles;
+  const int my_tiles = local < n_flat ? (n_flat - local + per_xcd - 1) / per_xcd : 0;
+  const int nkt = p.K / C::BK;
+  const int total = my_tiles * nkt;
+  if (total <= 0) return;
+  struct Where { const uint16_t* a; const uint16_t* b; char* y; int m0, n0; };
+  auto where = [&](int k) -> Where {                               // k-th tile of this work-group
+    const int j = local + k * per_xcd;
+    const int item = xcd + 8 * (j / tiles), tile = j % tiles;
+    Where w;
+    w.m0 = (tile % p.tiles_m) * C::BM; w.n0 = (tile / p.tiles_m) * C::BN;
+    w.a = p.A + (size_t)item * p.stride_a + w.m0;                  // A[b] is [K][lda], m contiguous
+    w.b = p.B + (size_t)item * p.stride_b + w.n0;
+    w.y = (char*)p.Y + (size_t)item * p.stride_y * 4;
+    return w;
+  };
+
+  // ---- LDS read offsets of this lane (bytes inside a stage), as in tf_gemm_lds_kernel
+  int a_toff[C::TM], b_off[C::TN];
+  {
+    const int b = lane >> 4, s = lane & 15;
+    const int krow = 8 * (b >> 1) + (s >> 2);
+    const int within = (16 * (b & 1) + 4 * (s & 3)) * 2;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) {
+      const int j = (wave_m * C::WTM) / 32 + i;
+      a_toff[i] = krow * C::A_ROW_BYTES + (j ^ b_swz<C::A_PIECES>(krow)) * 64 + within;
+    }
+#pragma unroll
+    for (int t = 0; t < C::TN; ++t) {
+      const int j = (wave_n * C::WTN) / 32 + t;
+      b_off[t] = C::A_BYTES + krow * C::B_ROW_BYTES + (j ^ b_swz<C::B_PIECES>(krow)) * 64 + within;
+    }
+  }
+  auto read_tr = [&](const char* ptr, int row_bytes) -> bf16x8 {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(ptr));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(ptr + 4 * row_bytes));
+    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  };
+
+  f32x16 acc[C::TM][C::TN];
+#pragma unroll
+  for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+    for (int t = 0; t < C::TN; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][t][r] = 0.0f;
+
+  const bool loader = wave < LW;                 // wave-uniform
+  TileLoader<CL> ld;
+  ld.init(p, 0, 0, loader ? wave : 0, lane);     // offsets relative to the tile's corner: whole tiles only
+  const unsigned lds0 = (unsigned)(size_t)smem;
+  const size_t a_step = (size_t)C::BK * p.lda, b_step = (size_t)C::BK * p.ldb;
+
+  // the loader runs D flat steps ahead of the multiplier
+  int l_tile = 0, l_kt = 0, l_stage = 0;
+  Where lw = where(0);
+  auto issue_next = [&]() {
+    if (loader) ld.issue_direct(lw.a + (size_t)l_kt * a_step, lw.b + (size_t)l_kt * b_step, lds0 + l_stage * C::STAGE_BYTES, wave);
+    if (++l_stage == C::STAGES) l_stage = 0;
+    if (l_tile * nkt + l_kt + 1 < total) {       // else: stay on the last step (fetched again, never read)
+      if (++l_kt == nkt) { l_kt = 0; ++l_tile; lw = where(l_tile); }
+    }
+  };
+#pragma unroll
+  for (int s = 0; s < D; ++s) issue_next();
+
+  int c_tile = 0, c_kt = 0, c_stage = 0;
+  Where cw = where(0);
+  for (int f = 0; f < total; ++f) {
+    if (loader) wait_vmcnt<(D - 1) * PER_TILE>();   // this wave's transfers of step f have landed (it issues nothing else)
+    barrier_lds();                 // step f has landed for every wave; every wave has left the buffer of step f - 1
+    issue_next();                  // step f + D into that buffer
+    const char* cur = smem + c_stage * C::STAGE_BYTES;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 af[C::TM], bfr[C::TN];
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i) af[i] = read_tr(cur + a_toff[i] + (16 * kk) * C::A_ROW_BYTES, C::A_ROW_BYTES);
+#pragma unroll
+      for (int t = 0; t < C::TN; ++t) bfr[t] = read_tr(cur + b_off[t] + (16 * kk) * C::B_ROW_BYTES, C::B_ROW_BYTES);
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int t = 0; t < C::TN; ++t)
+          acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[t], af[i], acc[i][t], 0, 0, 0);
+    }
+    if (++c_stage == C::STAGES) c_stage = 0;
+    if (++c_kt == nkt) {
+      // ---- the tile is complete: out through the staging area, 32 rows per wave row at a time
+      char* wr = staging + (wave_m * 32 + lane_m) * ROWB + (wave_n * C::WTN + 4 * lane_g) * 4;
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i) {
+        if (i) barrier_lds();      // the previous pass has been read back
+#pragma unroll
+        for (int t = 0; t < C::TN; ++t)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const f32x4 v = {acc[i][t][4 * q], acc[i][t][4 * q + 1], acc[i][t][4 * q + 2], acc[i][t][4 * q + 3]};
+            *(f32x4*)(wr + (32 * t + 8 * q) * 4) = v;
+          }
+        barrier_lds();
+        if (!loader) {
+#pragma unroll
+          for (int j = 0; j < PER_THREAD; ++j) {
+            const int c = (tid - LW * 64) + STORE_THREADS * j;
+            const int rs = c / CPR, cc = c % CPR;
+            const int m = cw.m0 + (rs >> 5) * C::WTM + 32 * i + (rs & 31);
+            const u32x4 v = *(const u32x4*)(staging + rs * ROWB + cc * 16);
+            __builtin_nontemporal_store(v, (u32x4*)(cw.y + ((size_t)m * p.ldy + cw.n0) * 4 + cc * 16));
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int t = 0; t < C::TN; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][t][r] = 0.0f;
+      c_kt = 0; ++c_tile;
+      if (c_tile < my_tiles) cw = where(c_tile);
+    }
+  }
+  wait_vmcnt<0>();                 // no transfer may still be on its way into this work-group's LDS when it ends
+}
+
+template <class C>
+static void launch_persist(const GemmParams& p, dim3 grid, hipStream_t stream) {
+  hipLaunchKernelGGL(tf_bgemm_persist_kernel<C>, grid, dim3(C::THREADS), C::PERSIST_LDS_BYTES, stream, p);
+}
+
+template <class C>
+static LdsKernelInfo make_persist_info();
+
 template <class C>
 static void launch_lds(const GemmParams& p, dim3 grid, hipStream_t stream) {
   hipLaunchKernelGGL(tf_gemm_lds_kernel<C>, grid, dim3(C::THREADS), C::LDS_BYTES, stream, p);
@@ -1023,8 +1204,19 @@ static LdsKernelInfo make_info() {
   k.bm = C::BM; k.bn = C::BN; k.bk = C::BK; k.waves_m = C::WM; k.waves_n = C::WN; k.waves_k = C::WK;
   k.stages = C::STAGES; k.direct_to_lds = C::DIRECT ? 1 : 0; k.a_bypass_lds = C::ABYPASS ? 1 : 0; k.trans_a = C::TRANSA ? 1 : 0;
   k.threads = C::THREADS; k.lds_bytes = C::LDS_BYTES; k.fused_ok = C::FUSED_OK ? 1 : 0;
+  k.persistent = 0;
   k.func = (const void*)tf_gemm_lds_kernel<C>;
   k.launch = launch_lds<C>;
+  return k;
+}
+
+template <class C>
+static LdsKernelInfo make_persist_info() {
+  LdsKernelInfo k = make_info<C>();
+  k.persistent = 1;
+  k.lds_bytes = C::PERSIST_LDS_BYTES;
+  k.func = (const void*)tf_bgemm_persist_kernel<C>;
+  k.launch = launch_persist<C>;
   return k;
 }
 
@@ -1079,6 +1271,7 @@ static LdsKernelInfo g_table[] = {
     make_info<T256x128_d2>(), make_info<T64x64_d3>(),
     make_info<T128x128_w8s2>(), make_info<T128x64_d2>(), make_info<T64x128_d2>(), make_info<T64x64_d2>(),
     make_info<K256x256_w8a>(), make_info<K256x256_w8b>(),
+    make_persist_info<T128x128_w8>(), make_persist_info<T128x128_d3>(),
 };
 
 int lds_kernel_count() { return (int)(sizeof(g_table) / sizeof(g_table[0])); }

@@ -26,6 +26,7 @@ struct GemmParams {
   int group_m;            // tile rows per L2 group in the tile order (>= 1)
   int xcd_swizzle;        // 1: remap work-group ids so that neighbouring tiles share an XCD
   int slice_major;        // split-K tile order: 1 = slice by slice (two-kernel reduction), 0 = the slices of a tile side by side
+  int batch;              // batched problems: number of items (the persistent kernel deals them out itself)
   int batch_xcd;          // batched problems: 1 = all tiles of a batch item on one XCD (batch a multiple of 8)
   int ws_vec16;           // 1: the split-K workspace starts on a 16-byte boundary (its rows of N floats then do too)
   int y_vec16;            // 1: every row of Y (of every batch item) starts on a 16-byte boundary
@@ -37,6 +38,7 @@ struct LdsKernelInfo {
   int trans_a;            // 1: A is [K][lda] with m contiguous (staged and read like the B tile)
   int threads, lds_bytes;
   int fused_ok;           // 1: the kernel contains the in-kernel split-K reduction (fused_reduce 1 and 2)
+  int persistent;         // 1: tf_bgemm_persist_kernel (one work-group per CU walks through many tiles; grid.x = work-groups)
   const void* func;       // kernel symbol, for hipFuncGetAttributes / occupancy queries
   void (*launch)(const GemmParams&, dim3 grid, hipStream_t);
 };

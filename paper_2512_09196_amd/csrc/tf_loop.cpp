@@ -139,6 +139,13 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
     one.op = TF_OP_GEMM_EPILOGUE;
     tf_variant_desc v1 = *v;
     v1.trans_a = 0;
+    if (v->persistent) {
+      // one work-group per CU walks through the tiles and never lets its ring drain: the tile model over all
+      // tiles, without the start-up that every work-group of the plain kernels pays
+      v1.persistent = 0;
+      v1.grid = (int32_t)(((pr->M + v->bm - 1) / v->bm) * (long)((pr->N + v->bn - 1) / v->bn) * (long)items);
+      return fmax(0.8 * tf_predict_us(&one, hw, &v1), floor_us + 4.0);
+    }
     double us = fmax(tf_predict_us(&one, hw, &v1), floor_us + 4.0);
     // with few K steps per tile a work-group is a short read - multiply - write sequence; alone on its CU
     // it leaves memory idle while it multiplies and the matrix pipes idle while it writes (measured 1.4-1.6x)

@@ -121,11 +121,12 @@ def test_enumerate_the_other_operations_without_gpu():
         assert any(v.trans_a for v in tiles) and any(not v.trans_a for v in tiles)
         for v in tiles:
             assert v.split_k == 1 and v.direct_to_lds == 1
-            assert v.grid == -(-1024 // v.bm) * -(-1024 // v.bn) * 32
+            assert v.grid == (hw.cus if v.persistent else -(-1024 // v.bm) * -(-1024 // v.bn) * 32)
             assert v.workspace_bytes == (0 if v.trans_a else 32 * 1024 * 256 * 2)
+        assert sum(v.persistent for v in tiles) >= 2 and all(v.trans_a and v.stages >= 3 for v in tiles if v.persistent)
         pred = {v.name.decode(): tf.predict_us(p.desc, hw, v) for v in vs}
         best = min(pred, key=pred.get)
-        assert best.endswith("ldstrans")                                       # the extra pass is never predicted to pay
+        assert not best.endswith("pretrans")                                   # the extra pass is never predicted to pay
     with tf.Problem(40, 24, 96, op=tf.TF_OP_BATCHED_GEMM_TN, batch=2) as p:  # K not a multiple of 64
         assert [v.kind for v in p.variants()] == [tf.TF_KIND_BGEMM_TN_NAIVE]
     # element-wise sine: the four-element baseline first, then one kernel per launch shape, also as a grid-stride launch

@@ -85,6 +85,15 @@ def test_shapes_the_tile_kernels_do_not_take_run_on_the_naive_kernel(shape):
     assert ran == ["bgemm_tn_naive_1elem_per_thread"]
 
 
+@pytest.mark.parametrize("shape", [(3, 256, 384, 192), (16, 128, 128, 128), (9, 256, 128, 256), (1, 128, 256, 512), (40, 128, 128, 192)])
+def test_whole_tile_shapes_include_the_persistent_kernels(shape):
+    # batches that are and are not multiples of 8, fewer tiles than work-groups and more, 2 to 8 K steps per tile
+    nb, M, N, K = shape
+    A, B = wl.make_bgemm(nb, M, N, K, seed=300 + nb)
+    ran = check_all(nb, M, N, K, A, B)
+    assert any(n.endswith("persist") for n in ran)
+
+
 def test_leading_dimensions_and_item_strides():
     nb, M, N, K = 3, 200, 136, 128
     A, B = wl.make_bgemm(nb, M, N, K, seed=77)
