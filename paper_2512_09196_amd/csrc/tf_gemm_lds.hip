@@ -1031,8 +1031,9 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
 //     waves therefore split the memory work: the first half of the waves issue all transfers into the ring,
 //     the second half all stores of the output; every wave multiplies.
 //   * tried and dropped: setting the finished tile's accumulators aside and writing them out pass by pass
-//     during the next tile's first K steps (T2: 49 us against 39 us; every later transfer then completes
-//     behind those stores), and a fourth buffer with half-size output passes (43 us).
+//     during the next tile's first K steps (T2: 48 us against 42 us, also with the waves split as above: the
+//     second barrier in the middle of a step costs more than the overlap gains), and a fourth buffer with
+//     half-size output passes (43 us against 39 us).
 template <class C>
 __global__ void __launch_bounds__(C::THREADS) tf_bgemm_persist_kernel(const GemmParams p) {
   static_assert(C::TRANSA && C::DIRECT && C::WK == 1 && !C::ABYPASS && C::STAGES >= 3, "transposed staging, direct, three buffers or more");
