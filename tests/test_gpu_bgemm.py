@@ -98,6 +98,11 @@ def test_leading_dimensions_and_item_strides():
     nb, M, N, K = 3, 200, 136, 128
     A, B = wl.make_bgemm(nb, M, N, K, seed=77)
     check_all(nb, M, N, K, A, B, lda=M + 8, ldb=N + 24, ldy=N + 4, extra_rows=3)
+    # whole tiles, so that the persistent kernels take part
+    nb, M, N, K = 5, 256, 128, 192
+    A, B = wl.make_bgemm(nb, M, N, K, seed=78)
+    ran = check_all(nb, M, N, K, A, B, lda=M + 8, ldb=N + 24, ldy=N + 4, extra_rows=3)
+    assert any(n.endswith("persist") for n in ran)
 
 
 def test_integer_operands_are_bit_exact():
