@@ -34,7 +34,16 @@ HBM_TRAFFIC_KIB = {
     ("C2", "lds_128x128x64_w4x2_s3_direct_sk1"): (24690.6, 8192.0),
     ("C2", "lds_128x128x64_w2x4_s4_direct_sk1"): (24694.9, 8192.0),
     ("C2", "lds_128x128x64_w2x2x2_s3_direct_sk1"): (24690.5, 8192.0),
+    ("C2", "lds_128x128x64_w2x2x2_s4_direct_sk1"): (24699.5, 8192.0),
+    ("C2", "lds_128x128x64_w2x4_s3_direct_sk1x"): (24696.9, 8192.0),
+    ("C2", "lds_128x128x64_w4x2_s3_direct_sk1x"): (24699.6, 8193.1),
+    ("C2", "lds_128x128x64_w2x4_s4_direct_sk1x"): (24700.9, 8192.0),
+    ("C2", "lds_128x128x64_w2x2x2_s3_direct_sk1x"): (24700.5, 8192.0),
+    ("C2", "lds_128x128x64_w2x2x2_s4_direct_sk1x"): (24699.5, 8192.0),
     ("C3", "lds_256x256x64_w2x4_s2_direct_sk1"): (314016.0, 88064.9),
+    ("C3", "lds_256x256x64_w4x2_s2_direct_sk1"): (303331.0, 88073.8),
+    ("C3", "lds_256x256x64_w2x4_s2_direct_sk1x"): (309078.1, 88064.3),
+    ("C3", "lds_256x256x64_w4x2_s2_direct_sk1x"): (303378.0, 88067.8),
     ("C4", "lds_32x64x64_w1x2_s4_direct_sk2l"): (67568.4, 1290.9),
     ("C4", "lds_32x64x64_w1x2_s4_direct_sk2r"): (66466.8 + 546.0, 1024.0 + 256.0),      # GEMM kernel + reduce kernel
     ("V2", "vecmat_r1_u4_w4_g0"): (525341.2, 1024.1),

@@ -144,6 +144,9 @@ typedef struct {
   int32_t trans_a;         /* TF_OP_BATCHED_GEMM_TN, tile kernels: 1 = the A tile is staged as it lies in memory
                               ([k][m]) and transposed by the LDS read; 0 = a separate pass first writes A^T
                               into the workspace and the tile kernel reads that                        */
+  int32_t k_rotate;        /* tile kernels without split-K: 1 = the work-groups of XCD x walk through K starting x/8 of the
+                              way in and wrapping round, so that the eight XCDs fetch different slabs of A and B at
+                              any moment (a different, equally valid, summation order) */
   int32_t persistent;      /* TF_OP_BATCHED_GEMM_TN tile kernels: 1 = one work-group per CU walks through many output
                               tiles and fetches the next tile's K steps while the current one multiplies and
                               writes out (whole tiles, at least stages - 1 K steps per tile); grid = work-groups */

@@ -253,8 +253,12 @@ void build_family(tf_problem* p) {
       for (int fused = fused_mode; fused >= 0; fused -= fused_mode) {
         if (s == 1 && fused == 0) continue;
         if (s > 1 && fused != 0 && !k.fused_ok) continue;
+        // without split-K also with the K order rotated by XCD (worth it for some shapes, not for others)
+        const int rotations = (s == 1 && k.direct_to_lds && ktiles >= 8) ? 2 : 1;
+        for (int kr = 0; kr < rotations; ++kr) {
         tf_variant_desc v;
         memset(&v, 0, sizeof(v));
+        v.k_rotate = kr;
         v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n; v.waves_k = k.waves_k;
         v.stages = k.stages; v.split_k = s; v.fused_reduce = (s > 1) ? fused : 0;
         v.direct_to_lds = k.direct_to_lds; v.a_bypass_lds = k.a_bypass_lds; v.xcd_swizzle = 1;
@@ -269,8 +273,9 @@ void build_family(tf_problem* p) {
         if (k.waves_k > 1) snprintf(wk, sizeof(wk), "x%d", k.waves_k);
         snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d%s_s%d_%s_sk%d%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n,
                  wk, k.stages, k.a_bypass_lds ? "areg" : (k.direct_to_lds ? "direct" : "regs"), s,
-                 s > 1 ? (fused == 2 ? "l" : (fused ? "f" : "r")) : "");
+                 s > 1 ? (fused == 2 ? "l" : (fused ? "f" : "r")) : (kr ? "x" : ""));
         add_variant(p, v, im);
+        }
       }
     }
   }
@@ -382,6 +387,7 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
                 (d.op != TF_OP_BATCHED_GEMM_TN || (size_t)d.stride_y * esz % 16 == 0);
   }
   g.slice_major = v.split_k > 1 && v.fused_reduce == 0 && v.kind == TF_KIND_MFMA_LDS;
+  g.k_rotate = v.k_rotate;
   g.epi = d.epi; g.split_k = v.split_k; g.fused_reduce = v.fused_reduce; g.group_m = v.group_m > 0 ? v.group_m : 1; g.xcd_swizzle = v.xcd_swizzle;
   if (v.kind == TF_KIND_SIN) {
     if (im.lds_index < 0) {

@@ -589,6 +589,13 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   // tile instead (into a buffer nobody reads any more): the number of transfers in flight is
   // then the same in every iteration and the vmcnt waits are constants.
   const int last = nkt - 1;
+  // Order of the K tiles (a sum: any order is right). Without split-K the work-groups of XCD x start an
+  // eighth of the way further into K than those of XCD x - 1 and wrap round: at any moment the eight XCDs
+  // then fetch eight different slabs of A and B, and seven times out of eight a line has already been
+  // brought into the memory-side cache by another XCD instead of all eight waiting for it together.
+  // (All work-groups of an XCD keep the same order, so they still share panels in its L2.)
+  const int k_rot = (p.k_rotate && nkt > 0) ? (int)(((blockIdx.x & 7u) * (unsigned)nkt) >> 3) : 0;
+  auto k_order = [&](int t) { const int u = t + k_rot; return u >= nkt ? u - nkt : u; };
   if constexpr (C::ABYPASS) {
     // A straight from memory into MFMA operand registers: lane l of a wave needs, for row block
     // i and k16-step kk, the 16 bytes at row 32 i + (l & 31), k = 16 kk + 8 (l >> 5): one
@@ -604,8 +611,8 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       if (m >= p.M) m = p.M - 1;
       a_goff[i] = ((unsigned)m * (unsigned)p.lda + 8u * (lane >> 5)) * 2u;
     }
-    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * a_step; };
-    auto tile_b = [&](int t) { return Bk + (long)(t < last ? t : last) * b_step; };
+    auto tile_a = [&](int t) { return Ak + (long)k_order(t < last ? t : last) * a_step; };
+    auto tile_b = [&](int t) { return Bk + (long)k_order(t < last ? t : last) * b_step; };
     auto load_a = [&](u32x4 (&dst)[C::TM][4], const uint16_t* base) {
 #pragma unroll
       for (int i = 0; i < C::TM; ++i)
@@ -695,8 +702,8 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     constexpr int PER_TILE = C::A_PER_WAVE + C::B_PER_WAVE;
     static_assert((D - 1) * PER_TILE < 64, "vmcnt range");
     const unsigned lds0 = (unsigned)(size_t)smem;
-    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * a_step; };
-    auto tile_b = [&](int t) { return Bk + (long)(t < last ? t : last) * b_step; };
+    auto tile_a = [&](int t) { return Ak + (long)k_order(t < last ? t : last) * a_step; };
+    auto tile_b = [&](int t) { return Bk + (long)k_order(t < last ? t : last) * b_step; };
     bf16x8 fa[2][C::KS][C::TM], fb[2][C::KS][C::TN];
     auto read_tile = [&](const char* stage, bf16x8 (&a)[C::KS][C::TM], bf16x8 (&b)[C::KS][C::TN]) {
 #pragma unroll
@@ -760,8 +767,8 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     constexpr int PER_TILE = C::A_PER_WAVE + C::B_PER_WAVE;   // transfers per wave per tile
     static_assert((D - 1) * PER_TILE < 64, "vmcnt range");
     const unsigned lds0 = (unsigned)(size_t)smem;
-    auto tile_a = [&](int t) { return Ak + (long)(t < last ? t : last) * a_step; };
-    auto tile_b = [&](int t) { return Bk + (long)(t < last ? t : last) * b_step; };
+    auto tile_a = [&](int t) { return Ak + (long)k_order(t < last ? t : last) * a_step; };
+    auto tile_b = [&](int t) { return Bk + (long)k_order(t < last ? t : last) * b_step; };
     // A wave issues in order: a burst of transfers right after the barrier would hold back the
     // MFMAs behind it for as long as the load unit takes to accept the burst (the four waves of a
     // CU share one, at about 16 cycles per transfer). So the transfers of a tile are dealt out

@@ -27,6 +27,7 @@ struct GemmParams {
   int xcd_swizzle;        // 1: remap work-group ids so that neighbouring tiles share an XCD
   int slice_major;        // split-K tile order: 1 = slice by slice (two-kernel reduction), 0 = the slices of a tile side by side
   int batch;              // batched problems: number of items (the persistent kernel deals them out itself)
+  int k_rotate;           // 1: the K tiles of a work-group start a (blockIdx mod 8) / 8 of the way in and wrap round
   int batch_xcd;          // batched problems: 1 = all tiles of a batch item on one XCD (batch a multiple of 8)
   int ws_vec16;           // 1: the split-K workspace starts on a 16-byte boundary (its rows of N floats then do too)
   int y_vec16;            // 1: every row of Y (of every batch item) starts on a 16-byte boundary

@@ -263,7 +263,10 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   double inflight = (double)co_resident * (v->stages - 1) * stage_bytes / 32768.0;
   if (inflight > 1.0) inflight = 1.0;
   // launch, first tile from HBM and drain: about 4 us per launch
-  return fmax(us, (hbm_us + ws_us) / (0.75 * inflight)) + 4.0 + reduce_us + fused_tail_us;
+  // K order rotated by XCD: measured 2-4 % faster on 2048^3, between equal and 10 % faster on
+  // 4096 x 11008 x 4096 depending on the kernel and the chip: proposed first, the plain order right behind
+  const double rot = v->k_rotate ? 0.98 : 1.0;
+  return fmax(us * rot, (hbm_us + ws_us) / (0.75 * inflight)) + 4.0 + reduce_us + fused_tail_us;
 }
 
 // ------------------------------------------------------------------ Proposal
