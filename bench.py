@@ -137,7 +137,7 @@ def main():
                     help="launch a plain device copy of known size instead (reference reading for the HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        log("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)." % args.gpus)
+        log("bench.py: the library runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)." % args.gpus)
         sys.exit(2)
 
     import numpy as np
