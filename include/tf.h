@@ -26,6 +26,11 @@
  *   - A kernel launch is asynchronous on the given stream; tf_variant_profile and tf_tune
  *     synchronise that stream before they return.
  *   - There is no CPU fallback: without a GPU every launching call fails with TF_E_LAUNCH.
+ *   - A tf_problem is not thread safe (it owns a lazily allocated workspace and per-kernel set-up
+ *     flags): one thread at a time per problem; different problems are independent. Launches of one
+ *     problem that use its own split-K workspace must be ordered on one stream (they share it).
+ *   - After one eager call of a variant, tf_variant_run records nothing but kernel launches, so it
+ *     may be captured into a HIP graph.
  */
 #ifndef TF_H_
 #define TF_H_
