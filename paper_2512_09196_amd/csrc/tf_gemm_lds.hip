@@ -265,11 +265,18 @@ __device__ __forceinline__ void wait_vmcnt() {
 // work-group on another XCD (another L2) reads the new value from memory. Split-K uses it for
 // the partial sums instead of a device-wide fence, which would write back and invalidate the
 // whole L2 twice per work-group.
+// (One 16-byte store with the device-scope bit, as the compiler emits for a relaxed device-scope atomic store
+// of one dword; the atomic builtins themselves stop at 8 bytes. ptr is 16-byte aligned.)
 __device__ __forceinline__ void store_through_f32x4(float* ptr, const f32x4 v) {
-  __hip_atomic_store(ptr + 0, v[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(ptr + 1, v[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(ptr + 2, v[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __hip_atomic_store(ptr + 3, v[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(ptr), "v"(v) : "memory");
+}
+// The matching load: 16 bytes past this XCD's L2. Only issues it; the data is there after wait_through().
+__device__ __forceinline__ void load_through_f32x4(f32x4& dst, const float* ptr) {
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(dst) : "v"(ptr) : "memory");
+}
+// Waits for every load above; the values pass through it, so that no use of them can be moved ahead of the wait.
+__device__ __forceinline__ void wait_through(f32x4& a, f32x4& b, f32x4& c, f32x4& d) {
+  asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) :: "memory");
 }
 
 // Split-K: one slice's partial tile -> workspace (fp32, [slice][M][N]).
@@ -300,6 +307,33 @@ __device__ __forceinline__ void store_partial(const f32x16 (&acc)[C::TM][C::TN],
 template <class C, bool FULL, bool THROUGH>
 __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0) {
   const size_t slice = (size_t)p.M * p.N;
+  if constexpr (THROUGH && FULL) {
+    // whole tiles: 16-byte device-scope loads, a slice's worth in flight at a time
+    constexpr int NV = C::TM_OUT * C::TN * 4;
+    static_assert(NV % 4 == 0 && NV <= 16, "register budget of the exchange");
+    f32x4 sum[NV];
+#pragma unroll
+    for (int x = 0; x < NV; ++x) sum[x] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int sidx = 0; sidx < p.split_k; ++sidx) {
+      f32x4 v[NV];
+#pragma unroll
+      for (int x = 0; x < NV; ++x) {
+        const int i = x / (C::TN * 4), t = (x / 4) % C::TN, q = x % 4;
+        load_through_f32x4(v[x], p.ws + (size_t)sidx * slice + (size_t)(wm0 + 32 * i) * p.N + (wn0 + 32 * t + 8 * q));
+      }
+#pragma unroll
+      for (int x = 0; x < NV; x += 4) wait_through(v[x], v[x + 1], v[x + 2], v[x + 3]);
+#pragma unroll
+      for (int x = 0; x < NV; ++x) sum[x] += v[x];
+    }
+#pragma unroll
+    for (int x = 0; x < NV; ++x) {
+      const int i = x / (C::TN * 4), t = (x / 4) % C::TN, q = x % 4;
+      acc[i][t][4 * q] = sum[x][0]; acc[i][t][4 * q + 1] = sum[x][1];
+      acc[i][t][4 * q + 2] = sum[x][2]; acc[i][t][4 * q + 3] = sum[x][3];
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < C::TM_OUT; ++i) {
     const int m = wm0 + 32 * i;
