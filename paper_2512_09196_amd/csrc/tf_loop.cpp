@@ -243,9 +243,9 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
       // ... but the last slice of a tile still sums all slices and runs the epilogue alone, on one CU
       fused_tail_us = 2.0 + 3.0 * big + v->bm * (double)v->bn * 4.0 * (1.0 + 2.0 * v->split_k) / 64.0 / mhz;
     } else if (v->fused_reduce) {
-      // partial tiles go out and come back through device-scope scalar accesses at about
-      // 2 B/clk, and the last slice of a tile reads all of them alone
-      fused_tail_us = v->bm * (double)v->bn * 4.0 * (1.0 + v->split_k) / 2.0 / mhz;
+      // partial tiles go out and come back through 16-byte device-scope accesses; the store acknowledgement,
+      // the ticket and one load round trip per slice are dependent trips to memory on the last slice's path
+      fused_tail_us = 4.0 + 2.5 * v->split_k + v->bm * (double)v->bn * 4.0 * (1.0 + v->split_k) / 32.0 / mhz;
     } else {
       tile_end = v->bm * (double)v->bn * 4.0 / 32.0;
       reduce_us = 3.7 + (v->split_k + 0.5) * 4.0 * pr->M * (double)pr->N / (0.4 * hw->hbm_gbs_peak * 1e3);
