@@ -149,6 +149,12 @@ typedef struct {
   int32_t trans_a;         /* TF_OP_BATCHED_GEMM_TN, tile kernels: 1 = the A tile is staged as it lies in memory
                               ([k][m]) and transposed by the LDS read; 0 = a separate pass first writes A^T
                               into the workspace and the tile kernel reads that                        */
+  int32_t stream_k;        /* 1: stream-K scheduling. All but the last one to two rounds of tiles are computed whole,
+                              one work-group each; the K steps of the remaining tiles are dealt out evenly to one
+                              further work-group per CU, each taking up to three (tile, K range) pieces; a tile
+                              has at most two contributors, who exchange fp32 partial tiles through the workspace
+                              like two split-K slices (offered when the tile count is above the CU count and no
+                              multiple of it; split_k stays 1) */
   int32_t k_rotate;        /* tile kernels without split-K: 1 = the work-groups of XCD x walk through K starting x/8 of the
                               way in and wrapping round, so that the eight XCDs fetch different slabs of A and B at
                               any moment (a different, equally valid, summation order) */

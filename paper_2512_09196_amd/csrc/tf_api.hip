@@ -35,6 +35,7 @@ struct VariantImpl {
   int ktiles_per_split;
   int tiles_m, tiles_n;
   size_t counter_bytes;   // leading part of the workspace
+  int sk_first, sk_tiles; // stream-K: tiles computed whole (= first shared work-group), tiles whose K steps are shared
 };
 
 }  // namespace
@@ -128,7 +129,7 @@ void build_bgemm_family(tf_problem* p) {
   for (int pass = 0; pass < 2; ++pass) {          // 0: transposed staging, 1: separate transposing pass
     for (int i = 0; i < tf::lds_kernel_count(); ++i) {
       const tf::LdsKernelInfo& k = tab[i];
-      if (!k.direct_to_lds || k.a_bypass_lds || k.waves_k != 1) continue;
+      if (!k.direct_to_lds || k.a_bypass_lds || k.waves_k != 1 || k.stream_k) continue;
       if (pass == 0 && !k.trans_a) continue;
       // the persistent kernel: whole tiles, enough K steps to keep its ring busy across a tile's output
       if (k.persistent && (pass == 1 || d.M % k.bm || d.N % k.bn || d.K / 64 < k.stages - 1)) continue;
@@ -152,7 +153,7 @@ void build_bgemm_family(tf_problem* p) {
         v.grid = (int32_t)(8 * std::max<long>(1, std::min<long>(std::max(p->hw.cus, 8) / 8, busiest)));
       }
       v.workspace_bytes = k.trans_a ? 0 : (int64_t)batch * d.M * d.K * 2;
-      VariantImpl im;
+      VariantImpl im{};
       im.lds_index = i; im.ktiles_per_split = (int)cdivl(d.K, 64); im.tiles_m = (int)tm; im.tiles_n = (int)tn; im.counter_bytes = 0;
       snprintf(v.name, sizeof(v.name), "bgemm_%dx%dx%d_w%dx%d_s%d_%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n, k.stages,
                k.persistent ? "persist" : k.trans_a ? "ldstrans" : "pretrans");
@@ -236,6 +237,29 @@ void build_family(tf_problem* p) {
     const tf::LdsKernelInfo& k = tab[i];
     if (k.trans_a) continue;                               // kernels of the transposed-operand product
     if (k.direct_to_lds && d.K % 64 != 0) continue;        // no zero fill on the direct path
+    if (k.stream_k) {
+      // stream-K: more tiles than CUs, not a whole number of rounds, and enough K steps to be worth sharing
+      const long tm = cdivl(d.M, k.bm), tn = cdivl(d.N, k.bn), T = tm * tn;
+      if (T <= cus || T % cus == 0 || ktiles < 8 || T > 0x7fffffffL / 16 || k.lds_bytes > p->hw.lds_bytes_per_cu) continue;
+      const long dp = (T / cus - 1) * cus;                 // the last one to two rounds are shared: at most two contributors per tile
+      tf_variant_desc v;
+      memset(&v, 0, sizeof(v));
+      v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n; v.waves_k = k.waves_k;
+      v.stages = k.stages; v.split_k = 1; v.fused_reduce = 1; v.stream_k = 1;
+      v.direct_to_lds = k.direct_to_lds; v.xcd_swizzle = 1; v.group_m = (int32_t)std::min<long>(tm, 8);
+      v.threads = k.threads; v.lds_bytes = k.lds_bytes;
+      v.grid = (int32_t)(dp + cus);
+      VariantImpl im{};
+      im.lds_index = i; im.ktiles_per_split = (int)ktiles; im.tiles_m = (int)tm; im.tiles_n = (int)tn;
+      im.counter_bytes = (size_t)((T * 8 + 255) / 256 * 256);
+      im.sk_first = (int)dp; im.sk_tiles = (int)(T - dp);
+      v.workspace_bytes = (int64_t)(im.counter_bytes + (size_t)2 * d.M * d.N * 4);
+      char wk[8] = "";
+      if (k.waves_k > 1) snprintf(wk, sizeof(wk), "x%d", k.waves_k);
+      snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d%s_s%d_direct_streamk", k.bm, k.bn, k.bk, k.waves_m, k.waves_n, wk, k.stages);
+      add_variant(p, v, im);
+      continue;
+    }
     if (k.bm > 32 && k.bm / 2 >= d.M) continue;            // tile more than twice the problem
     if (k.bn > 64 && k.bn / 2 >= d.N) continue;
     if (k.lds_bytes > p->hw.lds_bytes_per_cu) continue;
@@ -265,7 +289,7 @@ void build_family(tf_problem* p) {
         v.group_m = (int32_t)std::min<long>(tm, 8);
         v.threads = k.threads; v.lds_bytes = k.lds_bytes;
         v.grid = (int32_t)(tm * tn * s);
-        VariantImpl im;
+        VariantImpl im{};
         im.lds_index = i; im.ktiles_per_split = (int)per; im.tiles_m = (int)tm; im.tiles_n = (int)tn;
         im.counter_bytes = s > 1 ? (size_t)((tm * tn * 8 + 255) / 256 * 256) : 0;
         v.workspace_bytes = s > 1 ? (int64_t)(im.counter_bytes + (size_t)s * d.M * d.N * 4) : 0;
@@ -303,7 +327,7 @@ void build_family(tf_problem* p) {
           v.fused_reduce = s > 1 ? fused : 0;
           v.group_m = 1; v.threads = k.threads; v.lds_bytes = k.lds_bytes;
           v.grid = (int32_t)(tn * s);
-          VariantImpl im;
+          VariantImpl im{};
           im.lds_index = i; im.ktiles_per_split = (int)per; im.tiles_m = 1; im.tiles_n = (int)tn;
           im.counter_bytes = s > 1 ? (size_t)((tn * 8 + 255) / 256 * 256) : 0;
           v.workspace_bytes = s > 1 ? (int64_t)(im.counter_bytes + (size_t)s * d.M * d.N * 4) : 0;
@@ -444,7 +468,12 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
     tf::launch_mfma_direct(g, stream);
   } else {
     g.tiles_m = im.tiles_m; g.tiles_n = im.tiles_n; g.ktiles_per_split = im.ktiles_per_split;
-    if (v.split_k > 1) {
+    if (v.stream_k) {
+      // two contributors per shared tile exchange partial tiles like two split-K slices, through memory
+      g.stream_k = 1; g.split_k = 2; g.fused_reduce = 1; g.slice_major = 0;
+      g.sk_first_wg = im.sk_first; g.sk_tiles = im.sk_tiles; g.sk_wgs = v.grid - im.sk_first;
+    }
+    if (v.split_k > 1 || v.stream_k) {
       if (!ws) {
         if (p->own_ws_bytes < (size_t)v.workspace_bytes) {
           if (p->own_ws) { (void)hipFree(p->own_ws); p->own_ws = nullptr; p->own_ws_bytes = 0; }

@@ -92,6 +92,26 @@ __device__ __forceinline__ float activate(float z, int epi) {
 //    the next tile column, so a group re-uses its A panels while B panels stream.
 struct TileCoord { int tm, tn, ks; };
 
+// Position t in the grouped tile order -> tile coordinates (ks = 0).
+__device__ __forceinline__ TileCoord tile_at(const GemmParams& p, int t) {
+  TileCoord c;
+  c.ks = 0;
+  const int gsz = p.group_m * p.tiles_n;
+  const int g = t / gsz;
+  const int first_m = g * p.group_m;
+  const int rows = (p.tiles_m - first_m) < p.group_m ? (p.tiles_m - first_m) : p.group_m;
+  const int in_g = t - g * gsz;
+  c.tm = first_m + in_g % rows;
+  c.tn = in_g / rows;
+  return c;
+}
+// id in [0, total) -> the same range renumbered so that XCD (id mod 8) owns one contiguous run
+__device__ __forceinline__ int xcd_run(int id, int total) {
+  const int xcd = id & 7, local = id >> 3;
+  const int base = total >> 3, rem = total & 7;
+  return xcd * base + (xcd < rem ? xcd : rem) + local;
+}
+
 __device__ __forceinline__ TileCoord map_tile(const GemmParams& p, int wg) {
   const int tiles = p.tiles_m * p.tiles_n;
   const int total = tiles * p.split_k;

@@ -73,6 +73,7 @@ struct LdsCfg {
   // registers: behind bigger ones its code makes the compiler spill, and the scratch memory
   // that reserves per wave slows every launch of the kernel, split or not.
   static constexpr bool FUSED_OK = TM * TN <= 4;
+  static constexpr bool SEGMENTS = false;                  // see StreamKCfg
   // Output staging (see epilogue_staged): each pass moves 32 rows per wave row (and k group) through the tile
   // ring, rows padded by 16 bytes; used for an output type when one pass fits into the ring.
   static constexpr int ST_ROWS = 32 * WM * WK_;
@@ -490,12 +491,57 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   const int wave_k = wave / (C::WM * C::WN), wave_mn = wave % (C::WM * C::WN);
   const int wave_m = wave_mn / C::WN, wave_n = wave_mn % C::WN;
 
-  const TileCoord tc = map_tile(p, tile_id);
-  const int m0 = tc.tm * C::BM, n0 = tc.tn * C::BN;
+  // A work-group computes one segment = one tile over one range of K tiles - except the stream-K work-groups,
+  // which take an equal share of the K steps of the last tiles each, a share that may span up to three tiles
+  // (the end of one, a whole one, the beginning of the next). The host arranges that a tile has at most two
+  // contributors: they exchange partial tiles like two split-K slices (slice 0 = the part that begins the
+  // tile), and since a sum of two terms does not depend on their order the result is the same whoever
+  // arrives last.
   const int ktiles_total = (p.K + C::BK - 1) / C::BK;
-  const int kt_begin = tc.ks * p.ktiles_per_split;
-  int kt_end = kt_begin + p.ktiles_per_split;
-  if (kt_end > ktiles_total) kt_end = ktiles_total;
+  // (Compiled only into the stream-K instances, StreamKCfg<>; in every other kernel the loop below is one pass
+  // and costs nothing: wrapped around the ordinary kernels it cost them 1-2 % through register pressure.)
+  constexpr bool SEGMENTS = C::SEGMENTS;
+  static_assert(!SEGMENTS || C::FUSED_OK, "stream-K needs the in-kernel reduction");
+  int sk_cur = 0, sk_end = 0;
+  const bool stream_k = SEGMENTS && p.stream_k;
+  const bool stream_wg = stream_k && tile_id >= p.sk_first_wg;
+  if (stream_wg) {
+    // (the shares of the work-groups of one XCD lie side by side: they work on neighbouring tiles)
+    const long g = xcd_run(tile_id - p.sk_first_wg, p.sk_wgs), total_steps = (long)p.sk_tiles * ktiles_total;
+    sk_cur = (int)(g * total_steps / p.sk_wgs);
+    sk_end = (int)((g + 1) * total_steps / p.sk_wgs);
+  }
+  bool more = true;
+  for (int seg = 0; more; ++seg) {
+  if (seg) {                       // the ring, the bias copy and the staging area are about to be reused
+    wait_vmcnt<0>();
+    __syncthreads();
+  }
+  TileCoord tc;
+  int kt_begin, kt_end;
+  bool split = p.split_k > 1;      // this segment is one of several contributions to its tile
+  if (!stream_k) {
+    tc = map_tile(p, tile_id);
+    kt_begin = tc.ks * p.ktiles_per_split;
+    kt_end = kt_begin + p.ktiles_per_split;
+    if (kt_end > ktiles_total) kt_end = ktiles_total;
+    more = false;
+  } else if (!stream_wg) {
+    tc = tile_at(p, p.xcd_swizzle ? xcd_run(tile_id, p.sk_first_wg) : tile_id);
+    kt_begin = 0; kt_end = ktiles_total; split = false; more = false;
+  } else {
+    if (sk_cur >= sk_end) break;   // (an empty share: more work-groups than steps)
+    const int t = sk_cur / ktiles_total;
+    kt_begin = sk_cur - t * ktiles_total;
+    kt_end = kt_begin + (sk_end - sk_cur);
+    if (kt_end > ktiles_total) kt_end = ktiles_total;
+    tc = tile_at(p, p.sk_first_wg + t);
+    split = !(kt_begin == 0 && kt_end == ktiles_total);
+    tc.ks = kt_begin == 0 ? 0 : 1;
+    sk_cur += kt_end - kt_begin;
+    more = sk_cur < sk_end;
+  }
+  const int m0 = tc.tm * C::BM, n0 = tc.tn * C::BN;
   const int nkt = kt_end - kt_begin;   // may be <= 0 for a trailing empty slice: contributes zeros
 
   // ---- LDS read offsets of this lane (bytes inside a stage)
@@ -969,7 +1015,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   const int wn0 = n0 + wave_n * C::WTN + 4 * lane_g;          // + 32 t + 8 q
   const bool full = (m0 + C::BM <= p.M) && (n0 + C::BN <= p.N);
 
-  if (p.split_k > 1) {
+  if (split) {
     // publish the partial tile; the last slice to arrive sums all slices in slice order
     const size_t slice = (size_t)p.M * p.N;
     float* wsk = p.ws + (size_t)tc.ks * slice;
@@ -981,7 +1027,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
           epilogue_staged<C, TF_EPI_NONE_F32, true>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g, (char*)wsk, (size_t)p.N);
       } else if (full) store_partial<C, true, false>(acc, wsk, p, wm0, wn0);
       else store_partial<C, false, false>(acc, wsk, p, wm0, wn0);
-      return;
+      continue;
     }
     if constexpr (C::FUSED_OK) {
     // Two ways to hand the partial tiles to the last slice:
@@ -1012,7 +1058,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     if (tid == 0) ticket = atomicAdd(ctr, mine) + mine;
     __syncthreads();
     const unsigned long long tk = ticket;
-    if ((unsigned)(tk & 255u) != (unsigned)p.split_k) return;
+    if ((unsigned)(tk & 255u) != (unsigned)p.split_k) continue;
     if (tid == 0) *ctr = 0ull;        // ready for the next launch
     if (local) {
       if (full) sum_partials<C, true, false>(acc, p, wm0, wn0);
@@ -1053,6 +1099,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   else if (p.epi == TF_EPI_NONE_F32) finish(EpiTag<TF_EPI_NONE_F32>{});
   else if (p.epi == TF_EPI_BIAS) finish(EpiTag<TF_EPI_BIAS>{});
   else finish(EpiTag<TF_EPI_BIAS_GELU_TANH>{});
+  }   // segments
 }
 
 // Persistent kernel for the batched transposed-operand product with few K steps per tile
@@ -1240,13 +1287,17 @@ static void launch_lds(const GemmParams& p, dim3 grid, hipStream_t stream) {
   hipLaunchKernelGGL(tf_gemm_lds_kernel<C>, grid, dim3(C::THREADS), C::LDS_BYTES, stream, p);
 }
 
+// The same kernel with the loop over segments compiled in: work-groups may take several (tile, K range) pieces.
+template <class Base>
+struct StreamKCfg : Base { static constexpr bool SEGMENTS = true; };
+
 template <class C>
 static LdsKernelInfo make_info() {
   LdsKernelInfo k;
   k.bm = C::BM; k.bn = C::BN; k.bk = C::BK; k.waves_m = C::WM; k.waves_n = C::WN; k.waves_k = C::WK;
   k.stages = C::STAGES; k.direct_to_lds = C::DIRECT ? 1 : 0; k.a_bypass_lds = C::ABYPASS ? 1 : 0; k.trans_a = C::TRANSA ? 1 : 0;
   k.threads = C::THREADS; k.lds_bytes = C::LDS_BYTES; k.fused_ok = C::FUSED_OK ? 1 : 0;
-  k.persistent = 0;
+  k.persistent = 0; k.stream_k = C::SEGMENTS ? 1 : 0;
   k.func = (const void*)tf_gemm_lds_kernel<C>;
   k.launch = launch_lds<C>;
   return k;
@@ -1314,6 +1365,7 @@ static LdsKernelInfo g_table[] = {
     make_info<T128x128_w8s2>(), make_info<T128x64_d2>(), make_info<T64x128_d2>(), make_info<T64x64_d2>(),
     make_info<K256x256_w8a>(), make_info<K256x256_w8b>(),
     make_persist_info<T128x128_w8>(), make_persist_info<T128x128_d3>(),
+    make_info<StreamKCfg<K128x128_w8a>>(), make_info<StreamKCfg<K128x128_w8b>>(), make_info<StreamKCfg<K128x128_k2a>>(),
 };
 
 int lds_kernel_count() { return (int)(sizeof(g_table) / sizeof(g_table[0])); }

@@ -27,6 +27,8 @@ struct GemmParams {
   int xcd_swizzle;        // 1: remap work-group ids so that neighbouring tiles share an XCD
   int slice_major;        // split-K tile order: 1 = slice by slice (two-kernel reduction), 0 = the slices of a tile side by side
   int batch;              // batched problems: number of items (the persistent kernel deals them out itself)
+  int stream_k;           // 1: work-groups from sk_first_wg on share the K steps of the last sk_tiles tiles evenly
+  int sk_first_wg, sk_tiles, sk_wgs;   // (stream_k) first such work-group = number of tiles computed whole; tiles and work-groups of the shared part
   int k_rotate;           // 1: the K tiles of a work-group start a (blockIdx mod 8) / 8 of the way in and wrap round
   int batch_xcd;          // batched problems: 1 = all tiles of a batch item on one XCD (batch a multiple of 8)
   int ws_vec16;           // 1: the split-K workspace starts on a 16-byte boundary (its rows of N floats then do too)
@@ -39,6 +41,7 @@ struct LdsKernelInfo {
   int trans_a;            // 1: A is [K][lda] with m contiguous (staged and read like the B tile)
   int threads, lds_bytes;
   int fused_ok;           // 1: the kernel contains the in-kernel split-K reduction (fused_reduce 1 and 2)
+  int stream_k;           // 1: instance with the loop over (tile, K range) segments compiled in (stream-K variants only)
   int persistent;         // 1: tf_bgemm_persist_kernel (one work-group per CU walks through many tiles; grid.x = work-groups)
   const void* func;       // kernel symbol, for hipFuncGetAttributes / occupancy queries
   void (*launch)(const GemmParams&, dim3 grid, hipStream_t);

@@ -255,6 +255,15 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   // number of work-groups per slot, plus a ragged end
   double rounds = (double)v->grid / (double)slots;
   rounds = rounds <= 1.0 ? 1.0 : rounds + 0.25;
+  if (v->stream_k) {
+    // every CU gets the same number of K steps: the tile count over the CU count, no ragged last round. But the
+    // shares start at arbitrary K offsets, so the work-groups of an XCD no longer walk through K together and
+    // stop sharing operand panels in its L2 (measured: about 1.6x the time per K step), each piece refills
+    // the pipeline, and each shared tile costs its contributors the store acknowledgement, the ticket and a
+    // load round trip, one after the other
+    rounds = 1.6 * (double)((pr->M + v->bm - 1) / v->bm) * (double)((pr->N + v->bn - 1) / v->bn) / (double)hw->cus;
+    fused_tail_us = 12.0;
+  }
   const double per_cu = rounds * (double)co_resident;            // work-groups one CU works through
   const double us = per_cu * (ktiles * ktile + fill + tile_end) / mhz;
   const double ws_us = v->split_k > 1 ? 2.0 * v->split_k * 4.0 * pr->M * (double)pr->N / (hw->hbm_gbs_peak * 1e3) : 0.0;

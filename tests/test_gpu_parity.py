@@ -169,6 +169,37 @@ def test_epilogues_differ_where_they_should():
     assert np.any(d > 0)
 
 
+@pytest.mark.parametrize("shape", [(2304, 2304, 512), (2200, 2312, 576), (1408, 3200, 1024), (4224, 2176, 512)])
+def test_stream_k_variants(shape):
+    # between one and three tiles per CU, whole and ragged tiles, both epilogue types; a tile of the shared part
+    # has one or two contributors and the result must not depend on who arrives last (run twice, compare bits)
+    torch = gu.torch_mod()
+    M, N, K = shape
+    A, B, bias = wl.make_custom(M, N, K, seed=500 + M)
+    ran = check_all_variants(M, N, K, A, B, bias, only=lambda v: v.stream_k == 1)
+    assert len(ran) >= 4 and all(n.endswith("streamk") for n in ran)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    Y1 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    Y2 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    with tf.Problem(M, N, K) as prob:
+        sk = [v for v in prob.variants() if v.stream_k][0]
+        plain = [v for v in prob.variants() if v.kind == tf.TF_KIND_MFMA_LDS and not v.stream_k and v.split_k == 1
+                 and v.k_rotate == 0 and (v.bm, v.bn, v.waves_m, v.waves_n, v.waves_k, v.stages) ==
+                 (sk.bm, sk.bn, sk.waves_m, sk.waves_n, sk.waves_k, sk.stages)][0]
+        for _ in range(3):
+            prob.run(sk.id, dA, dB, dbias, Y1)
+            prob.run(sk.id, dA, dB, dbias, Y2)
+            torch.cuda.synchronize()
+            assert torch.equal(Y1.view(torch.int16), Y2.view(torch.int16))
+        # against the same kernel without stream-K: tiles computed whole are bit-identical, shared tiles differ
+        # by the rounding of one extra fp32 addition at most (then by at most one bf16 step)
+        prob.run(plain.id, dA, dB, dbias, Y2)
+        torch.cuda.synchronize()
+        d = (Y1.float() - Y2.float()).abs()
+        assert bool((d <= 2.0 ** -7 * Y2.float().abs() + 1e-6).all().item())
+        assert float((d == 0).float().mean().item()) > 0.5
+
+
 def test_degenerate_sizes():
     torch = gu.torch_mod()
     # K = 0: Y = GELU(bias) on every row
