@@ -140,7 +140,9 @@ typedef struct {
   int32_t stages;          /* LDS buffers in the ring */
   int32_t split_k;         /* K slices, summed in fp32 in slice order (1 = no split) */
   int32_t fused_reduce;    /* split_k > 1: 2 = as 1, with the partial tiles exchanged through the L2 of the one XCD
-                              that all slices of a tile run on (offered when the tile count is a multiple of 8);
+                              that all slices of a tile run on (offered when the tile count is a multiple of 8 and
+                              the rows of the partial sums are whole 128-byte lines, N a multiple of 32; launched
+                              only on a device whose work-group placement has been probed, see tf_variant_run);
                               1 = the last slice to arrive reduces inside the GEMM kernel (one launch,
                               arrival counters); 0 = a second kernel sums the slices and applies the epilogue */
   int32_t direct_to_lds;   /* 1: global_load_lds staging; 0: via registers (allows a ragged K tail) */
@@ -240,13 +242,32 @@ int32_t tf_variant_enumerate(const tf_problem* p, tf_variant_desc* out, int32_t 
 
 /* BuildRun: launches variant `variant_id` on `hip_stream` (a hipStream_t, may be NULL for the
  * default stream). A, B, bias, Y: device pointers (Y: bf16 or float per desc.epi).
- * workspace: device pointer of at least the variant's workspace_bytes, or NULL to let the
- * library use a buffer it allocates once per problem and keeps until tf_problem_destroy.
- * The first use of a workspace is preceded by one fill kernel that zeroes its counters; the
- * kernels leave the counters zero. Calls that share a workspace must not overlap. */
+ * workspace: device pointer of at least the variant's workspace_bytes, 256-byte aligned, or NULL to
+ * let the library use a buffer it allocates once per problem and keeps until tf_problem_destroy.
+ * Layout: [arrival counters and one status word | fp32 partial sums]. A caller's workspace has its
+ * counter area zeroed by a fill kernel ahead of every launch (its contents between calls are the
+ * caller's); the library's own buffer is zeroed once, the kernels leave the counters zero.
+ * Calls that share a workspace must not overlap.
+ * Variants with fused_reduce == 2 rely on work-groups whose ids are equal modulo 8 running on one
+ * XCD. The first such launch on a device runs a small probe kernel and waits for it (a
+ * synchronisation of the stream, once per device and process); if the probe does not confirm the
+ * placement, these variants fail with TF_E_UNSUPPORTED on that device and nothing is launched.
+ * Should a later launch still find the slices of a tile on different XCDs, the tile is written as
+ * NaN and the status word of the workspace is set: tf_variant_profile, tf_tune and
+ * tf_workspace_status then fail with TF_E_LAUNCH. */
 tf_status tf_variant_run(tf_problem* p, int32_t variant_id, const void* A, const void* B,
                          const void* bias, void* Y, void* workspace, size_t workspace_bytes,
                          void* hip_stream);
+
+/* Synchronises hip_stream and reads the status word of `workspace` (device pointer; NULL = the
+ * problem's own buffer): TF_OK, or TF_E_LAUNCH if a launch since the last zeroing of the counter
+ * area found the slices of a tile on different XCDs (fused_reduce == 2). */
+tf_status tf_workspace_status(tf_problem* p, const void* workspace, void* hip_stream);
+
+/* The host-side decision of the placement probe: xcc_of_wg[i] (host pointer) is the XCD that
+ * work-group i of a probe launch reported, n their number. Returns 1 if all work-groups with equal
+ * i modulo 8 ran on one XCD (n >= 16), else 0. Needs no GPU. */
+int32_t tf_xcc_placement_ok(const uint32_t* xcc_of_wg, int32_t n);
 
 /* Profile: `warmup` untimed iterations, then `iters` timed ones; each iteration brackets
  * `launches_per_iter` back-to-back launches (0 = pick so that an iteration lasts >= ~1 ms)
@@ -307,11 +328,29 @@ tf_status tf_tune_replay(const tf_problem_desc* prob, const tf_hw* hw, const tf_
  * equivalence of every candidate before its time counts). Returns non-zero if Y is accepted. */
 typedef int32_t (*tf_parity_fn)(void* user, int32_t variant_id);
 
+/* The comparison of tf_tune's built-in gate, on host arrays (all host pointers; needs no GPU).
+ * Y: the candidate's output, rows x N with leading dimension ldy, bf16 bit patterns or float per
+ * epi. zref: fp32 pre-activation of the baseline kernel, dense rows x N (for the operations
+ * without bias: its output). norm_a[m], norm_b[m * norm_b_row_stride + n]: Euclidean norms of
+ * the two vectors whose dot product element (m, n) is; their product bounds sum |a b|.
+ * An element passes if
+ *   |y - act(zref)| <= 2^-8 |act(zref)| + 1.13 (3 g norm_a norm_b + 2^-22 |zref|) + 2e-6 (1 + |zref|)
+ * for a bf16 epilogue (act = the epilogue's activation evaluated with the math library), and
+ *   |y - zref| <= 3 g norm_a norm_b + 2^-22 |zref| + 1e-30
+ * for fp32 output, with g = (K + 1) 2^-24 / (1 - (K + 1) 2^-24): one bf16 rounding, the
+ * summation error of two fp32 evaluations in any order, the activation's slope. A NaN never
+ * passes. Returns the number of elements that fail, or a negative tf_status. */
+int64_t tf_gate_count_bad(const void* Y, int64_t ldy, const float* zref, const float* norm_a,
+                          const float* norm_b, int64_t norm_b_row_stride, int32_t rows, int32_t N,
+                          int32_t K, int32_t epi);
+
 /* Algorithm 1. Profiles the baseline (variant 0), then runs at most theta->max_rounds rounds of
  * Proposal -> BuildRun -> parity gate -> Profile -> Arbiter -> RefineHint. round_log (host
  * pointer, capacity log_cap >= 1 + max_rounds) receives the baseline report followed by one
- * report per round; *n_log their number. *best_variant / *best get K* and R*. parity may be
- * NULL (every candidate is then taken as correct). */
+ * report per round; *n_log their number. *best_variant / *best get K* and R*. Y is filled with
+ * NaN before every candidate's BuildRun, so an element a candidate does not write fails the gate.
+ * parity may be NULL: the library then compares every candidate with the baseline kernel's fp32
+ * pre-activation by the rule of tf_gate_count_bad (on the device). */
 tf_status tf_tune(tf_problem* p, const void* A, const void* B, const void* bias, void* Y,
                   void* workspace, size_t workspace_bytes, void* hip_stream,
                   const tf_theta* theta, tf_parity_fn parity, void* parity_user,

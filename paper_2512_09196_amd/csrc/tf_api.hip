@@ -30,6 +30,8 @@ tf_status fail(tf_status st, const char* fmt, ...) {
     if (e_ != hipSuccess) return fail(TF_E_LAUNCH, "%s: %s", #call, hipGetErrorString(e_)); \
   } while (0)
 
+constexpr size_t kStatusBytes = 256;   // tail of the counter area of a workspace: the status word
+
 struct VariantImpl {
   int lds_index;   // index into tf::lds_kernel_table() (tf::stream_kernel_table() for the streaming kind), -1 for the unstaged kernels
   int ktiles_per_split;
@@ -273,7 +275,9 @@ void build_family(tf_problem* p) {
       // slices summed by the last one to arrive (2: partial tiles exchanged through the L2 of the XCD
       // all slices of a tile run on, possible when the tile order gives every XCD whole tiles;
       // 1: through memory, wherever they run) or by a second kernel (0)
-      const int fused_mode = (tm * tn) % 8 == 0 ? 2 : 1;
+      // (2 also needs every row of a partial tile to be whole 128-byte lines, or a line would straddle two
+      // tiles and a CU could sum a neighbour's columns from a copy it fetched before they were stored)
+      const int fused_mode = ((tm * tn) % 8 == 0 && d.N % 32 == 0) ? 2 : 1;
       for (int fused = fused_mode; fused >= 0; fused -= fused_mode) {
         if (s == 1 && fused == 0) continue;
         if (s > 1 && fused != 0 && !k.fused_ok) continue;
@@ -317,7 +321,7 @@ void build_family(tf_problem* p) {
       for (int s : splits) {
         const long per = cdivl(kblocks, s);
         if (s > 1 && (per < k.waves || per * (s - 1) >= kblocks || tn * s > 8L * cus)) continue;
-        const int fused_mode = tn % 8 == 0 ? 2 : 1;      // slices of a column block are tn work-groups apart
+        const int fused_mode = (tn % 8 == 0 && d.N % 32 == 0) ? 2 : 1;      // slices of a column block are tn work-groups apart; whole-line rows
         for (int fused = fused_mode; fused >= 0; fused -= fused_mode) {
           if (s == 1 && fused == 0) continue;
           tf_variant_desc v;
@@ -339,13 +343,16 @@ void build_family(tf_problem* p) {
     }
   }
   // One counter area for the whole family, so that the partial sums of one variant never
-  // land on the counters of another: [counters | partial sums].
+  // land on the counters of another: [counters, status word | partial sums]. The status word
+  // takes the last 256 bytes of the area.
   size_t maxc = 0;
   for (const VariantImpl& o : p->impl) maxc = std::max(maxc, o.counter_bytes);
+  if (maxc > 0) maxc += kStatusBytes;
   for (size_t i = 0; i < p->impl.size(); ++i) {
-    if (p->family[i].split_k > 1) {
+    if (p->impl[i].counter_bytes > 0) {
+      const size_t slices = p->family[i].stream_k ? 2 : (size_t)p->family[i].split_k;
       p->impl[i].counter_bytes = maxc;
-      p->family[i].workspace_bytes = (int64_t)(maxc + (size_t)p->family[i].split_k * d.M * d.N * 4);
+      p->family[i].workspace_bytes = (int64_t)(maxc + slices * d.M * d.N * 4);
     }
   }
 }
@@ -388,9 +395,26 @@ tf_status check_ptrs(const tf_problem* p, const tf_variant_desc& v, const void* 
   return TF_OK;
 }
 
+// The placement the L2-local reduction relies on, per device: 0 = not probed yet, 1 = confirmed, -1 = refuted.
+int g_placement[64];
+
+// Runs the probe kernel into `scratch` (device memory of at least 4 * wgs bytes that nothing else uses right
+// now) and waits for it.
+tf_status probe_placement(int device, unsigned* scratch, int wgs, hipStream_t stream) {
+  std::vector<uint32_t> host((size_t)wgs);
+  tf::launch_xcc_probe(scratch, wgs, stream);
+  TF_HIP(hipMemcpyAsync(host.data(), scratch, sizeof(uint32_t) * (size_t)wgs, hipMemcpyDeviceToHost, stream));
+  TF_HIP(hipStreamSynchronize(stream));
+  g_placement[device] = tf_xcc_placement_ok(host.data(), wgs) ? 1 : -1;
+  return TF_OK;
+}
+
+// epi_override >= 0: run with that epilogue instead of the problem's (Y then has rows of ldy_override elements);
+// used by the correctness gate of the variant loop to get the baseline kernel's fp32 pre-activation.
 tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const void* bias, void* Y, void* ws,
-                    size_t ws_bytes, hipStream_t stream) {
-  const tf_problem_desc& d = p->desc;
+                    size_t ws_bytes, hipStream_t stream, int epi_override = -1, long ldy_override = 0) {
+  tf_problem_desc d = p->desc;
+  if (epi_override >= 0) { d.epi = epi_override; d.ldy = ldy_override; }
   const tf_variant_desc& v = p->family[id];
   const VariantImpl& im = p->impl[id];
   tf_status st = check_ptrs(p, v, A, B, bias, Y);
@@ -430,7 +454,7 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
       // separate pass: A^T of every item into the workspace, which then is the A operand
       if (!ws) {
         if (p->own_ws_bytes < (size_t)v.workspace_bytes) {
-          if (p->own_ws) { (void)hipFree(p->own_ws); p->own_ws = nullptr; p->own_ws_bytes = 0; }
+          if (p->own_ws) { (void)hipFree(p->own_ws); p->own_ws = nullptr; p->own_ws_bytes = 0; p->zeroed_ws = nullptr; p->zeroed_bytes = 0; }
           size_t need = 0;
           for (const tf_variant_desc& f : p->family) need = std::max(need, (size_t)f.workspace_bytes);
           if (hipMalloc(&p->own_ws, need) != hipSuccess) {
@@ -476,7 +500,7 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
     if (v.split_k > 1 || v.stream_k) {
       if (!ws) {
         if (p->own_ws_bytes < (size_t)v.workspace_bytes) {
-          if (p->own_ws) { (void)hipFree(p->own_ws); p->own_ws = nullptr; p->own_ws_bytes = 0; }
+          if (p->own_ws) { (void)hipFree(p->own_ws); p->own_ws = nullptr; p->own_ws_bytes = 0; p->zeroed_ws = nullptr; p->zeroed_bytes = 0; }
           size_t need = 0;
           for (const tf_variant_desc& f : p->family) need = std::max(need, (size_t)f.workspace_bytes);
           if (hipMalloc(&p->own_ws, need) != hipSuccess) {
@@ -491,17 +515,31 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
         return fail(TF_E_UNSUPPORTED, "workspace of %zu bytes, variant %s needs %lld", ws_bytes, v.name,
                     (long long)v.workspace_bytes);
       if ((uintptr_t)ws & 255u) return fail(TF_E_UNSUPPORTED, "workspace must be 256-byte aligned");
-      if (p->zeroed_ws != ws || p->zeroed_bytes < im.counter_bytes) {
-        // the counters of a workspace seen for the first time may hold anything
-        size_t maxc = 0;
-        for (const VariantImpl& o : p->impl) maxc = std::max(maxc, o.counter_bytes);
-        maxc = std::min(maxc, ws_bytes);
-        tf::launch_fill_u32((unsigned*)ws, maxc / 4, 0u, stream);
-        p->zeroed_ws = ws; p->zeroed_bytes = maxc;
-      }
       g.counters = (unsigned*)ws;
+      g.status = (unsigned*)((char*)ws + im.counter_bytes - kStatusBytes);
       g.ws = (float*)((char*)ws + im.counter_bytes);
       g.ws_vec16 = ((uintptr_t)g.ws % 16 == 0) && (d.N % 4 == 0);
+      if (v.fused_reduce == 2) {
+        // the L2-local reduction: only on a device whose work-group placement has been confirmed
+        const int dev = d.device >= 0 && d.device < 64 ? d.device : 0;
+        if (g_placement[dev] == 0) {
+          // (the partial-sum area is free until the kernel below runs; it holds at least one tile of floats)
+          const size_t room = (ws_bytes - im.counter_bytes) / 4;
+          const int wgs = (int)std::min<size_t>(room, 2048);
+          if (wgs < 16) return fail(TF_E_UNSUPPORTED, "variant %s: workspace too small for the placement probe", v.name);
+          st = probe_placement(dev, (unsigned*)g.ws, wgs, stream);
+          if (st != TF_OK) return st;
+        }
+        if (g_placement[dev] < 0)
+          return fail(TF_E_UNSUPPORTED, "variant %s: on device %d work-groups with equal ids modulo 8 do not share an XCD", v.name, dev);
+      }
+      // The library's own buffer is zeroed when it is first used (the kernels leave the counters zero); what a
+      // caller's buffer holds between two calls is the caller's business, so its counter area is zeroed every time.
+      const bool own = ws == p->own_ws;
+      if (!own || p->zeroed_ws != ws || p->zeroed_bytes < im.counter_bytes) {
+        tf::launch_fill_u32((unsigned*)ws, im.counter_bytes / 4, 0u, stream);
+        if (own) { p->zeroed_ws = ws; p->zeroed_bytes = im.counter_bytes; }
+      }
     }
     const bool streaming = v.kind == TF_KIND_MFMA_STREAM;
     const int slot = streaming ? tf::lds_kernel_count() + im.lds_index : im.lds_index;
@@ -551,23 +589,53 @@ void fill_static(tf_problem* p, int id, tf_report* r) {
 }
 
 // ---------------------------------------------------------------- built-in parity gate
-// A candidate is accepted only if its output matches the baseline kernel's output on the
+// A candidate is accepted only if its output matches what the baseline kernel computes on the
 // same inputs (the paper checks functional equivalence of every variant before timing it).
+// The reference is the baseline kernel's fp32 pre-activation zref; the bound is what two correct
+// fp32 evaluations of the same dot product can differ by, so it can see the matrix product even
+// where a bias dominates the output: g = gamma_{K+1}; the baseline's sequential sum is within
+// g sum|ab| of the true value, a tile kernel's within 2 g sum|ab| (any order, the matrix
+// instruction's internal order included), and sum|ab| <= |a| |b| (Cauchy-Schwarz), the two norms
+// being cheap to compute. The activation is evaluated with the math library, not with the
+// kernels' own approximation.
+struct GateRule {
+  float g3;        // 3 gamma_{K+1}
+  int epi;
+};
+__host__ __device__ inline float gate_activation(float z, int epi) {
+  if (epi == TF_EPI_BIAS_GELU_ERF) return 0.5f * z * erfcf(-z * 0.70710678118654752f);
+  if (epi == TF_EPI_BIAS_GELU_TANH) return 0.5f * z * (1.0f + tanhf(0.79788456080286536f * (z + 0.044715f * z * z * z)));
+  return z;
+}
+// y: the candidate's value; zref: the baseline's pre-activation; nab: |a| |b| of the element
+__host__ __device__ inline bool gate_pass(float y, float zref, float nab, const GateRule& r) {
+  const float sum_err = r.g3 * nab + 2.384185791015625e-07f * fabsf(zref);        // + 2^-22 |z|
+  if (r.epi == TF_EPI_NONE_F32) return fabsf(y - zref) <= sum_err + 1e-30f;       // (false for NaN)
+  const float ref = gate_activation(zref, r.epi);
+  return fabsf(y - ref) <= 0.00390625f * fabsf(ref) + 1.13f * sum_err + 2e-6f * (1.0f + fabsf(zref));
+}
+inline GateRule gate_rule(int K, int epi) {
+  const double u = ldexp(1.0, -24), n = (double)K + 1.0;
+  GateRule r;
+  r.g3 = (float)(3.0 * n * u / (1.0 - n * u));
+  r.epi = epi;
+  return r;
+}
+
 template <typename T>
-__global__ void compare_kernel(const T* y, const T* ref, size_t rows, int n, long ldy, unsigned* bad) {
+__global__ void gate_kernel(const T* y, long ldy, const float* zref, const float* na, const float* nb, long nb_row_stride,
+                            size_t rows, int n, GateRule rule, unsigned* bad) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= rows * (size_t)n) return;
   const size_t m = i / n, c = i % n;
-  float a, b;
-  if (sizeof(T) == 2) {
-    a = tf::bf16_bits_to_f32((uint16_t)y[m * ldy + c]);
-    b = tf::bf16_bits_to_f32((uint16_t)ref[m * ldy + c]);
-  } else {
-    a = (float)y[m * ldy + c];
-    b = (float)ref[m * ldy + c];
-  }
-  const bool ok = fabsf(a - b) <= 1e-2f * (1.0f + fabsf(b));   // also false for NaN
-  if (!ok) atomicAdd(bad, 1u);
+  const float v = sizeof(T) == 2 ? tf::bf16_bits_to_f32((uint16_t)y[m * ldy + c]) : (float)y[m * ldy + c];
+  if (!gate_pass(v, zref[i], na[m] * nb[m * nb_row_stride + c], rule)) atomicAdd(bad, 1u);
+}
+// element-wise sine: every launch shape runs the same arithmetic, so the outputs agree to the last bit or nearly
+__global__ void gate_sin_kernel(const float* y, const float* ref, size_t n, unsigned* bad) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  if (!(fabsf(y[i] - ref[i]) <= 2.384185791015625e-07f)) atomicAdd(bad, 1u);
 }
 
 // Copies of the operands that the Profile stage cycles through, one set per launch, so that a
@@ -588,7 +656,9 @@ struct TuneCtx {
   hipStream_t stream;
   tf_parity_fn parity;
   void* parity_user;
-  void* yref;        // baseline output
+  void* yref;        // gate: fp32 pre-activation of the baseline kernel, dense [items][M][N] (the sine: its output), then the norms
+  float* norm_a;     // gate: norms of the left vectors  (inside the yref allocation)
+  float* norm_b;     // gate: norms of the right vectors
   unsigned* bad;     // device counter
   size_t ybytes;
   const Rotation* rot;   // cold-cache operand copies for the Profile stage, or null
@@ -598,35 +668,107 @@ tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, cons
                        size_t ws_bytes, hipStream_t stream, int warmup, int iters, int lpi, tf_report* out,
                        const Rotation* rot = nullptr);
 
+// Rows of the output (of one batch item) filled with NaN, padding between rows untouched.
+void poison_output(const tf_problem_desc& d, void* Y, hipStream_t stream) {
+  const size_t esz = d.epi == TF_EPI_NONE_F32 ? 4 : 2;
+  const unsigned pattern = esz == 4 ? 0x7fc00000u : 0x7fc07fc0u;
+  if (d.op == TF_OP_ELEMENTWISE_SIN) { tf::launch_fill_rows(Y, 1, (size_t)d.N * 4, (size_t)d.N * 4, pattern, stream); return; }
+  const int items = d.op == TF_OP_BATCHED_GEMM_TN ? d.batch : 1;
+  for (int b = 0; b < items; ++b)
+    tf::launch_fill_rows((char*)Y + (size_t)b * d.stride_y * esz, (size_t)d.M, (size_t)d.N * esz, (size_t)d.ldy * esz, pattern, stream);
+}
+
+// The baseline's references for the gate: pre-activation and norms (see GateRule).
+tf_status gate_prepare(TuneCtx* c) {
+  tf_problem* p = c->p;
+  const tf_problem_desc& d = p->desc;
+  if (d.op == TF_OP_ELEMENTWISE_SIN) {
+    TF_HIP(hipMemcpyAsync(c->yref, c->Y, (size_t)d.N * 4, hipMemcpyDeviceToDevice, c->stream));
+    return TF_OK;
+  }
+  if (d.op == TF_OP_GEMM_EPILOGUE) {
+    tf_status st = do_launch(p, 0, c->A, c->B, c->bias, c->yref, nullptr, 0, c->stream, TF_EPI_NONE_F32, d.N);
+    if (st != TF_OK) return st;
+    tf::launch_norms((const uint16_t*)c->A, 1, 0, d.M, d.lda, d.K, 1, c->norm_a, c->stream);
+    tf::launch_norms((const uint16_t*)c->B, 1, 0, d.N, 1, d.K, d.ldb, c->norm_b, c->stream);
+  } else if (d.op == TF_OP_BATCHED_VECMAT) {
+    TF_HIP(hipMemcpy2DAsync(c->yref, (size_t)d.N * 4, c->Y, (size_t)d.ldy * 4, (size_t)d.N * 4, (size_t)d.M, hipMemcpyDeviceToDevice, c->stream));
+    tf::launch_norms((const uint16_t*)c->A, 1, 0, d.M, d.lda, d.K, 1, c->norm_a, c->stream);
+    tf::launch_norms((const uint16_t*)c->B, 1, 0, (long)d.M * d.N, d.ldb, d.K, 1, c->norm_b, c->stream);
+  } else {   // TF_OP_BATCHED_GEMM_TN
+    for (int b = 0; b < d.batch; ++b)
+      TF_HIP(hipMemcpy2DAsync((float*)c->yref + (size_t)b * d.M * d.N, (size_t)d.N * 4, (const float*)c->Y + (size_t)b * d.stride_y,
+                              (size_t)d.ldy * 4, (size_t)d.N * 4, (size_t)d.M, hipMemcpyDeviceToDevice, c->stream));
+    tf::launch_norms((const uint16_t*)c->A, d.batch, d.stride_a, d.M, 1, d.K, d.lda, c->norm_a, c->stream);
+    tf::launch_norms((const uint16_t*)c->B, d.batch, d.stride_b, d.N, 1, d.K, d.ldb, c->norm_b, c->stream);
+  }
+  TF_HIP(hipGetLastError());
+  return TF_OK;
+}
+
+// Number of elements of Y (the candidate's output) that the gate rejects, via the device counter.
+tf_status gate_count(TuneCtx* c, unsigned* bad_out) {
+  tf_problem* p = c->p;
+  const tf_problem_desc& d = p->desc;
+  tf::launch_fill_u32(c->bad, 1, 0u, c->stream);
+  const size_t total = (size_t)d.M * d.N;
+  const unsigned blocks = (unsigned)((total + 255) / 256);
+  const GateRule rule = gate_rule(d.K, d.epi);
+  if (d.op == TF_OP_ELEMENTWISE_SIN) {
+    hipLaunchKernelGGL(gate_sin_kernel, dim3((unsigned)(((size_t)d.N + 255) / 256)), dim3(256), 0, c->stream, (const float*)c->Y,
+                       (const float*)c->yref, (size_t)d.N, c->bad);
+  } else if (d.op == TF_OP_BATCHED_GEMM_TN) {
+    for (int b = 0; b < d.batch; ++b)     // item by item: the items may lie apart
+      hipLaunchKernelGGL(gate_kernel<float>, dim3(blocks), dim3(256), 0, c->stream, (const float*)c->Y + (size_t)b * d.stride_y,
+                         (long)d.ldy, (const float*)c->yref + (size_t)b * total, c->norm_a + (size_t)b * d.M,
+                         c->norm_b + (size_t)b * d.N, 0L, (size_t)d.M, d.N, rule, c->bad);
+  } else {
+    const long nbs = d.op == TF_OP_BATCHED_VECMAT ? (long)d.N : 0L;
+    if (d.epi == TF_EPI_NONE_F32)
+      hipLaunchKernelGGL(gate_kernel<float>, dim3(blocks), dim3(256), 0, c->stream, (const float*)c->Y, (long)d.ldy,
+                         (const float*)c->yref, c->norm_a, c->norm_b, nbs, (size_t)d.M, d.N, rule, c->bad);
+    else
+      hipLaunchKernelGGL(gate_kernel<uint16_t>, dim3(blocks), dim3(256), 0, c->stream, (const uint16_t*)c->Y, (long)d.ldy,
+                         (const float*)c->yref, c->norm_a, c->norm_b, nbs, (size_t)d.M, d.N, rule, c->bad);
+  }
+  TF_HIP(hipMemcpyAsync(bad_out, c->bad, 4, hipMemcpyDeviceToHost, c->stream));
+  TF_HIP(hipStreamSynchronize(c->stream));
+  return TF_OK;
+}
+
+// Status word of a workspace after a synchronisation: non-zero if an L2-local reduction went wrong.
+tf_status read_status_word(tf_problem* p, int id, const void* ws, hipStream_t stream, unsigned* word) {
+  *word = 0;
+  const VariantImpl& im = p->impl[id];
+  if (im.counter_bytes < kStatusBytes) return TF_OK;
+  const void* base = ws ? ws : p->own_ws;
+  if (!base) return TF_OK;
+  TF_HIP(hipMemcpyAsync(word, (const char*)base + im.counter_bytes - kStatusBytes, 4, hipMemcpyDeviceToHost, stream));
+  TF_HIP(hipStreamSynchronize(stream));
+  return TF_OK;
+}
+
 tf_status tune_profile(void* user, int32_t id, tf_report* out) {
   TuneCtx* c = (TuneCtx*)user;
   tf_problem* p = c->p;
   memset(out, 0, sizeof(*out));
   out->variant_id = id;
+  const bool have_output = p->desc.M > 0 && p->desc.N > 0 && (p->desc.op != TF_OP_BATCHED_GEMM_TN || p->desc.batch > 0);
+  // an element the candidate does not write must not pass on what the previous candidate left there
+  if (have_output) poison_output(p->desc, c->Y, c->stream);
   tf_status st = do_launch(p, id, c->A, c->B, c->bias, c->Y, c->ws, c->ws_bytes, c->stream);
   if (st != TF_OK) { out->status = st; return TF_OK; }   // BuildRun failed: recorded, the loop goes on
   TF_HIP(hipStreamSynchronize(c->stream));
   int ok = 1;
   if (c->parity) ok = c->parity(c->parity_user, id) != 0;
-  else if (id == 0) { TF_HIP(hipMemcpyAsync(c->yref, c->Y, c->ybytes, hipMemcpyDeviceToDevice, c->stream)); }
-  else if (p->desc.M > 0 && p->desc.N > 0) {
-    tf::launch_fill_u32(c->bad, 1, 0u, c->stream);
-    const size_t total = (size_t)p->desc.M * p->desc.N;
-    const unsigned blocks = (unsigned)((total + 255) / 256);
-    if (p->desc.op == TF_OP_BATCHED_GEMM_TN) {
-      for (int b = 0; b < p->desc.batch; ++b)     // item by item: the items may lie apart
-        hipLaunchKernelGGL(compare_kernel<float>, dim3(blocks), dim3(256), 0, c->stream,
-                           (const float*)c->Y + (size_t)b * p->desc.stride_y, (const float*)c->yref + (size_t)b * p->desc.stride_y,
-                           (size_t)p->desc.M, p->desc.N, (long)p->desc.ldy, c->bad);
-    } else if (p->desc.epi == TF_EPI_NONE_F32)
-      hipLaunchKernelGGL(compare_kernel<float>, dim3(blocks), dim3(256), 0, c->stream, (const float*)c->Y,
-                         (const float*)c->yref, (size_t)p->desc.M, p->desc.N, (long)p->desc.ldy, c->bad);
-    else
-      hipLaunchKernelGGL(compare_kernel<uint16_t>, dim3(blocks), dim3(256), 0, c->stream, (const uint16_t*)c->Y,
-                         (const uint16_t*)c->yref, (size_t)p->desc.M, p->desc.N, (long)p->desc.ldy, c->bad);
+  else if (have_output) {
+    if (id == 0) {
+      st = gate_prepare(c);
+      if (st != TF_OK) return st;
+    }
     unsigned bad = 0;
-    TF_HIP(hipMemcpyAsync(&bad, c->bad, 4, hipMemcpyDeviceToHost, c->stream));
-    TF_HIP(hipStreamSynchronize(c->stream));
+    st = gate_count(c, &bad);      // (the baseline itself goes through the same comparison)
+    if (st != TF_OK) return st;
     ok = bad == 0;
   }
   st = profile_impl(p, id, c->A, c->B, c->bias, c->Y, c->ws, c->ws_bytes, c->stream, 3, 5, 0, out, c->rot);
@@ -693,6 +835,12 @@ tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, cons
   }
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
+  if (st == TF_OK && p->family[id].fused_reduce == 2) {
+    unsigned word = 0;
+    st = read_status_word(p, id, ws, stream, &word);
+    if (st == TF_OK && word != 0)
+      st = fail(TF_E_LAUNCH, "variant %s: the slices of a tile ran on different XCDs; its output is invalid", p->family[id].name);
+  }
   out->status = st;
   if (st != TF_OK) return st;
   out->warmup = warmup; out->iters = iters; out->launches_per_iter = lpi;
@@ -916,6 +1064,48 @@ extern "C" tf_status tf_variant_profile(tf_problem* p, int32_t id, const void* A
                       launches_per_iter, out);
 }
 
+extern "C" tf_status tf_workspace_status(tf_problem* p, const void* workspace, void* hip_stream) {
+  if (!p) return fail(TF_E_INVALID, "null problem");
+  int id = -1;
+  for (size_t i = 0; i < p->impl.size(); ++i) if (p->impl[i].counter_bytes >= kStatusBytes) { id = (int)i; break; }
+  if (id < 0) return TF_OK;                         // no variant of this problem uses a workspace with counters
+  if (!workspace && !p->own_ws) return TF_OK;       // nothing has been launched into the library's own buffer yet
+  tf_status st = prepare(p, id);
+  if (st != TF_OK) return st;
+  unsigned word = 0;
+  st = read_status_word(p, id, workspace, (hipStream_t)hip_stream, &word);
+  if (st != TF_OK) return st;
+  if (word != 0) return fail(TF_E_LAUNCH, "an L2-local split-K reduction found the slices of a tile on different XCDs; that output is invalid");
+  return TF_OK;
+}
+
+extern "C" int32_t tf_xcc_placement_ok(const uint32_t* xcc_of_wg, int32_t n) {
+  if (!xcc_of_wg || n < 16) return 0;
+  for (int32_t i = 8; i < n; ++i)
+    if (xcc_of_wg[i] != xcc_of_wg[i & 7]) return 0;
+  return 1;
+}
+
+extern "C" int64_t tf_gate_count_bad(const void* Y, int64_t ldy, const float* zref, const float* norm_a, const float* norm_b,
+                                     int64_t norm_b_row_stride, int32_t rows, int32_t N, int32_t K, int32_t epi) {
+  if (rows < 0 || N < 0 || K < 0 || ldy < N || epi < TF_EPI_BIAS_GELU_ERF || epi > TF_EPI_BIAS_GELU_TANH) return fail(TF_E_INVALID, "bad argument");
+  if (rows == 0 || N == 0) return 0;
+  if (!Y || !zref || !norm_a || !norm_b) return fail(TF_E_INVALID, "null argument");
+  const GateRule rule = gate_rule(K, epi);
+  int64_t bad = 0;
+  for (int64_t m = 0; m < rows; ++m)
+    for (int64_t n = 0; n < N; ++n) {
+      float y;
+      if (epi == TF_EPI_NONE_F32) y = ((const float*)Y)[m * ldy + n];
+      else {
+        const uint32_t w = (uint32_t)((const uint16_t*)Y)[m * ldy + n] << 16;
+        memcpy(&y, &w, 4);
+      }
+      if (!gate_pass(y, zref[m * N + n], norm_a[m] * norm_b[m * norm_b_row_stride + n], rule)) ++bad;
+    }
+  return bad;
+}
+
 extern "C" tf_status tf_report_set_counters(tf_report* r, const tf_hw* hw, const char* csv_path,
                                             const char* kernel_substr) {
   if (!r || !hw || !csv_path || !kernel_substr) return fail(TF_E_INVALID, "null argument");
@@ -1010,7 +1200,16 @@ extern "C" tf_status tf_tune(tf_problem* p, const void* A, const void* B, const 
   if (p->desc.op == TF_OP_BATCHED_GEMM_TN)
     c.ybytes = p->desc.batch > 0 && p->desc.M > 0 ? c.ybytes + (size_t)(p->desc.batch - 1) * p->desc.stride_y * esz : 0;
   if (!parity) {
-    if (hipMalloc(&c.yref, std::max<size_t>(c.ybytes, 16)) != hipSuccess) return fail(TF_E_NOMEM, "cannot allocate the reference output");
+    // one allocation: [fp32 reference, dense | norms of the left vectors | norms of the right vectors]
+    const tf_problem_desc& d = p->desc;
+    const size_t items = d.op == TF_OP_BATCHED_GEMM_TN ? (size_t)std::max(d.batch, 0) : 1;
+    const size_t ref_bytes = ((d.op == TF_OP_ELEMENTWISE_SIN ? (size_t)d.N : items * (size_t)d.M * d.N) * 4 + 255) & ~(size_t)255;
+    const size_t na = d.op == TF_OP_ELEMENTWISE_SIN ? 0 : items * (size_t)d.M;
+    const size_t nb = d.op == TF_OP_ELEMENTWISE_SIN ? 0 : d.op == TF_OP_BATCHED_VECMAT ? (size_t)d.M * d.N : items * (size_t)d.N;
+    const size_t na_bytes = (na * 4 + 255) & ~(size_t)255;
+    if (hipMalloc(&c.yref, ref_bytes + na_bytes + nb * 4 + 256) != hipSuccess) return fail(TF_E_NOMEM, "cannot allocate the reference output");
+    c.norm_a = (float*)((char*)c.yref + ref_bytes);
+    c.norm_b = (float*)((char*)c.yref + ref_bytes + na_bytes);
     if (hipMalloc((void**)&c.bad, 256) != hipSuccess) { (void)hipFree(c.yref); return fail(TF_E_NOMEM, "cannot allocate the mismatch counter"); }
   }
   Rotation rot;

@@ -1037,7 +1037,8 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     //    the partial tiles: a store acknowledged by the L2 (vmcnt) is what any CU of the same XCD
     //    reads afterwards, and no CU has read these addresses earlier in the launch. Every slice
     //    reports the XCD it really ran on with its ticket; if they differ, the tile is poisoned
-    //    with NaN rather than summed from memory that may be stale.
+    //    with NaN rather than summed from memory that may be stale, and the status word of the
+    //    workspace is set (the host probes the placement once per device before it launches this mode).
     const bool local = p.fused_reduce == 2;
     if (local) {
       if (full) store_partial<C, true, false>(acc, wsk, p, wm0, wn0);
@@ -1064,6 +1065,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       if (full) sum_partials<C, true, false>(acc, p, wm0, wn0);
       else sum_partials<C, false, false>(acc, p, wm0, wn0);
       if ((unsigned)((tk >> (8 + 7 * xcc)) & 127u) != (unsigned)p.split_k) {
+        if (tid == 0) atomicOr(p.status, 1u);   // reported by the next synchronous call of the library
         const float nan = __builtin_nanf("");
 #pragma unroll
         for (int i = 0; i < C::TM_OUT; ++i)

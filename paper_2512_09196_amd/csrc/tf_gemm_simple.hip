@@ -208,4 +208,60 @@ void launch_fill_u32(unsigned* p, size_t n, unsigned v, hipStream_t s) {
   hipLaunchKernelGGL(tf_fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, v);
 }
 
+// Fills the first row_bytes of every row (ld_bytes apart) with a 16-bit pattern, two bytes per thread and
+// step: the rows of an output matrix without touching the padding between them, whatever its alignment.
+__global__ void __launch_bounds__(256) tf_fill_rows_kernel(uint16_t* y, size_t rows, size_t row_halves, size_t ld_halves,
+                                                           unsigned lo, unsigned hi) {
+  const size_t total = rows * row_halves;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const size_t r = i / row_halves, c = i % row_halves;
+    y[r * ld_halves + c] = (uint16_t)((c & 1) ? hi : lo);
+  }
+}
+void launch_fill_rows(void* y, size_t rows, size_t row_bytes, size_t ld_bytes, unsigned pattern, hipStream_t s) {
+  const size_t total = rows * (row_bytes / 2);
+  if (total == 0) return;
+  size_t blocks = (total + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  // 2-byte elements: both halves are the low half of the pattern; 4-byte elements: low then high half
+  const bool four = (pattern >> 16) != (pattern & 0xffffu);
+  hipLaunchKernelGGL(tf_fill_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint16_t*)y, rows, row_bytes / 2, ld_bytes / 2,
+                     pattern & 0xffffu, four ? (pattern >> 16) : (pattern & 0xffffu));
+}
+
+// Placement probe: work-group i records the XCD it runs on.
+__global__ void __launch_bounds__(64) tf_xcc_probe_kernel(unsigned* out) {
+  if (threadIdx.x == 0) out[blockIdx.x] = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u;   // HW_REG_XCC_ID, bits 0..3
+}
+void launch_xcc_probe(unsigned* out, int wgs, hipStream_t s) {
+  if (wgs <= 0) return;
+  hipLaunchKernelGGL(tf_xcc_probe_kernel, dim3((unsigned)wgs), dim3(64), 0, s, out);
+}
+
+// Euclidean norms of bf16 vectors (one wave per vector, lanes stride through it, lane-exchange sum).
+__global__ void __launch_bounds__(256) tf_norms_kernel(const uint16_t* X, long n_outer, long outer_stride, long n_inner,
+                                                       long inner_stride, long len, long elem_stride, float* out) {
+  const long v = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (v >= n_outer * n_inner) return;
+  const int lane = threadIdx.x & 63;
+  const long o = v / n_inner, i = v % n_inner;
+  const uint16_t* x = X + o * outer_stride + i * inner_stride;
+  float acc = 0.0f;
+  for (long e = lane; e < len; e += 64) {
+    const float f = bf16_bits_to_f32(x[e * elem_stride]);
+    acc = __builtin_fmaf(f, f, acc);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+  // rounded up a little: the gate uses the product of two norms as an upper bound of sum |a b|
+  if (lane == 0) out[v] = __builtin_sqrtf(acc) * 1.0001f;
+}
+void launch_norms(const uint16_t* X, long n_outer, long outer_stride, long n_inner, long inner_stride, long len,
+                  long elem_stride, float* out, hipStream_t s) {
+  const long n = n_outer * n_inner;
+  if (n <= 0) return;
+  hipLaunchKernelGGL(tf_norms_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, X, n_outer, outer_stride, n_inner,
+                     inner_stride, len, elem_stride, out);
+}
+
 }  // namespace tf

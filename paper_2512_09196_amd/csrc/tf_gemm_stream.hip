@@ -197,6 +197,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_stream_kernel(const GemmPa
     if ((unsigned)(tk & 255u) != (unsigned)p.split_k) return;
     if (threadIdx.x == 0) *ctr = 0ull;          // ready for the next launch
     poisoned = local && (unsigned)((tk >> (8 + 7 * xcc)) & 127u) != (unsigned)p.split_k;
+    if (poisoned && threadIdx.x == 0) atomicOr(p.status, 1u);   // reported by the next synchronous call of the library
 #pragma unroll
     for (int o = 0; o < OWN; ++o) {
       const int f = wave + o * C::NW;

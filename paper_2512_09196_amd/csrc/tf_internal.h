@@ -15,6 +15,7 @@ struct GemmParams {
   void* Y;                // [M, ldy]: bf16 bits (TF_EPI_BIAS_GELU_ERF) or float (TF_EPI_NONE_F32)
   float* ws;              // split-K partial sums [split_k][M][N] (unused when split_k == 1)
   unsigned* counters;     // one 8-byte arrival counter per output tile, zero between launches
+  unsigned* status;       // status word of the workspace (behind the counters): bit 0 = an L2-local reduction found its slices on different XCDs
   int M, N, K;
   long lda, ldb, ldy;     // in elements
   long stride_a, stride_b, stride_y;   // batched problems (grid.y = batch items): elements between consecutive items
@@ -95,6 +96,12 @@ void launch_mfma_direct(const GemmParams&, hipStream_t);
 const void* naive_func();
 const void* mfma_direct_func();
 void launch_fill_u32(unsigned* p, size_t n, unsigned v, hipStream_t);
+void launch_fill_rows(void* y, size_t rows, size_t row_bytes, size_t ld_bytes, unsigned pattern, hipStream_t);   // row_bytes, ld_bytes multiples of 2; pattern repeated per 4 bytes (2-byte elements take its low half)
+void launch_xcc_probe(unsigned* out, int wgs, hipStream_t);                // out[i] = XCD id work-group i ran on
+// Euclidean norms of n_outer x n_inner vectors of `len` bf16 elements: vector (o, i) starts at X + o * outer_stride + i * inner_stride,
+// its elements are elem_stride apart; out[o * n_inner + i]
+void launch_norms(const uint16_t* X, long n_outer, long outer_stride, long n_inner, long inner_stride, long len, long elem_stride,
+                  float* out, hipStream_t);
 void launch_calib_mfma(float* sink, int wgs, int iters, hipStream_t);                       // 4 * iters MFMA 32x32x16 per wave, 4 waves per work-group
 void launch_calib_read(const void* src, size_t bytes, unsigned* sink, int wgs, hipStream_t);  // reads every byte once
 void launch_splitk_reduce(const GemmParams&, hipStream_t);   // sums ws slices in order, bias + epilogue -> Y

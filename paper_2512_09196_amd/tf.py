@@ -92,6 +92,10 @@ SIGNATURES = {
     "tf_variant_profile": (C.c_int32, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                        _P(Report)]),
+    "tf_workspace_status": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "tf_xcc_placement_ok": (C.c_int32, [_P(C.c_uint32), C.c_int32]),
+    "tf_gate_count_bad": (C.c_int64, [C.c_void_p, C.c_int64, _P(C.c_float), _P(C.c_float), _P(C.c_float), C.c_int64,
+                                      C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "tf_report_set_counters": (C.c_int32, [_P(Report), _P(Hw), C.c_char_p, C.c_char_p]),
     "tf_arbiter": (C.c_int32, [_P(Report), _P(Report), _P(Theta), C.c_int32, C.c_int32, C.c_int32]),
     "tf_refine_hint": (C.c_int32, [_P(Report), _P(Report), _P(Hw)]),
@@ -252,6 +256,28 @@ def tune_replay(desc: ProblemDesc, hw: Hw, family, reports, theta: Theta):
     return bv.value, best, [log[i] for i in range(nl.value)]
 
 
+def xcc_placement_ok(xcc_of_wg) -> bool:
+    arr = (C.c_uint32 * len(xcc_of_wg))(*[int(x) for x in xcc_of_wg])
+    return bool(lib().tf_xcc_placement_ok(arr, len(xcc_of_wg)))
+
+
+def gate_count_bad(Y, zref, norm_a, norm_b, K: int, epi: int, norm_b_row_stride: int = 0) -> int:
+    """tf_tune's built-in comparison on host arrays (numpy): Y uint16 bf16 bits or float32 [rows, N] (C-contiguous
+    rows; ldy = its row stride), zref float32 [rows, N] dense, norms float32. Returns the number of rejected elements."""
+    import numpy as np
+    rows, N = zref.shape
+    zref = np.ascontiguousarray(zref, dtype=np.float32)
+    norm_a = np.ascontiguousarray(norm_a, dtype=np.float32)
+    norm_b = np.ascontiguousarray(norm_b, dtype=np.float32)
+    assert Y.dtype == (np.float32 if epi == TF_EPI_NONE_F32 else np.uint16) and Y.shape[0] == rows and Y.strides[1] == Y.itemsize
+    ldy = Y.strides[0] // Y.itemsize
+    fp = lambda a: a.ctypes.data_as(_P(C.c_float))
+    r = lib().tf_gate_count_bad(C.c_void_p(Y.ctypes.data), ldy, fp(zref), fp(norm_a), fp(norm_b), norm_b_row_stride, rows, N, K, epi)
+    if r < 0:
+        _check(int(r))
+    return int(r)
+
+
 def report_set_counters(report: Report, hw: Hw, csv_path: str, kernel_substr: str) -> None:
     _check(lib().tf_report_set_counters(C.byref(report), C.byref(hw), csv_path.encode(), kernel_substr.encode()))
 
@@ -310,6 +336,10 @@ class Problem:
     def run(self, variant_id, A, B, bias, Y, workspace=None, workspace_bytes=0, stream=None):
         _check(lib().tf_variant_run(self._h, variant_id, _ptr(A), _ptr(B), _ptr(bias), _ptr(Y), _ptr(workspace),
                                     workspace_bytes, _stream(stream)))
+
+    def workspace_status(self, workspace=None, stream=None):
+        """Synchronises the stream; raises TfError(TF_E_LAUNCH) if an L2-local reduction reported a misplaced slice."""
+        _check(lib().tf_workspace_status(self._h, _ptr(workspace), _stream(stream)))
 
     def profile(self, variant_id, A, B, bias, Y, workspace=None, workspace_bytes=0, stream=None,
                 warmup=3, iters=5, launches_per_iter=0) -> Report:

@@ -330,11 +330,25 @@ def test_caller_workspace_and_errors():
     out = gu.OutBuf(M, N)
     with tf.Problem(M, N, K) as prob:
         v = [v for v in prob.variants() if v.split_k > 1][0]
-        ws = torch.full((v.workspace_bytes // 4 + 64,), -1, dtype=torch.int32, device="cuda")   # dirty on purpose
+        biggest = max(x.workspace_bytes for x in prob.variants())
+        ws = torch.full((biggest // 4 + 64,), -1, dtype=torch.int32, device="cuda")   # dirty on purpose
         got, intact, _ = gu.run_variant(prob, v.id, dA, dB, dbias, out, workspace=ws, workspace_bytes=ws.numel() * 4)
         assert intact and np.all(np.abs(got - y) <= gu.strict_bound(y, z, s, K))
         got2, _, _ = gu.run_variant(prob, v.id, dA, dB, dbias, out, workspace=ws, workspace_bytes=ws.numel() * 4)
         assert np.array_equal(got, got2)
+        # what a caller's workspace holds between two calls is the caller's: every reduction mode must cope with
+        # counters that were overwritten since the last launch (the library zeroes them ahead of each launch)
+        modes = set()
+        for v2 in [x for x in prob.variants() if x.split_k > 1]:
+            for fill in (-1, 0x01010101):
+                ws.fill_(fill)
+                got3, intact, _ = gu.run_variant(prob, v2.id, dA, dB, dbias, out, workspace=ws, workspace_bytes=ws.numel() * 4)
+                assert intact and not np.isnan(got3).any(), v2.name.decode()
+                assert np.all(np.abs(got3 - y) <= gu.strict_bound(y, z, s, K)), v2.name.decode()
+            modes.add(v2.fused_reduce)
+            prob.workspace_status(ws)          # synchronises; raises if an L2-local reduction reported misplaced slices
+        assert modes == {0, 1, 2}
+        prob.workspace_status()                # the library's own buffer (never used here): nothing to report
         with pytest.raises(tf.TfError) as e:
             prob.run(v.id, dA, dB, dbias, out.ptr, workspace=ws, workspace_bytes=1024)
         assert e.value.status == tf.TF_E_UNSUPPORTED
