@@ -259,6 +259,20 @@ tf_status tf_variant_run(tf_problem* p, int32_t variant_id, const void* A, const
                          const void* bias, void* Y, void* workspace, size_t workspace_bytes,
                          void* hip_stream);
 
+/* Same launch for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the workspace is a buffer of
+ * tf_static_scratch_bytes() bytes that is part of the library's device image, one copy per GPU,
+ * held until the process ends. The call allocates nothing and frees nothing. Variants whose
+ * workspace_bytes exceed the buffer fail with TF_E_UNSUPPORTED (nothing launched). The counter
+ * area is zeroed by a fill kernel ahead of every launch (no memset node), the rest keeps the last
+ * call's contents. Every call on a GPU shares that GPU's buffer: calls that overlap on one GPU
+ * race, whatever their streams or problems. The first fused_reduce == 2 launch on a device still
+ * runs the placement probe described above (it uses the same buffer). */
+tf_status tf_variant_run_static(tf_problem* p, int32_t variant_id, const void* A, const void* B,
+                                const void* bias, void* Y, void* hip_stream);
+/* Size of that buffer in bytes. */
+int64_t tf_static_scratch_bytes(void);
+
 /* Synchronises hip_stream and reads the status word of `workspace` (device pointer; NULL = the
  * problem's own buffer): TF_OK, or TF_E_LAUNCH if a launch since the last zeroing of the counter
  * area found the slices of a tile on different XCDs (fused_reduce == 2). */

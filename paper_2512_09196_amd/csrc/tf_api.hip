@@ -1064,6 +1064,37 @@ extern "C" tf_status tf_variant_profile(tf_problem* p, int32_t id, const void* A
                       launches_per_iter, out);
 }
 
+// ---- the workspace that is part of the device image, for callers that cannot allocate
+// 32 MiB of partial sums (e.g. four slices of a 1024 x 1024 output, or eight of 16 x 8192 ... 1024 x 1024) plus
+// the counter area.
+constexpr size_t kStaticScratchBytes = (32u << 20) + (64u << 10);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+// The array's name is a host-side stand-in, not a device address: each GPU holds its own copy at its own address,
+// looked up once per device (with that device current) and used from then on.
+static void* g_scratch_ptr[64];
+
+extern "C" int64_t tf_static_scratch_bytes(void) { return (int64_t)kStaticScratchBytes; }
+
+extern "C" tf_status tf_variant_run_static(tf_problem* p, int32_t id, const void* A, const void* B, const void* bias,
+                                           void* Y, void* hip_stream) {
+  tf_status st = prepare(p, id);        // makes the problem's device current
+  if (st != TF_OK) return st;
+  const int dev = p->desc.device;
+  if (dev < 0 || dev >= 64) return fail(TF_E_UNSUPPORTED, "device ordinal %d outside the table of per-device buffers", dev);
+  const tf_variant_desc& v = p->family[id];
+  if ((size_t)v.workspace_bytes > kStaticScratchBytes)
+    return fail(TF_E_UNSUPPORTED, "variant %s needs %lld bytes of workspace, the built-in buffer has %zu", v.name,
+                (long long)v.workspace_bytes, kStaticScratchBytes);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    TF_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(TF_E_LAUNCH, "hipGetSymbolAddress returned no address for the built-in buffer");
+    g_scratch_ptr[dev] = ptr;
+  }
+  // do_launch allocates only when it is handed no workspace; variants without one ignore it
+  return do_launch(p, id, A, B, bias, Y, g_scratch_ptr[dev], kStaticScratchBytes, (hipStream_t)hip_stream);
+}
+
 extern "C" tf_status tf_workspace_status(tf_problem* p, const void* workspace, void* hip_stream) {
   if (!p) return fail(TF_E_INVALID, "null problem");
   int id = -1;

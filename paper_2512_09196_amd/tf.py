@@ -92,6 +92,9 @@ SIGNATURES = {
     "tf_variant_profile": (C.c_int32, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                        _P(Report)]),
+    "tf_variant_run_static": (C.c_int32, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p]),
+    "tf_static_scratch_bytes": (C.c_int64, []),
     "tf_workspace_status": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "tf_xcc_placement_ok": (C.c_int32, [_P(C.c_uint32), C.c_int32]),
     "tf_gate_count_bad": (C.c_int64, [C.c_void_p, C.c_int64, _P(C.c_float), _P(C.c_float), _P(C.c_float), C.c_int64,
@@ -336,6 +339,10 @@ class Problem:
     def run(self, variant_id, A, B, bias, Y, workspace=None, workspace_bytes=0, stream=None):
         _check(lib().tf_variant_run(self._h, variant_id, _ptr(A), _ptr(B), _ptr(bias), _ptr(Y), _ptr(workspace),
                                     workspace_bytes, _stream(stream)))
+
+    def run_static(self, variant_id, A, B, bias, Y, stream=None):
+        """tf_variant_run on the workspace that is part of the library's device image: allocates nothing."""
+        _check(lib().tf_variant_run_static(self._h, variant_id, _ptr(A), _ptr(B), _ptr(bias), _ptr(Y), _stream(stream)))
 
     def workspace_status(self, workspace=None, stream=None):
         """Synchronises the stream; raises TfError(TF_E_LAUNCH) if an L2-local reduction reported a misplaced slice."""
