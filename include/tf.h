@@ -186,8 +186,9 @@ typedef struct {
   int32_t vgprs, agprs, sgprs, spill_bytes, lds_bytes;
   double occupancy_pct;          /* waves_per_simd / 8 */
   double grid_fill;              /* grid / (compute units * resident work-groups per CU), tail included */
-  int32_t have_counters;         /* 1 once tf_report_set_counters has filled the next five fields */
+  int32_t have_counters;         /* 1 once tf_report_set_counters has filled (some of) the next six fields */
   double mfma_busy_pct, lds_bank_conflict_pct, hbm_read_gbs, hbm_write_gbs, l2_hit_pct;
+  double achieved_occupancy_pct; /* resident waves per SIMD over the dispatch, as a share of max_waves_per_simd */
   int32_t bottleneck;            /* tf_bottleneck, filled by tf_refine_hint / tf_tune */
   int32_t parity_ok;             /* set by the caller's correctness gate; tf_tune takes it from its callback */
 } tf_report;
@@ -292,8 +293,19 @@ tf_status tf_variant_profile(tf_problem* p, int32_t variant_id, const void* A, c
                              void* hip_stream, int32_t warmup, int32_t iters,
                              int32_t launches_per_iter, tf_report* out);
 
-/* Reads a rocprofv3 counter CSV (columns Kernel_Name, Counter_Name, Counter_Value) and fills the
- * counter fields of *r from the rows whose kernel name contains `kernel_substr`. */
+/* Reads a rocprofv3 counter CSV (`rocprofv3 --pmc ... --output-format csv`: columns Kernel_Name,
+ * Counter_Name, Counter_Value; Dispatch_Id, Start_Timestamp, End_Timestamp if present) and fills
+ * the counter fields of *r (Sec. 3.4 "Profiling": the report carries what the profiler measured)
+ * from the rows whose kernel name contains `kernel_substr`, averaged over its dispatches:
+ *   mfma_busy_pct          SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE / xcds * cus * simds_per_cu)
+ *                          (without GRBM_GUI_ACTIVE: / (SQ_BUSY_CU_CYCLES * simds_per_cu))
+ *   achieved_occupancy_pct 4 SQ_WAVE_CYCLES / (GRBM_GUI_ACTIVE / xcds * cus * simds_per_cu * max_waves_per_simd)
+ *   lds_bank_conflict_pct  SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE
+ *   hbm_read_gbs           2 * FETCH_SIZE KiB / dispatch time;  hbm_write_gbs  WRITE_SIZE KiB / dispatch time
+ *   l2_hit_pct             TCC_HIT_sum / (TCC_HIT_sum + TCC_MISS_sum)
+ * A file holds the counters of one profiler pass; call once per file, fields a file does not cover keep
+ * their values. Sets have_counters and re-classifies r->bottleneck. TF_E_PROFILER if the file cannot be
+ * read, has no matching row or none of these counters. hw, csv_path, kernel_substr: host pointers. */
 tf_status tf_report_set_counters(tf_report* r, const tf_hw* hw, const char* csv_path,
                                  const char* kernel_substr);
 

@@ -1196,15 +1196,29 @@ extern "C" tf_status tf_report_set_counters(tf_report* r, const tf_hw* hw, const
   const double dur_us = dur_n > 0 ? dur_ns / dur_n * 1e-3 : r->t_med_us;
   double a = 0, b = 0;
   int got = 0;
-  if (mean("SQ_VALU_MFMA_BUSY_CYCLES", &a) && mean("SQ_BUSY_CU_CYCLES", &b) && b > 0) { r->mfma_busy_pct = 100.0 * a / b; ++got; }
-  else if (mean("SQ_VALU_MFMA_BUSY_CYCLES", &a) && mean("GRBM_GUI_ACTIVE", &b) && b > 0) {
-    // busy cycles are summed over the SIMD-quads of all CUs; GRBM_GUI_ACTIVE is wall cycles
-    r->mfma_busy_pct = 100.0 * a / (b * hw->cus * hw->simds_per_cu); ++got;
+  // GRBM_GUI_ACTIVE is reported as the sum over the XCDs of the cycles each was active: per XCD it is the
+  // dispatch's length in cycles. SQ_VALU_MFMA_BUSY_CYCLES (32 per 32x32x16 MFMA) is summed over all SIMDs,
+  // SQ_WAVE_CYCLES (units of four cycles) over all wave slots.
+  double wall_cycles = 0.0;
+  if (mean("GRBM_GUI_ACTIVE", &b) && b > 0 && hw->xcds > 0) wall_cycles = b / hw->xcds;
+  const double simds = (double)hw->cus * hw->simds_per_cu;
+  if (mean("SQ_VALU_MFMA_BUSY_CYCLES", &a)) {
+    if (wall_cycles > 0) { r->mfma_busy_pct = 100.0 * a / (wall_cycles * simds); ++got; }
+    else if (mean("SQ_BUSY_CU_CYCLES", &b) && b > 0) {
+      // no wall clock in the file: relative to the cycles the compute units were busy (each has simds_per_cu pipes)
+      r->mfma_busy_pct = 100.0 * a / (b * hw->simds_per_cu); ++got;
+    }
+  }
+  if (mean("SQ_WAVE_CYCLES", &a) && wall_cycles > 0 && hw->max_waves_per_simd > 0) {
+    r->achieved_occupancy_pct = 100.0 * 4.0 * a / (wall_cycles * simds * hw->max_waves_per_simd); ++got;
   }
   if (mean("SQ_LDS_BANK_CONFLICT", &a) && (mean("SQ_LDS_IDX_ACTIVE", &b) || mean("SQ_ACTIVE_INST_LDS", &b)) && b > 0) {
     r->lds_bank_conflict_pct = 100.0 * a / b; ++got;
   }
-  if (mean("FETCH_SIZE", &a) && dur_us > 0) { r->hbm_read_gbs = a * 1024.0 / dur_us * 1e-3; ++got; }
+  // FETCH_SIZE / WRITE_SIZE are KiB per dispatch. On this chip FETCH_SIZE reads half the bytes a plain device
+  // copy of known size fetches (it prices 128-byte requests as 64), WRITE_SIZE reads them all.
+  const double fetch_scale = 2.0;
+  if (mean("FETCH_SIZE", &a) && dur_us > 0) { r->hbm_read_gbs = a * fetch_scale * 1024.0 / dur_us * 1e-3; ++got; }
   if (mean("WRITE_SIZE", &a) && dur_us > 0) { r->hbm_write_gbs = a * 1024.0 / dur_us * 1e-3; ++got; }
   if (mean("TCC_HIT_sum", &a) && mean("TCC_MISS_sum", &b) && a + b > 0) { r->l2_hit_pct = 100.0 * a / (a + b); ++got; }
   if (!got) return fail(TF_E_PROFILER, "%s: none of the known counters present", csv_path);

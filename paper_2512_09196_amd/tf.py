@@ -58,7 +58,7 @@ class Report(_Struct):
                 ("lds_bytes", C.c_int32),
                 ("occupancy_pct", C.c_double), ("grid_fill", C.c_double), ("have_counters", C.c_int32),
                 ("mfma_busy_pct", C.c_double), ("lds_bank_conflict_pct", C.c_double), ("hbm_read_gbs", C.c_double),
-                ("hbm_write_gbs", C.c_double), ("l2_hit_pct", C.c_double),
+                ("hbm_write_gbs", C.c_double), ("l2_hit_pct", C.c_double), ("achieved_occupancy_pct", C.c_double),
                 ("bottleneck", C.c_int32), ("parity_ok", C.c_int32)]
 
 

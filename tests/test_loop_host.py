@@ -164,3 +164,38 @@ def test_cost_model_orders_the_obvious_cases():
                 assert tf.resident_wgs(hw, v) == (3 if v.stages == 3 else 4)
             f = tf.grid_fill(hw, v)
             assert 0.0 < f <= 1.0
+
+
+def test_case_study2_and_the_papers_two_hints_through_the_library():
+    """The same paper-fixed pins as in test_loop_oracle.py, applied to the library's own functions: the
+    profile table of Case Study 2 (Sec. 5) and the two example hints of Sec. 3.3."""
+    t = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "case_study2_profile.txt")):
+        if line.strip() and not line.startswith("#"):
+            f = line.split()
+            t[f[0]] = (float(f[1]), float(f[2]))
+    hw, th = tf.hw_nominal(), tf.theta_default()
+
+    def rep(t_us, mem, comp, occ, intensity=1.0):
+        d = rand_report(random.Random(0))
+        d.update(status=0, parity_ok=1, t_med_us=t_us, t_min_us=0.99 * t_us, grid_fill=1.0, have_counters=0,
+                 pct_mfma_peak=comp, pct_hbm_peak=mem, occupancy_pct=occ, arithmetic_intensity=intensity,
+                 lds_bank_conflict_pct=0.0)
+        return c_report(d)
+    before = rep(t["runtime_us"][0], t["memory_pct"][0], t["compute_pct"][0], t["occupancy_pct"][0])
+    after = rep(t["runtime_us"][1], t["memory_pct"][1], t["compute_pct"][1], 50.0)
+    assert tf.refine_hint(None, before, hw) == tf.TF_BN_LATENCY
+    assert tf.refine_hint(None, after, hw) == tf.TF_BN_HBM
+    assert tf.arbiter(after, before, th, True, 0, 1) == tf.TF_DEC_ACCEPT
+    # "memory stalls => improve tiling or staging", "low occupancy => adjust register pressure":
+    # the next proposal from a 128x128 two-buffer kernel
+    fam = [c_variant(dict(kind=0, bm=4, bn=64, stages=0, split_k=1, direct_to_lds=0, lds_bytes=0, grid=4096), 0),
+           c_variant(dict(kind=2, bm=128, bn=128, stages=2, split_k=1, direct_to_lds=1, lds_bytes=65536, grid=256), 1),
+           c_variant(dict(kind=2, bm=128, bn=128, stages=3, split_k=1, direct_to_lds=1, lds_bytes=98304, grid=256), 2),
+           c_variant(dict(kind=2, bm=64, bn=64, stages=2, split_k=1, direct_to_lds=1, lds_bytes=32768, grid=1024), 3)]
+    pred = [1000.0, 10.0, 20.0, 20.0]
+    tried = [True, True, False, False]
+    stalled = rep(100.0, 20.0, 30.0, 50.0, intensity=1000.0)
+    starved = rep(100.0, 20.0, 30.0, 12.5, intensity=1000.0)
+    assert tf.proposal_from(hw, fam, pred, tried, 1, tf.refine_hint(None, stalled, hw)) == 2     # deeper staging
+    assert tf.proposal_from(hw, fam, pred, tried, 1, tf.refine_hint(None, starved, hw)) == 3     # smaller tile, less LDS
