@@ -58,6 +58,10 @@ def _load():
             lib.tfo_gemm_bias_gelu.argtypes = [
                 ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long,
                 u16p, ctypes.c_long, u16p, f64p, f64p, f64p]
+            lib.tfo_gemm_nt_bias_gelu.restype = ctypes.c_int
+            lib.tfo_gemm_nt_bias_gelu.argtypes = [
+                ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long,
+                u16p, ctypes.c_long, u16p, f64p, f64p, f64p]
             lib.tfo_batched_vecmat.restype = ctypes.c_int
             lib.tfo_batched_vecmat.argtypes = [
                 ctypes.c_int, ctypes.c_int, ctypes.c_int, u16p, ctypes.c_long,
@@ -131,6 +135,28 @@ def gemm_bias_gelu(A, B, bias):
         _ptr(y, ctypes.c_double), _ptr(z, ctypes.c_double), _ptr(s, ctypes.c_double))
     if rc != 0:
         raise RuntimeError(f"tfo_gemm_bias_gelu failed with {rc}")
+    return y, z, s
+
+
+def gemm_nt_bias_gelu(A, Bt, bias):
+    """The same operation with the second operand given as [N, K] (k contiguous): z = A . Bt^T + bias.
+
+    A: uint16 [M, K], Bt: uint16 [N, K], bias: uint16 [N]. Returns (y, z, s), float64 [M, N]."""
+    A, Bt, bias = _u16(A, "A"), _u16(Bt, "Bt"), _u16(bias, "bias")
+    if A.ndim != 2 or Bt.ndim != 2 or bias.ndim != 1:
+        raise ValueError("A and Bt must be 2-D, bias 1-D")
+    M, K = A.shape
+    N, K2 = Bt.shape
+    if K2 != K or bias.shape[0] != N:
+        raise ValueError(f"shape mismatch A{A.shape} Bt{Bt.shape} bias{bias.shape}")
+    y = np.empty((M, N), np.float64)
+    z = np.empty((M, N), np.float64)
+    s = np.empty((M, N), np.float64)
+    rc = _load().tfo_gemm_nt_bias_gelu(
+        M, N, K, _ptr(A, ctypes.c_uint16), K, _ptr(Bt, ctypes.c_uint16), K, _ptr(bias, ctypes.c_uint16),
+        _ptr(y, ctypes.c_double), _ptr(z, ctypes.c_double), _ptr(s, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError(f"tfo_gemm_nt_bias_gelu failed with {rc}")
     return y, z, s
 
 

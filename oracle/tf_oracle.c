@@ -1,5 +1,6 @@
 /*
- * CPU oracle for the fused tile kernel  Y = GELU_erf(A.B + bias), and (last two functions of
+ * CPU oracle for the fused tile kernel  Y = GELU_erf(A.B + bias) (B as [K][N], or as [N][K] in
+ * tfo_gemm_nt_bias_gelu), and (last two functions of
  * the file but one) for the batched vector-matrix product of the paper's Case Study 2 and the
  * batched transposed-operand product of its Case Study 3, and (last) for the element-wise sine of
  * its Case Study 1.  tfo_gelu_tanh is the activation of the kernel's second bf16 epilogue.
@@ -153,6 +154,49 @@ int tfo_gemm_bias_gelu_at(int M, int N, int K,
         if (z) z[t] = zz;
         if (y) y[t] = tfo_gelu(zz);
         if (s) s[t] = abs_acc + fabs(bv);
+    }
+    return 0;
+}
+
+/*
+ * The same operation with the second operand given as [N][ldb], k contiguous (a weight matrix
+ * stored output-major; the layout question of the paper's Case Study 3, where an operand arrives
+ * transposed and the kernel either reads it as it lies or pays for a separate transposing pass):
+ *     z[m,n] = sum_{k=0}^{K-1} a[m,k] * bt[n,k] + bias[n],   y = GELU(z),   s = sum |a bt| + |bias|
+ * Written out as the definition: three nested loops (m, n, k), one dot product of two rows per
+ * element, products and sums in double, k ascending. Any of Y, Z, S may be NULL.
+ * Pinned by tests/test_oracle_gemm_nt.py: exact rational brute force, selector matrices that
+ * copy single columns of A, integer operands against an int64 contraction, a library product
+ * of the explicitly transposed operand, power-of-two scaling, and the zero-matrix / GELU(0)
+ * cases.
+ */
+int tfo_gemm_nt_bias_gelu(int M, int N, int K,
+                          const uint16_t *A, long lda,
+                          const uint16_t *Bt, long ldb,
+                          const uint16_t *bias,
+                          double *Y, double *Z, double *S)
+{
+    if (M < 0 || N < 0 || K < 0) return -1;
+    if (M == 0 || N == 0) return 0;
+    if ((K > 0 && (!A || !Bt)) || !bias) return -1;
+    if (lda < K || ldb < K) return -1;
+    for (int m = 0; m < M; ++m) {
+        const uint16_t *arow = A + (size_t)m * (size_t)lda;
+        for (int n = 0; n < N; ++n) {
+            const uint16_t *brow = Bt + (size_t)n * (size_t)ldb;
+            double acc = 0.0, abs_acc = 0.0;
+            for (int k = 0; k < K; ++k) {
+                const double p = tfo_bf16_to_double(arow[k]) * tfo_bf16_to_double(brow[k]);
+                acc += p;
+                abs_acc += fabs(p);
+            }
+            const double bv = tfo_bf16_to_double(bias[n]);
+            const double z = acc + bv;
+            const size_t o = (size_t)m * (size_t)N + (size_t)n;
+            if (Z) Z[o] = z;
+            if (Y) Y[o] = tfo_gelu(z);
+            if (S) S[o] = abs_acc + fabs(bv);
+        }
     }
     return 0;
 }
