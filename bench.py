@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the tile kernel Y = GELU_erf(A.B + bias) on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--variant NAME] [--no-cpu]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--variant NAME] [--no-cpu]
+                  [--no-per-config] [--counters FILE.csv ...]
 
 One step = one launch of the kernel the variant loop selected, over one batch of synthetic
 input that is already resident in HBM; batches rotate over enough buffer sets to exceed the
@@ -9,9 +10,18 @@ input that is already resident in HBM; batches rotate over enough buffer sets to
 The variant loop (Algorithm 1 of the paper: baseline profile, up to 8 rounds of proposal,
 run, parity gate, profile, arbiter) runs once before the timed region; its result, its
 round log and the tuned-vs-naive speedup are reported in the same JSON line.
+
+The headline workload is the largest of the five configurations (C3). Unless --no-per-config
+or another --workload is given, the other four are measured in the same run with the same
+protocol (fewer steps) and listed under "per_config".
+
+--counters: rocprofv3 counter files (one per profiler pass, e.g. of this same command run under
+`rocprofv3 --pmc ...`) are attached to the reports of the loop's rounds; the round log is then
+printed with the profiler's figures in the layout of the paper's Case Study 3 table.
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -24,32 +34,19 @@ if ROOT not in sys.path:
 BF16_PEAK_TFLOPS = 256 * 4096 * 2.4e9 / 1e12     # 2516.6: 256 CUs x 4096 flop/clk x 2.4 GHz, dense
 HBM_PEAK_GBS = 8000.0
 MALL_BYTES = 256 << 20
+TARGET_FRAC = {"mfma": 0.60, "hbm": 0.70}        # the stated goals: share of the bf16 MFMA peak / of the HBM peak
+GEMM_WORKLOADS = ["C1", "C2", "C3", "C4", "C5"]
 
 
-# rocprofv3 --pmc readings (KiB per dispatch) of the C2 kernels the loop ends on: (FETCH_SIZE, WRITE_SIZE).
-# A 256 MiB device copy reads FETCH_SIZE 131086 and WRITE_SIZE 262144 KiB, hence the scale factors.
+# HBM traffic per launch, RECORDED from earlier rocprofv3 --pmc runs of this file with --variant (KiB per dispatch:
+# FETCH_SIZE, WRITE_SIZE; summaries with the commands under profiles/). A kernel that is not listed, or that has
+# changed since its counters were taken, reports null. A 256 MiB device copy reads FETCH_SIZE 131086 and WRITE_SIZE
+# 262144 KiB, hence the scale factors.
 FETCH_SCALE, WRITE_SCALE = 262144.0 / 131084.9, 1.0
+TRAFFIC_SOURCE = "recorded: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, see profiles/"
 HBM_TRAFFIC_KIB = {
-    ("C2", "lds_128x128x64_w2x4_s3_direct_sk1"): (24691.0, 8192.0),
-    ("C2", "lds_128x128x64_w4x2_s3_direct_sk1"): (24690.6, 8192.0),
-    ("C2", "lds_128x128x64_w2x4_s4_direct_sk1"): (24694.9, 8192.0),
-    ("C2", "lds_128x128x64_w2x2x2_s3_direct_sk1"): (24690.5, 8192.0),
-    ("C2", "lds_128x128x64_w2x2x2_s4_direct_sk1"): (24699.5, 8192.0),
-    ("C2", "lds_128x128x64_w2x4_s3_direct_sk1x"): (24696.9, 8192.0),
-    ("C2", "lds_128x128x64_w4x2_s3_direct_sk1x"): (24699.6, 8193.1),
-    ("C2", "lds_128x128x64_w2x4_s4_direct_sk1x"): (24700.9, 8192.0),
-    ("C2", "lds_128x128x64_w2x2x2_s3_direct_sk1x"): (24700.5, 8192.0),
-    ("C2", "lds_128x128x64_w2x2x2_s4_direct_sk1x"): (24699.5, 8192.0),
-    ("C3", "lds_256x256x64_w2x4_s2_direct_sk1"): (314016.0, 88064.9),
-    ("C3", "lds_256x256x64_w4x2_s2_direct_sk1"): (303331.0, 88073.8),
-    ("C3", "lds_256x256x64_w2x4_s2_direct_sk1x"): (309078.1, 88064.3),
-    ("C3", "lds_256x256x64_w4x2_s2_direct_sk1x"): (303378.0, 88067.8),
-    ("C4", "lds_32x64x64_w1x2_s4_direct_sk2l"): (67568.4, 1290.9),
-    ("C4", "lds_32x64x64_w1x2_s4_direct_sk2r"): (66466.8 + 546.0, 1024.0 + 256.0),      # GEMM kernel + reduce kernel
     ("V2", "vecmat_r1_u4_w4_g0"): (525341.2, 1024.1),
     ("V2", "vecmat_r1_u8_w4_g0"): (525349.2, 1024.0),
-    ("T2", "bgemm_128x128x64_w2x2_s2_ldstrans"): (16516.6, 131878.9),
-    ("T2", "bgemm_128x128x64_w2x4_s2_ldstrans"): (16486.7, 131239.7),
     ("E2", "sin_b1024_t256_v4_g0_nt"): (131091.8, 262147.1),
     ("E2", "sin_b2048_t256_v4_g0_nt"): (131101.2, 262145.1),
 }
@@ -119,69 +116,105 @@ def cpu_baseline_sin(w, x, budget_s=12.0):
             "sample": "first %d of %d elements of %s in %.2f s" % (n, w.n, w.name, dt)}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    # a timed region of tens of milliseconds: shorter ones read a few per cent low and scatter more (clock ramp)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "V1", "V2", "T1", "T2", "E1", "E2"],
-                    help="C1..C5: Y = GELU_erf(A.B + bias); V1, V2: batched vector-matrix product C[m,n] = sum_k A[m,k] B[m,n,k]; "
-                         "T1, T2: batched transposed-operand product C[b] = A[b]^T B[b]; E1, E2: element-wise sine y = sin(x), fp32")
-    ap.add_argument("--epilogue", default="gelu_erf", choices=["gelu_erf", "gelu_tanh", "bias"],
-                    help="C1..C5 only: the bf16 epilogue (the headline metric is gelu_erf)")
-    ap.add_argument("--variant", default=None, help="time this variant instead of the loop's choice")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-tune", action="store_true", help="skip the loop (needs --variant)")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="launch a plain device copy of known size instead (reference reading for the HBM traffic counters)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        log("bench.py: the library runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)." % args.gpus)
-        sys.exit(2)
+def describe_change(prev, cur):
+    """What distinguishes variant `cur` from `prev` (descriptor fields), for the round table."""
+    if prev is None:
+        return "baseline kernel"
+    if prev.kind != cur.kind:
+        return "kernel family: %s" % cur.name.decode().split("_")[0]
+    fields = [("bm", "tile M"), ("bn", "tile N"), ("bk", "tile K"), ("waves_m", "waves M"), ("waves_n", "waves N"),
+              ("waves_k", "k groups"), ("stages", "buffers"), ("split_k", "K slices"), ("fused_reduce", "reduction"),
+              ("direct_to_lds", "staging"), ("a_bypass_lds", "A bypass"), ("k_rotate", "K order"), ("stream_k", "stream-K"),
+              ("trans_a", "A staging"), ("persistent", "persistent"), ("group_m", "grid cut"), ("nontemporal", "non-temporal")]
+    out = ["%s %d->%d" % (label, getattr(prev, f), getattr(cur, f)) for f, label in fields if getattr(prev, f) != getattr(cur, f)]
+    return ", ".join(out) if out else "same kernel"
 
+
+def round_table(tf, prob, variants, rlog, counter_files):
+    """The loop's round log with the profiler's figures, one row per round (the baseline is round 0), in the layout
+    of the paper's Case Study 3 table: variant and main change, time, speed-up, throughputs, occupancy, and the
+    direction each figure moved against the previous round."""
+    hw = tf.hw_query(0)
+    theta = tf.theta_default()
+    rows = []
+    best, best_is_base, stall = rlog[0], True, 0
+    prev_row, prev_v = None, None
+    for i, r in enumerate(rlog):
+        v = variants[r.variant_id]
+        sub = tf.kernel_substr(v)
+        got = []
+        if sub:
+            for f in counter_files:
+                try:
+                    tf.report_set_counters(r, hw, f, sub)
+                    got.append(os.path.basename(f))
+                except tf.TfError:
+                    pass            # this pass holds no dispatch of that kernel, or none of the known counters
+        if i == 0:
+            dec = "baseline"
+        else:
+            d = tf.arbiter(r, best, theta, best_is_base, stall, i)
+            dec = ["continue", "accept", "finish"][d]
+            if d == tf.TF_DEC_ACCEPT:
+                best, best_is_base, stall = r, False, 0
+            else:
+                stall += 1
+        hbm_pct = 100.0 * (r.hbm_read_gbs + r.hbm_write_gbs) / HBM_PEAK_GBS if r.have_counters else None
+        row = {"round": i, "variant": v.name.decode(), "main_change": describe_change(prev_v, v),
+               "t_med_us": round(r.t_med_us, 3), "speedup_vs_baseline": round(rlog[0].t_med_us / r.t_med_us, 3) if r.t_med_us > 0 else None,
+               "status": r.status, "parity_ok": r.parity_ok, "have_counters": r.have_counters, "counter_files": got,
+               "mfma_busy_pct": round(r.mfma_busy_pct, 2) if r.have_counters else None,
+               "hbm_pct": round(hbm_pct, 2) if hbm_pct is not None else None,
+               "l2_hit_pct": round(r.l2_hit_pct, 2) if r.have_counters else None,
+               "lds_bank_conflict_pct": round(r.lds_bank_conflict_pct, 3) if r.have_counters else None,
+               "achieved_occupancy_pct": round(r.achieved_occupancy_pct, 2) if r.have_counters else None,
+               "static_occupancy_pct": round(r.occupancy_pct, 1), "pct_mfma_peak": round(r.pct_mfma_peak, 2),
+               "pct_hbm_peak": round(r.pct_hbm_peak, 2),
+               "bottleneck": tf.BOTTLENECK_NAMES[tf.refine_hint(rlog[i - 1] if i else None, r, hw)], "decision": dec}
+        if prev_row is not None:
+            def delta(k):
+                a, b = prev_row.get(k), row.get(k)
+                return None if a is None or b is None else round(b - a, 2)
+            row["vs_previous_round"] = {"t_med_us": delta("t_med_us"), "mfma_busy_pct": delta("mfma_busy_pct"), "hbm_pct": delta("hbm_pct"),
+                                        "achieved_occupancy_pct": delta("achieved_occupancy_pct")}
+        rows.append(row)
+        prev_row, prev_v = row, v
+    fmt = "%-5s %-46s %-34s %10s %8s %9s %7s %7s %7s %-12s %-8s"
+    log(fmt % ("round", "variant", "main change", "time us", "speedup", "MFMA bsy%", "HBM %", "occ %", "LDScf%", "class", "decision"))
+    for row in rows:
+        def s(x, f="%.1f"):
+            return "-" if x is None else f % x
+        log(fmt % (row["round"], row["variant"][:46], row["main_change"][:34], "%.2f" % row["t_med_us"], s(row["speedup_vs_baseline"], "%.2fx"),
+                   s(row["mfma_busy_pct"]), s(row["hbm_pct"]), s(row["achieved_occupancy_pct"]), s(row["lds_bank_conflict_pct"], "%.2f"),
+                   row["bottleneck"], row["decision"]))
+    return rows
+
+
+def measure(args, name, steps, warmup, headline):
+    """Generates the workload, runs the variant loop, times `steps` launches of the selected kernel. Returns the
+    result record; with `headline` also the pieces the JSON line needs (host inputs for the CPU leg)."""
     import numpy as np
     import torch
     from paper_2512_09196_amd import tf
     from paper_2512_09196_amd import workloads as wl
 
-    if not torch.cuda.is_available():
-        log("bench.py: no GPU visible; there is no CPU path.")
-        sys.exit(3)
-    torch.cuda.set_device(0)
-    if args.copy_calibration:
-        # 256 MiB read + 256 MiB written per launch, from buffers that rotate past the memory-side cache
-        n = 128 << 20
-        src = [torch.ones(n, dtype=torch.int16, device="cuda") for _ in range(4)]
-        dst = [torch.empty(n, dtype=torch.int16, device="cuda") for _ in range(4)]
-        torch.cuda.synchronize()
-        for i in range(args.warmup + args.steps):
-            dst[i % 4].copy_(src[i % 4])
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_calibration": True, "launches": args.warmup + args.steps,
-                          "bytes_read_per_launch": 2 * n, "bytes_written_per_launch": 2 * n}))
-        return
-    vecmat = args.workload.startswith("V")
-    bgemm = args.workload.startswith("T")
-    sin = args.workload.startswith("E")
-    w = (wl.VECMAT_WORKLOADS[args.workload] if vecmat else wl.BGEMM_WORKLOADS[args.workload] if bgemm
-         else wl.SIN_WORKLOADS[args.workload] if sin else wl.WORKLOADS[args.workload])
+    vecmat, bgemm, sin = name.startswith("V"), name.startswith("T"), name.startswith("E")
+    w = (wl.VECMAT_WORKLOADS[name] if vecmat else wl.BGEMM_WORKLOADS[name] if bgemm
+         else wl.SIN_WORKLOADS[name] if sin else wl.WORKLOADS[name])
     if sin:
         log("generating %s (n=%d, seed %d)" % (w.name, w.n, w.seed))
         A = wl.make_sin_input(w.n, w.seed).view(np.int16)       # carried as raw 16-bit halves like the other operands
         B, bias = np.zeros(8, np.int16), None
     else:
         log("generating %s (M=%d N=%d K=%d, seed %d)" % (w.name, w.M, w.N, w.K, w.seed))
-    if sin:
-        pass
-    elif vecmat:
-        A, B = wl.make_vecmat(w.M, w.N, w.K, w.seed)
-        bias = None
-    elif bgemm:
-        A, B = wl.make_bgemm(w.batch, w.M, w.N, w.K, w.seed)
-        bias = None
-    else:
-        A, B, bias = wl.make_inputs(w)
+        if vecmat:
+            A, B = wl.make_vecmat(w.M, w.N, w.K, w.seed)
+            bias = None
+        elif bgemm:
+            A, B = wl.make_bgemm(w.batch, w.M, w.N, w.K, w.seed)
+            bias = None
+        else:
+            A, B, bias = wl.make_inputs(w)
     set_bytes = w.algorithmic_bytes
     nbuf = max(2, min(24, -(-2 * MALL_BYTES // set_bytes)))
     log("buffer sets: %d x %.1f MB" % (nbuf, set_bytes / 1e6))
@@ -205,34 +238,39 @@ def main():
     variants = prob.variants()
     names = [v.name.decode() for v in variants]
     tune = None
-    if not args.no_tune:
+    vid = None
+    use_variant = args.variant if headline else None
+    if not (args.no_tune and headline):
         t0 = time.perf_counter()
         best, rep, rlog = prob.tune(dA[0], dB[0], db[0], dY[0], stream=stream)
         tune_s = time.perf_counter() - t0
         rounds = [{"variant": names[r.variant_id], "t_med_us": round(r.t_med_us, 3), "status": r.status,
                    "parity_ok": r.parity_ok, "bottleneck": tf.BOTTLENECK_NAMES[r.bottleneck],
-                   "pct_mfma_peak": round(r.pct_mfma_peak, 2), "pct_hbm_peak": round(r.pct_hbm_peak, 2)} for r in rlog]
+                   "pct_mfma_peak": round(r.pct_mfma_peak, 2), "pct_hbm_peak": round(r.pct_hbm_peak, 2),
+                   "static_occupancy_pct": round(r.occupancy_pct, 1)} for r in rlog]
         for r in rounds:
             log("  loop:", r)
         tune = {"selected": names[best], "rounds": len(rlog) - 1, "wall_s": round(tune_s, 3),
                 "naive_us": round(rlog[0].t_med_us, 3), "tuned_us": round(rep.t_med_us, 3),
                 "tuned_vs_naive": round(rlog[0].t_med_us / rep.t_med_us, 2),
+                "gate": "built-in: every candidate against the baseline kernel's fp32 pre-activation, strict bound",
                 "one_shot_pick": rounds[1]["variant"] if len(rounds) > 1 else None,
                 "one_shot_us": rounds[1]["t_med_us"] if len(rounds) > 1 else None, "log": rounds}
+        if headline and args.counters:
+            tune["round_table"] = round_table(tf, prob, variants, rlog, args.counters)
         vid = best
-    if args.variant is not None:
-        if args.variant not in names:
-            log("unknown variant %s; have: %s" % (args.variant, ", ".join(names)))
+    if use_variant is not None:
+        if use_variant not in names:
+            log("unknown variant %s; have: %s" % (use_variant, ", ".join(names)))
             sys.exit(2)
-        vid = names.index(args.variant)
-    elif args.no_tune:
+        vid = names.index(use_variant)
+    elif vid is None:
         log("--no-tune needs --variant")
         sys.exit(2)
     v = variants[vid]
     log("timing variant", names[vid])
 
     # marshal the arguments once: the timed loop is nothing but tf_variant_run calls
-    import ctypes
     run = tf.lib().tf_variant_run
     sp = ctypes.c_void_p(stream.cuda_stream)
     argsets = [(prob._h, vid, ctypes.c_void_p(dA[j].data_ptr()), ctypes.c_void_p(dB[j].data_ptr()),
@@ -244,20 +282,26 @@ def main():
         if run(*argsets[i % nbuf]) != 0:
             raise RuntimeError(tf.lib().tf_last_error().decode())
 
-    for i in range(args.warmup):
+    if steps is None:
+        # the other configurations: a timed region of about 0.1 s
+        t_guess = tune["tuned_us"] if tune else 100.0
+        steps = int(max(50, min(4000, 1e5 / max(t_guess, 1.0))))
+        warmup = max(10, steps // 10)
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record(stream)
-    for i in range(args.steps):
+    for i in range(steps):
         step(i)
     e1.record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ev_ms = e0.elapsed_time(e1)
-    ms_per_step = wall_ms / args.steps
-    kern_us = ev_ms * 1e3 / args.steps          # average launch duration on the launch stream
+    prob.workspace_status(stream=stream)           # raises if a reduction that relies on work-group placement went wrong
+    ms_per_step = wall_ms / steps
+    kern_us = ev_ms * 1e3 / steps          # average launch duration on the launch stream
     tflops = w.flops / (ms_per_step * 1e-3) * 1e-12
     if bound_kind == "hbm":
         roof = {"bound": "hbm", "achieved": w.algorithmic_bytes / (kern_us * 1e-6) * 1e-9, "peak": HBM_PEAK_GBS,
@@ -266,46 +310,155 @@ def main():
         roof = {"bound": "mfma", "achieved": w.flops / (kern_us * 1e-6) * 1e-12, "peak": BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    # HBM traffic per launch from the TCC counters (two rocprofv3 --pmc runs of this file with --variant),
-    # scaled by what the same counters read for a plain 256 MiB copy; None for kernels not measured
+    roof["target_frac"] = TARGET_FRAC[roof["bound"]] if name in GEMM_WORKLOADS and name != "C1" else None
+    roof["met"] = None if roof["target_frac"] is None else bool(roof["frac"] >= roof["target_frac"])
     t = HBM_TRAFFIC_KIB.get((w.name, names[vid]))
     roof["traffic"] = None if t is None else (t[0] * FETCH_SCALE + t[1] * WRITE_SCALE) * 1024.0
     roof["traffic_unit"] = "bytes per launch"
+    roof["traffic_source"] = TRAFFIC_SOURCE if t is not None else None
     roof["kernel"] = names[vid]
     roof["avg_launch_us"] = kern_us
-    # context: what this chip sustains right now on a register-only MFMA loop with data-like operands and on a
-    # 1 GiB streaming read; `frac` stays the fraction of the published peak
-    mfma_meas, hbm_meas = tf.hw_measure(0, stream)
-    roof["measured_achievable"] = {"mfma_tflops": mfma_meas, "hbm_read_gbs": hbm_meas,
-                                   "frac_of_measured": roof["achieved"] / (hbm_meas if bound_kind == "hbm" else mfma_meas)}
+
+    # context only: the vendor's GEMM library on the same operands (matrix product alone: no bias, no activation)
+    lib_us = None
+    if not args.no_library_context and not nobias:
+        try:
+            a16 = [x.view(torch.bfloat16) for x in dA]
+            b16 = [x.view(torch.bfloat16) for x in dB]
+            n_lib = max(20, min(steps, 200))
+            for i in range(5):
+                torch.matmul(a16[i % nbuf], b16[i % nbuf], out=dY[i % nbuf])
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for i in range(n_lib):
+                torch.matmul(a16[i % nbuf], b16[i % nbuf], out=dY[i % nbuf])
+            e1.record(stream)
+            torch.cuda.synchronize()
+            lib_us = e0.elapsed_time(e1) * 1e3 / n_lib
+        except Exception as e:      # context must never fail the benchmark
+            log("library context skipped:", e)
 
     if sin:
         workload = "%s: n=%d fp32, N(0, 10) inputs, seed %d" % (w.name, w.n, w.seed)
     else:
         workload = "%s: %sM=%d N=%d K=%d bf16, seed %d" % (w.name, "batch=%d " % w.batch if bgemm else "", w.M, w.N, w.K, w.seed)
+    rec = {"workload": workload, "variant": names[vid], "grid": v.grid, "split_k": v.split_k, "buffer_sets": nbuf,
+           "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "avg_launch_us": kern_us,
+           "tflops": tflops, "gbs_algorithmic": w.algorithmic_bytes / (ms_per_step * 1e-3) * 1e-9,
+           "bound": roof["bound"], "frac": roof["frac"], "target_frac": roof["target_frac"], "met": roof["met"],
+           "traffic": roof["traffic"],
+           "naive_us": tune["naive_us"] if tune else None, "tuned_vs_naive": tune["tuned_vs_naive"] if tune else None,
+           "rounds": tune["rounds"] if tune else None, "one_shot_pick": tune["one_shot_pick"] if tune else None,
+           "vendor_library_gemm_us": lib_us}
+    extra = None
+    if headline:
+        extra = {"w": w, "A": A, "B": B, "bias": bias, "roof": roof, "tune": tune, "kinds": (vecmat, bgemm, sin),
+                 "value": w.n / (ms_per_step * 1e-3) * 1e-9 if sin else tflops, "stream": stream}
+    prob.close()
+    del dA, dB, db, dY, argsets
+    torch.cuda.empty_cache()
+    return rec, extra
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    # a timed region of hundreds of milliseconds: short ones read a few per cent low and scatter more (clock ramp)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default=None, choices=["C1", "C2", "C3", "C4", "C5", "V1", "V2", "T1", "T2", "E1", "E2"],
+                    help="C1..C5: Y = GELU_erf(A.B + bias) (default C3, the largest; the other four are then listed under per_config); "
+                         "V1, V2: batched vector-matrix product C[m,n] = sum_k A[m,k] B[m,n,k]; "
+                         "T1, T2: batched transposed-operand product C[b] = A[b]^T B[b]; E1, E2: element-wise sine y = sin(x), fp32")
+    ap.add_argument("--epilogue", default="gelu_erf", choices=["gelu_erf", "gelu_tanh", "bias"],
+                    help="C1..C5 only: the bf16 epilogue (the headline metric is gelu_erf)")
+    ap.add_argument("--variant", default=None, help="time this variant instead of the loop's choice")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-tune", action="store_true", help="skip the loop (needs --variant)")
+    ap.add_argument("--no-per-config", action="store_true", help="measure the headline workload only")
+    ap.add_argument("--no-library-context", action="store_true", help="skip the vendor-library matrix product timed for context")
+    ap.add_argument("--counters", action="append", default=[],
+                    help="rocprofv3 --pmc counter CSV (repeatable, one per profiler pass): attach to the loop's rounds and print the round table")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="launch a plain device copy of known size instead (reference reading for the HBM traffic counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: the library runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)." % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2512_09196_amd import tf
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; there is no CPU path.")
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    if args.copy_calibration:
+        # 256 MiB read + 256 MiB written per launch, from buffers that rotate past the memory-side cache
+        n = 128 << 20
+        src = [torch.ones(n, dtype=torch.int16, device="cuda") for _ in range(4)]
+        dst = [torch.empty(n, dtype=torch.int16, device="cuda") for _ in range(4)]
+        torch.cuda.synchronize()
+        for i in range(args.warmup + args.steps):
+            dst[i % 4].copy_(src[i % 4])
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "launches": args.warmup + args.steps,
+                          "bytes_read_per_launch": 2 * n, "bytes_written_per_launch": 2 * n}))
+        return
+    default_run = args.workload is None
+    name = "C3" if default_run else args.workload
+    per_config = default_run and not args.no_per_config and args.variant is None and not args.no_tune and args.epilogue == "gelu_erf"
+
+    rec, x = measure(args, name, args.steps, args.warmup, headline=True)
+    w, roof, tune = x["w"], x["roof"], x["tune"]
+    vecmat, bgemm, sin = x["kinds"]
+    # context: what this chip sustains right now on a register-only MFMA loop with data-like operands and on a
+    # 1 GiB streaming read; `frac` stays the fraction of the published peak
+    mfma_meas, hbm_meas = tf.hw_measure(0, x["stream"])
+    roof["measured_achievable"] = {"mfma_tflops": mfma_meas, "hbm_read_gbs": hbm_meas,
+                                   "frac_of_measured": roof["achieved"] / (hbm_meas if roof["bound"] == "hbm" else mfma_meas)}
+    configs = None
+    if per_config:
+        configs = []
+        for other in GEMM_WORKLOADS:
+            if other == name:
+                configs.append(rec)
+                continue
+            log("---- per-config:", other)
+            r2, _ = measure(args, other, None, None, headline=False)
+            configs.append(r2)
+        for c in configs:
+            log("  %-4s %-46s %9.2f us  %7.1f TFLOP/s  %7.1f GB/s  %s frac %.3f%s  tuned/naive %sx  vendor GEMM %s us" % (
+                c["workload"][:2], c["variant"], c["avg_launch_us"], c["tflops"], c["gbs_algorithmic"], c["bound"], c["frac"],
+                "" if c["target_frac"] is None else " (target %.2f, met: %s)" % (c["target_frac"], c["met"]),
+                c["tuned_vs_naive"], "-" if c["vendor_library_gemm_us"] is None else "%.1f" % c["vendor_library_gemm_us"]))
+
     out = {
         "metric": ("element-wise sine Gelement/s (y = sin(x), fp32 in and out)" if sin else
                    "batched vector-matrix product TFLOP/s (C[m,n] = sum_k A[m,k] B[m,n,k], bf16 in, fp32 out)" if vecmat
                    else "batched transposed-operand product TFLOP/s (C[b] = A[b]^T B[b], bf16 in, fp32 out)" if bgemm
                    else "GEMM+epilogue TFLOP/s (bf16 %s, fp32 accumulate)"
                    % {"gelu_erf": "GELU_erf(A.B+bias)", "gelu_tanh": "GELU_tanh(A.B+bias)", "bias": "A.B+bias"}[args.epilogue]),
-        "value": w.n / (ms_per_step * 1e-3) * 1e-9 if sin else tflops, "unit": "Gelement/s" if sin else "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": x["value"], "unit": "Gelement/s" if sin else "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": rec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if vecmat or sin else "bf16", "data": "synthetic",
-        "config": {"workload": workload,
-                   "variant": names[vid], "grid": v.grid, "split_k": v.split_k, "buffer_sets": nbuf},
-        "pct_bf16_mfma_peak": 100.0 * tflops / BF16_PEAK_TFLOPS,
-        "hbm_gbs_algorithmic": w.algorithmic_bytes / (ms_per_step * 1e-3) * 1e-9,
+        "config": {"workload": rec["workload"],
+                   "variant": rec["variant"], "grid": rec["grid"], "split_k": rec["split_k"], "buffer_sets": rec["buffer_sets"]},
+        "pct_bf16_mfma_peak": 100.0 * rec["tflops"] / BF16_PEAK_TFLOPS,
+        "hbm_gbs_algorithmic": rec["gbs_algorithmic"],
+        "vendor_library_gemm_us": rec["vendor_library_gemm_us"],
         "roofline": roof,
         "tune": tune,
+        "per_config": configs,
     }
     if not args.no_cpu:
         log("timing the CPU oracle on a bounded sample ...")
+        A, B, bias = x["A"], x["B"], x["bias"]
         out["cpu_baseline"] = (cpu_baseline_sin(w, A.view(np.float32)) if sin else cpu_baseline_vecmat(w, A, B) if vecmat else cpu_baseline_bgemm(w, A, B) if bgemm
                                else cpu_baseline(w, A, B, bias))
     else:
         out["cpu_baseline"] = None
-    prob.close()
     print(json.dumps(out))
 
 

@@ -97,7 +97,7 @@ typedef enum { TF_DEC_CONTINUE = 0, TF_DEC_ACCEPT = 1, TF_DEC_FINISH = 2 } tf_de
 
 /* The operation. */
 typedef enum {
-  TF_OP_GEMM_EPILOGUE = 0,  /* Y = epilogue(A.B + bias): A [M][lda], B [K][ldb], bias [N], Y [M][ldy] */
+  TF_OP_GEMM_EPILOGUE = 0,  /* Y = epilogue(A.B + bias): A [M][lda], B [K][ldb] (or [N][ldb], see trans_b), bias [N], Y [M][ldy] */
   TF_OP_BATCHED_VECMAT = 1, /* Case Study 2 of the paper (Sec. 5): C[m][n] = sum_k A[m][k] B[m][n][k].
                                A [M][lda] bf16 (lda >= K); B [M][N][ldb] bf16, k contiguous (ldb >= K),
                                matrix m starting N * ldb elements after matrix m - 1; Y = C as fp32
@@ -123,6 +123,8 @@ typedef struct {
   int32_t batch;           /* TF_OP_BATCHED_GEMM_TN: number of items (>= 0); otherwise ignored */
   int64_t stride_a, stride_b, stride_y;   /* TF_OP_BATCHED_GEMM_TN: elements between consecutive items
                                              (>= K * lda, K * ldb, M * ldy); otherwise ignored */
+  int32_t trans_b;         /* TF_OP_GEMM_EPILOGUE: 1 = B is given as [N][ldb] with k contiguous (ldb >= K), a weight
+                              matrix stored output-major; 0 = B is [K][ldb] (ldb >= N). Otherwise ignored */
 } tf_problem_desc;
 
 /* One member of the kernel family: the paper's "tiling/block shapes, num_warps, vectorization
@@ -130,7 +132,7 @@ typedef struct {
 typedef struct {
   int32_t id;              /* index for tf_variant_run; 0 is always the naive baseline */
   int32_t kind;            /* tf_kind */
-  int32_t bm, bn, bk;      /* macro tile; TF_KIND_SIN: bn = elements per work-group and pass of its grid stride (the
+  int32_t bm, bn, bk;      /* macro tile M, N, K (tile kernels: bk = 32, 64 or 128); TF_KIND_SIN: bn = elements per work-group and pass of its grid stride (the
                               case's BLOCK_SIZE), bk = consecutive elements per lane and access, stages = accesses
                               per lane and pass, group_m = work-groups per CU of a grid-stride launch (0: one
                               work-group per bn elements) */
@@ -151,6 +153,11 @@ typedef struct {
   int32_t trans_a;         /* TF_OP_BATCHED_GEMM_TN, tile kernels: 1 = the A tile is staged as it lies in memory
                               ([k][m]) and transposed by the LDS read; 0 = a separate pass first writes A^T
                               into the workspace and the tile kernel reads that                        */
+  int32_t trans_b;         /* problems with B given as [N][K] (tf_problem_desc.trans_b): 1 = a tile kernel compiled for
+                              that layout (the B tile is staged [n][k] and read like the A tile); 0 on a tile kernel
+                              = a separate pass first writes B^T ([K][N]) into the workspace and an ordinary tile
+                              kernel reads that (names ending in `pretransB`) - the kernel-or-host transposition
+                              question of the paper's Case Study 3                                      */
   int32_t stream_k;        /* 1: stream-K scheduling. All but the last one to two rounds of tiles are computed whole,
                               one work-group each; the K steps of the remaining tiles are dealt out evenly to one
                               further work-group per CU, each taking up to three (tile, K range) pieces; a tile

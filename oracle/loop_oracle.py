@@ -106,8 +106,8 @@ def moves_in_direction(hint, base, v, fill_base, fill_v):
     if hint == OCCUPANCY:
         return area_v < area_b or (area_v == area_b and v["lds_bytes"] < base["lds_bytes"])
     if hint == LATENCY:
-        return (v["stages"] > base["stages"] or (v["direct_to_lds"] and not base["direct_to_lds"])
-                or area_v > area_b)
+        return (v["stages"] > base["stages"] or v["bk"] > base["bk"]
+                or (v["direct_to_lds"] and not base["direct_to_lds"]) or area_v > area_b)
     return True
 
 

@@ -131,7 +131,7 @@ void build_bgemm_family(tf_problem* p) {
   for (int pass = 0; pass < 2; ++pass) {          // 0: transposed staging, 1: separate transposing pass
     for (int i = 0; i < tf::lds_kernel_count(); ++i) {
       const tf::LdsKernelInfo& k = tab[i];
-      if (!k.direct_to_lds || k.a_bypass_lds || k.waves_k != 1 || k.stream_k) continue;
+      if (!k.direct_to_lds || k.a_bypass_lds || k.waves_k != 1 || k.stream_k || k.trans_b || k.bk != 64) continue;
       if (pass == 0 && !k.trans_a) continue;
       // the persistent kernel: whole tiles, enough K steps to keep its ring busy across a tile's output
       if (k.persistent && (pass == 1 || d.M % k.bm || d.N % k.bn || d.K / 64 < k.stages - 1)) continue;
@@ -227,18 +227,31 @@ void build_family(tf_problem* p) {
   }
   // LDS-staged tile kernels: 16-byte chunks must not straddle a row end, and tile-relative
   // byte offsets are kept in 32 bits.
+  const bool tb = d.trans_b != 0;        // B given as [N][ldb], k contiguous
   const bool aligned = d.M > 0 && d.N >= 8 && d.K >= 8 && d.K % 8 == 0 && d.N % 8 == 0 && d.lda % 8 == 0 &&
                        d.ldb % 8 == 0 && d.ldy % 8 == 0 &&
                        (double)d.M * (double)d.lda * 2.0 < 4294967296.0 &&
-                       (double)d.K * (double)d.ldb * 2.0 < 4294967296.0;
+                       (double)(tb ? d.N : d.K) * (double)d.ldb * 2.0 < 4294967296.0 &&
+                       (double)d.K * (double)d.N * 2.0 < 4294967296.0;
   if (!aligned) return;
   const int cus = p->hw.cus > 0 ? p->hw.cus : 256;
   const tf::LdsKernelInfo* tab = tf::lds_kernel_table();
-  const long ktiles = cdivl(d.K, 64);
+  // pass 0: kernels compiled for the layout B arrives in; pass 1 (B as [N][K] only): a separate pass writes
+  // B^T ([K][N]) into the workspace and an ordinary kernel reads that - the alternative the loop measures
+  for (int pass = 0; pass < (tb ? 2 : 1); ++pass)
   for (int i = 0; i < tf::lds_kernel_count(); ++i) {
     const tf::LdsKernelInfo& k = tab[i];
     if (k.trans_a) continue;                               // kernels of the transposed-operand product
-    if (k.direct_to_lds && d.K % 64 != 0) continue;        // no zero fill on the direct path
+    if (pass == 0 && (k.trans_b != 0) != tb) continue;
+    if (pass == 1) {
+      // a few representative kernels behind the transposing pass
+      const bool pick = !k.trans_b && k.direct_to_lds && !k.a_bypass_lds && !k.stream_k && k.waves_k == 1 && k.bk == 64 &&
+                        ((k.bm == 256 && k.bn == 256) || (k.bm == 128 && k.bn == 128 && k.threads == 512 && k.stages == 3) ||
+                         (k.bm == 64 && k.bn == 64) || (k.bm == 32 && k.bn == 64 && k.stages == 4));
+      if (!pick) continue;
+    }
+    const long ktiles = cdivl(d.K, k.bk);
+    if (k.direct_to_lds && d.K % k.bk != 0) continue;      // no zero fill on the direct path
     if (k.stream_k) {
       // stream-K: more tiles than CUs, not a whole number of rounds, and enough K steps to be worth sharing
       const long tm = cdivl(d.M, k.bm), tn = cdivl(d.N, k.bn), T = tm * tn;
@@ -269,7 +282,9 @@ void build_family(tf_problem* p) {
     if (tm * tn > 0x7fffffffL / 16) continue;
     static const int splits[] = {1, 2, 4, 8, 16};
     for (int s : splits) {
-      if (s > 1 && (ktiles / s < 4 || tm * tn >= 2L * cus)) continue;
+      if (pass == 1 && s > 1) continue;
+      // a slice needs at least about 256 values of K (four tiles of 64) to be worth its partial tile
+      if (s > 1 && (ktiles * k.bk / s < 256 || ktiles / s < 2 || tm * tn >= 2L * cus)) continue;
       const long per = cdivl(ktiles, s);
       if (s > 1 && per * (s - 1) >= ktiles) continue;      // would leave an empty slice
       // slices summed by the last one to arrive (2: partial tiles exchanged through the L2 of the XCD
@@ -282,7 +297,7 @@ void build_family(tf_problem* p) {
         if (s == 1 && fused == 0) continue;
         if (s > 1 && fused != 0 && !k.fused_ok) continue;
         // without split-K also with the K order rotated by XCD (worth it for some shapes, not for others)
-        const int rotations = (s == 1 && k.direct_to_lds && ktiles >= 8) ? 2 : 1;
+        const int rotations = (s == 1 && k.direct_to_lds && ktiles * k.bk >= 512) ? 2 : 1;
         for (int kr = 0; kr < rotations; ++kr) {
         tf_variant_desc v;
         memset(&v, 0, sizeof(v));
@@ -290,6 +305,7 @@ void build_family(tf_problem* p) {
         v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n; v.waves_k = k.waves_k;
         v.stages = k.stages; v.split_k = s; v.fused_reduce = (s > 1) ? fused : 0;
         v.direct_to_lds = k.direct_to_lds; v.a_bypass_lds = k.a_bypass_lds; v.xcd_swizzle = 1;
+        v.trans_b = k.trans_b;
         v.group_m = (int32_t)std::min<long>(tm, 8);
         v.threads = k.threads; v.lds_bytes = k.lds_bytes;
         v.grid = (int32_t)(tm * tn * s);
@@ -297,10 +313,12 @@ void build_family(tf_problem* p) {
         im.lds_index = i; im.ktiles_per_split = (int)per; im.tiles_m = (int)tm; im.tiles_n = (int)tn;
         im.counter_bytes = s > 1 ? (size_t)((tm * tn * 8 + 255) / 256 * 256) : 0;
         v.workspace_bytes = s > 1 ? (int64_t)(im.counter_bytes + (size_t)s * d.M * d.N * 4) : 0;
+        if (pass == 1) v.workspace_bytes = (int64_t)(((size_t)d.K * d.N * 2 + 255) / 256 * 256);     // B^T
         char wk[8] = "";
         if (k.waves_k > 1) snprintf(wk, sizeof(wk), "x%d", k.waves_k);
-        snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d%s_s%d_%s_sk%d%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n,
-                 wk, k.stages, k.a_bypass_lds ? "areg" : (k.direct_to_lds ? "direct" : "regs"), s,
+        snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d%s_s%d_%s%s_sk%d%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n,
+                 wk, k.stages, k.a_bypass_lds ? "areg" : (k.direct_to_lds ? "direct" : "regs"),
+                 pass == 1 ? "_pretransB" : (k.trans_b ? "_bnk" : ""), s,
                  s > 1 ? (fused == 2 ? "l" : (fused ? "f" : "r")) : (kr ? "x" : ""));
         add_variant(p, v, im);
         }
@@ -308,7 +326,7 @@ void build_family(tf_problem* p) {
     }
   }
   // Streaming kernels for skinny problems: K in blocks of 32, each wave of a work-group at least one block.
-  if (d.M <= 32 && d.K % 32 == 0 && d.K >= 32) {
+  if (!tb && d.M <= 32 && d.K % 32 == 0 && d.K >= 32) {
     const tf::StreamKernelInfo* stab = tf::stream_kernel_table();
     const long kblocks = d.K / 32;
     for (int i = 0; i < tf::stream_kernel_count(); ++i) {
@@ -434,6 +452,7 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
     g.y_vec16 = ((uintptr_t)Y % 16 == 0) && ((size_t)d.ldy * esz % 16 == 0) &&
                 (d.op != TF_OP_BATCHED_GEMM_TN || (size_t)d.stride_y * esz % 16 == 0);
   }
+  g.trans_b = d.op == TF_OP_GEMM_EPILOGUE && d.trans_b;
   g.slice_major = v.split_k > 1 && v.fused_reduce == 0 && v.kind == TF_KIND_MFMA_LDS;
   g.k_rotate = v.k_rotate;
   g.epi = d.epi; g.split_k = v.split_k; g.fused_reduce = v.fused_reduce; g.group_m = v.group_m > 0 ? v.group_m : 1; g.xcd_swizzle = v.xcd_swizzle;
@@ -492,6 +511,29 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
     tf::launch_mfma_direct(g, stream);
   } else {
     g.tiles_m = im.tiles_m; g.tiles_n = im.tiles_n; g.ktiles_per_split = im.ktiles_per_split;
+    if (d.trans_b && v.kind == TF_KIND_MFMA_LDS && !v.trans_b) {
+      // B arrives as [N][K] and this kernel reads [K][N]: a separate pass writes B^T into the workspace first
+      if (!ws) {
+        if (p->own_ws_bytes < (size_t)v.workspace_bytes) {
+          if (p->own_ws) { (void)hipFree(p->own_ws); p->own_ws = nullptr; p->own_ws_bytes = 0; p->zeroed_ws = nullptr; p->zeroed_bytes = 0; }
+          size_t need = 0;
+          for (const tf_variant_desc& f : p->family) need = std::max(need, (size_t)f.workspace_bytes);
+          if (hipMalloc(&p->own_ws, need) != hipSuccess) {
+            p->own_ws = nullptr;
+            return fail(TF_E_NOMEM, "cannot allocate %zu bytes for the transposed operand", need);
+          }
+          p->own_ws_bytes = need;
+        }
+        ws = p->own_ws; ws_bytes = p->own_ws_bytes;
+      }
+      if (ws_bytes < (size_t)v.workspace_bytes)
+        return fail(TF_E_UNSUPPORTED, "workspace of %zu bytes, variant %s needs %lld", ws_bytes, v.name, (long long)v.workspace_bytes);
+      if ((uintptr_t)ws & 255u) return fail(TF_E_UNSUPPORTED, "workspace must be 256-byte aligned");
+      // B is [N][ldb]: N rows of K -> [K][N]
+      tf::launch_transpose(g.B, (uint16_t*)ws, d.N, d.K, d.ldb, 0, d.N, 0, 1, stream);
+      g.B = (const uint16_t*)ws; g.ldb = d.N;
+      if (p->zeroed_ws == ws) { p->zeroed_ws = nullptr; p->zeroed_bytes = 0; }     // the counter area of this buffer has been written over
+    }
     if (v.stream_k) {
       // two contributors per shared tile exchange partial tiles like two split-K slices, through memory
       g.stream_k = 1; g.split_k = 2; g.fused_reduce = 1; g.slice_major = 0;
@@ -690,7 +732,8 @@ tf_status gate_prepare(TuneCtx* c) {
     tf_status st = do_launch(p, 0, c->A, c->B, c->bias, c->yref, nullptr, 0, c->stream, TF_EPI_NONE_F32, d.N);
     if (st != TF_OK) return st;
     tf::launch_norms((const uint16_t*)c->A, 1, 0, d.M, d.lda, d.K, 1, c->norm_a, c->stream);
-    tf::launch_norms((const uint16_t*)c->B, 1, 0, d.N, 1, d.K, d.ldb, c->norm_b, c->stream);
+    if (d.trans_b) tf::launch_norms((const uint16_t*)c->B, 1, 0, d.N, d.ldb, d.K, 1, c->norm_b, c->stream);
+    else tf::launch_norms((const uint16_t*)c->B, 1, 0, d.N, 1, d.K, d.ldb, c->norm_b, c->stream);
   } else if (d.op == TF_OP_BATCHED_VECMAT) {
     TF_HIP(hipMemcpy2DAsync(c->yref, (size_t)d.N * 4, c->Y, (size_t)d.ldy * 4, (size_t)d.N * 4, (size_t)d.M, hipMemcpyDeviceToDevice, c->stream));
     tf::launch_norms((const uint16_t*)c->A, 1, 0, d.M, d.lda, d.K, 1, c->norm_a, c->stream);
@@ -997,7 +1040,8 @@ extern "C" tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem**
   }
   if (desc->op != TF_OP_GEMM_EPILOGUE && desc->op != TF_OP_BATCHED_VECMAT && desc->op != TF_OP_BATCHED_GEMM_TN) return fail(TF_E_INVALID, "unknown operation %d", desc->op);
   const bool vecmat = desc->op == TF_OP_BATCHED_VECMAT, bgemm = desc->op == TF_OP_BATCHED_GEMM_TN;
-  if (desc->lda < (bgemm ? desc->M : desc->K) || desc->ldb < (vecmat ? desc->K : desc->N) || desc->ldy < desc->N)
+  const bool nk = desc->op == TF_OP_GEMM_EPILOGUE && desc->trans_b != 0;     // B as [N][ldb]
+  if (desc->lda < (bgemm ? desc->M : desc->K) || desc->ldb < ((vecmat || nk) ? desc->K : desc->N) || desc->ldy < desc->N)
     return fail(TF_E_INVALID, "leading dimension smaller than the row length");
   if ((vecmat || bgemm) && desc->epi != TF_EPI_NONE_F32) return fail(TF_E_INVALID, "this operation writes fp32 (TF_EPI_NONE_F32)");
   if (bgemm) {
@@ -1010,6 +1054,7 @@ extern "C" tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem**
   tf_problem* p = new (std::nothrow) tf_problem();
   if (!p) return fail(TF_E_NOMEM, "out of host memory");
   p->desc = *desc;
+  p->desc.trans_b = nk ? 1 : 0;
   p->own_ws = nullptr; p->own_ws_bytes = 0; p->zeroed_ws = nullptr; p->zeroed_bytes = 0;
   // H: from the device when there is one, otherwise the published figures (enumeration and the
   // host-side loop logic work without a GPU; launching does not)
@@ -1264,6 +1309,7 @@ extern "C" tf_status tf_tune(tf_problem* p, const void* A, const void* B, const 
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     size_t araw = ((size_t)(d.M - 1) * d.lda + d.K) * 2;
     size_t braw = d.op == TF_OP_BATCHED_VECMAT ? (((size_t)d.M * d.N - 1) * d.ldb + d.K) * 2
+                  : (d.op == TF_OP_GEMM_EPILOGUE && d.trans_b) ? ((size_t)(d.N - 1) * d.ldb + d.K) * 2
                                                : ((size_t)(d.K - 1) * d.ldb + d.N) * 2;
     if (d.op == TF_OP_ELEMENTWISE_SIN) { araw = (size_t)d.N * 4; braw = 0; }
     if (d.op == TF_OP_BATCHED_GEMM_TN) {

@@ -1,14 +1,15 @@
 // LDS-staged bf16 MFMA GEMM with fused bias + GELU(erf) epilogue for gfx950.
 //
 // One work-group computes one BM x BN tile of Y (or one K slice of it). Per K step of
-// BK = 64 it stages an A tile [BM][64] and a B tile [64][BN] in LDS, multi-buffered, and
-// each of the WM x WN waves accumulates a (BM/WM) x (BN/WN) sub-tile with
+// BK (32, 64 or 128) it stages an A tile [BM][BK] and a B tile [BK][BN] in LDS, multi-buffered,
+// and each of the WM x WN waves accumulates a (BM/WM) x (BN/WN) sub-tile with
 // v_mfma_f32_32x32x16_bf16 in fp32.
 //
 // LDS layouts (chosen from measured bank behaviour: 64 banks x 4 B, b128 reads are
 // conflict free when 16 consecutive lanes cover 16 distinct 16-byte slots of a 256-byte line):
-//   A tile: row-major, 128 B per row, eight 16-byte chunks per row; chunk c of row r is
-//           stored in slot c ^ ((r >> 1) & 7). MFMA A operands are ds_read_b128.
+//   A tile: row-major, 2 BK bytes per row, BK / 8 16-byte chunks per row; chunk c of row r is
+//           stored in slot c ^ f(r), f(r) = (r / rows per 256-byte line) mod chunks per row
+//           (BK = 64: c ^ ((r >> 1) & 7)). MFMA A operands are ds_read_b128.
 //   B tile: row-major as in memory ([k][n], n contiguous), BN*2 bytes per row, split in
 //           64-byte pieces; piece j of row k is stored in slot j ^ f(k) so that four
 //           consecutive k rows fall in four different bank groups. MFMA B operands, which
@@ -22,7 +23,8 @@
 
 namespace tf {
 
-template <int BM_, int BN_, int WM_, int WN_, int STAGES_, bool DIRECT_, bool ABYPASS_ = false, int WK_ = 1, bool TRANSA_ = false>
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int STAGES_, bool DIRECT_, bool ABYPASS_ = false, int WK_ = 1, bool TRANSA_ = false,
+          bool TRANSB_ = false>
 struct LdsCfg {
   // TRANSA: A is given transposed, [K][lda] with m contiguous (the dO^T A product of the paper's
   // Case Study 3). Its tile is then staged exactly like the B tile, [64][BM] row-major with the
@@ -31,13 +33,21 @@ struct LdsCfg {
   // separate pass.
   static constexpr bool TRANSA = TRANSA_;
   static constexpr int A_ROW_BYTES = BM_ * 2, A_PIECES = A_ROW_BYTES / 64, A_ROWS_PER_INSTR = 1024 / A_ROW_BYTES;
-  static constexpr int BM = BM_, BN = BN_, BK = 64, WM = WM_, WN = WN_, STAGES = STAGES_;
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, STAGES = STAGES_;
+  static_assert(BK == 32 || BK == 64 || BK == 128, "K tile of 32, 64 or 128");
+  // TRANSB: B is given as [N][ldb] with k contiguous (weights stored output-major). Its tile is then staged
+  // exactly like the A tile, [BN][BK] with the same chunk swizzle, and its MFMA operands are ds_read_b128.
+  static constexpr bool TRANSB = TRANSB_;
+  // A tile rows (and B tile rows under TRANSB): BK / 8 chunks of 16 bytes; slot = chunk ^ row_swz(row)
+  static constexpr int K_ROW_BYTES = BK * 2, K_CHUNKS = BK / 8, K_ROWS_PER_LINE = 16 / K_CHUNKS, K_ROWS_PER_INSTR = 64 / K_CHUNKS;
+  static constexpr int KSTEPS = BK / 16;                   // 16-wide MFMA steps per K tile
   // WK: wave groups along k. With WK = 2 a second set of WM x WN waves works on the same
   // BM x BN tile but takes the other half of every 64-wide K step; the two sets add their
   // accumulators through LDS after the main loop. Eight waves then keep the LDS busier than
   // four can (a wave issues one LDS instruction every twenty-odd cycles) without the extra
   // fragment reads that a finer split of the tile along m or n costs.
-  static constexpr int WK = WK_, KS = 4 / WK_;             // k16-steps per wave per K step
+  static constexpr int WK = WK_, KS = KSTEPS / WK_;        // k16-steps per wave per K step
+  static_assert(KS >= 2 && KS % 2 == 0, "the pipeline alternates two fragment sets per k16-step");
   static constexpr bool DIRECT = DIRECT_;
   // ABYPASS: the A operand never enters LDS. Each wave loads its own A fragments from memory
   // straight into registers (WN must be 1, so no two waves need the same A rows) and only B is
@@ -47,7 +57,9 @@ struct LdsCfg {
   static constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
   static constexpr int TM = WTM / 32, TN = WTN / 32;       // 32x32 MFMA blocks per wave
   static constexpr int A_BYTES = ABYPASS ? 0 : BM * BK * 2, B_BYTES = BK * BN * 2;
-  static_assert(!ABYPASS || (WN == 1 && DIRECT && STAGES == 2 && WK_ == 1), "A bypass: one wave column, direct B staging, two buffers");
+  static_assert(!ABYPASS || (WN == 1 && DIRECT && STAGES == 2 && WK_ == 1 && BK == 64 && !TRANSB_), "A bypass: one wave column, direct B staging, two buffers, K tile of 64");
+  static_assert(DIRECT || (BK == 64 && !TRANSB_), "register staging: K tile of 64, B row-major");
+  static_assert(!TRANSB_ || !TRANSA_, "one transposed operand at a time");
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int RING_BYTES = STAGES * STAGE_BYTES;
   // behind the ring: this tile's BN bias values, fetched at kernel start so that the epilogue
@@ -57,7 +69,7 @@ struct LdsCfg {
   static constexpr int A_INSTR = A_BYTES / 1024;           // wave-wide 1 KB transfers per tile
   static constexpr int B_INSTR = B_BYTES / 1024;
   static constexpr int A_PER_WAVE = A_INSTR / NWAVES, B_PER_WAVE = B_INSTR / NWAVES;
-  static constexpr int B_ROW_BYTES = BN * 2;
+  static constexpr int B_ROW_BYTES = TRANSB ? K_ROW_BYTES : BN * 2;
   static constexpr int B_ROWS_PER_INSTR = 1024 / B_ROW_BYTES;
   static constexpr int B_SLOTS_PER_ROW = B_ROW_BYTES / 16;  // 16-byte slots per B row
   static constexpr int B_PIECES = B_ROW_BYTES / 64;         // 64-byte pieces per B row
@@ -84,6 +96,8 @@ struct LdsCfg {
   // 32-row tiles serve problems of few rows, where every B element is read by one work-group only: its
   // loads are marked non-temporal
   static constexpr bool B_NT = BM <= 32;
+  // slot permutation of the 16-byte chunks of a k-contiguous tile row (see the file header)
+  __device__ __forceinline__ static constexpr int row_swz(int r) { return (r / K_ROWS_PER_LINE) & (K_CHUNKS - 1); }
 };
 
 // Slot permutation of the 64-byte pieces of B row k (see header).
@@ -123,9 +137,9 @@ struct TileLoader {
         a_src[q] = ((unsigned)krow * (unsigned)p.lda + (unsigned)m) * 2u;
         a_k[q] = krow;
       } else {
-        const int row = 8 * ia + (lane >> 3);
-        const int slot = lane & 7;
-        const int c = slot ^ ((row >> 1) & 7);
+        const int row = C::K_ROWS_PER_INSTR * ia + lane / C::K_CHUNKS;
+        const int slot = lane % C::K_CHUNKS;
+        const int c = slot ^ C::row_swz(row);
         int m = m0 + row;
         a_ok[q] = m < p.M;
         if (m >= p.M) m = p.M - 1;
@@ -136,15 +150,27 @@ struct TileLoader {
 #pragma unroll
     for (int q = 0; q < C::B_PER_WAVE; ++q) {
       const int ib = wave + C::NWAVES * q;
-      constexpr int LPR = 64 / C::B_ROWS_PER_INSTR;          // lanes per row
-      const int krow = C::B_ROWS_PER_INSTR * ib + lane / LPR;
-      const int s16 = lane % LPR;
-      const int piece = (s16 >> 2) ^ b_swz<C::B_PIECES>(krow);
-      int n = n0 + 32 * piece + 8 * (s16 & 3);
-      b_ok[q] = n < p.N;
-      if (n >= p.N) n = 0;
-      b_src[q] = ((unsigned)krow * (unsigned)p.ldb + (unsigned)n) * 2u;
-      b_k[q] = krow;
+      if constexpr (C::TRANSB) {
+        // rows of the tile are n, columns k: the scheme of the A tile with n in place of m
+        const int row = C::K_ROWS_PER_INSTR * ib + lane / C::K_CHUNKS;
+        const int slot = lane % C::K_CHUNKS;
+        const int c = slot ^ C::row_swz(row);
+        int n = n0 + row;
+        b_ok[q] = n < p.N;
+        if (n >= p.N) n = p.N - 1;
+        b_src[q] = ((unsigned)n * (unsigned)p.ldb + 8u * c) * 2u;
+        b_k[q] = 8 * c;
+      } else {
+        constexpr int LPR = 64 / C::B_ROWS_PER_INSTR;          // lanes per row
+        const int krow = C::B_ROWS_PER_INSTR * ib + lane / LPR;
+        const int s16 = lane % LPR;
+        const int piece = (s16 >> 2) ^ b_swz<C::B_PIECES>(krow);
+        int n = n0 + 32 * piece + 8 * (s16 & 3);
+        b_ok[q] = n < p.N;
+        if (n >= p.N) n = 0;
+        b_src[q] = ((unsigned)krow * (unsigned)p.ldb + (unsigned)n) * 2u;
+        b_k[q] = krow;
+      }
     }
   }
 
@@ -545,13 +571,22 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   const int nkt = kt_end - kt_begin;   // may be <= 0 for a trailing empty slice: contributes zeros
 
   // ---- LDS read offsets of this lane (bytes inside a stage)
-  int a_off[4];
+  int a_off[C::KS];
   {
     const int r = wave_m * C::WTM + (lane & 31);
     const int g = lane >> 5;
-    const int sw = (r >> 1) & 7;
+    const int sw = C::row_swz(r);          // (the same for the rows 32, 64, ... further down)
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) a_off[kk] = r * 128 + ((((2 * (wave_k * C::KS + kk) + g) & 7) ^ sw) << 4);   // kk < KS used
+    for (int kk = 0; kk < C::KS; ++kk) a_off[kk] = r * C::K_ROW_BYTES + (((2 * (wave_k * C::KS + kk) + g) ^ sw) << 4);
+  }
+  // B given as [N][K]: its tile is read like the A tile. Its offsets are derived per read from two values (the
+  // chunk index 2 k + g only differs from g above bit 0, so the swizzled slot of step k is (g ^ sw) ^ 2 k):
+  // a table per k16-step as for A costs registers the big tiles do not have.
+  int bt_row = 0, bt_c0 = 0;
+  if constexpr (C::TRANSB) {
+    const int r = wave_n * C::WTN + (lane & 31);
+    bt_row = C::A_BYTES + r * C::K_ROW_BYTES;
+    bt_c0 = ((lane >> 5) ^ C::row_swz(r)) << 4;
   }
   int a_toff[C::TRANSA ? C::TM : 1];     // transposed A: offsets for the transposing read, as for B
   if constexpr (C::TRANSA) {
@@ -574,7 +609,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       return __builtin_bit_cast(bf16x8, v);
     } else {
-      return *(const bf16x8*)(stage + a_off[kk] + i * 32 * 128);
+      return *(const bf16x8*)(stage + a_off[kk] + i * 32 * C::K_ROW_BYTES);
     }
   };
   int b_off[C::TN];
@@ -589,6 +624,18 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       b_off[t] = C::A_BYTES + (krow + wave_k * C::KS * 16) * C::B_ROW_BYTES + piece * 64 + within;
     }
   }
+  // one B operand of k16-step kk (relative to the wave's first step), column block t
+  auto read_b1 = [&](const char* stage, int kk, int t) -> bf16x8 {
+    if constexpr (C::TRANSB) {
+      return *(const bf16x8*)(stage + bt_row + (bt_c0 ^ ((wave_k * C::KS + kk) << 5)) + t * 32 * C::K_ROW_BYTES);
+    } else {
+      const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + 4 * C::B_ROW_BYTES));
+      const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, v);
+    }
+  };
 
   f32x16 acc[C::TM][C::TN];
 #pragma unroll
@@ -623,8 +670,8 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   }
   const long a_step = C::TRANSA ? (long)C::BK * p.lda : (long)C::BK;     // one K tile further in A
   const uint16_t* Ak = p.A + (long)kt_begin * a_step;
-  const uint16_t* Bk = p.B + (long)kt_begin * C::BK * p.ldb;
-  const long b_step = (long)C::BK * p.ldb;
+  const long b_step = C::TRANSB ? (long)C::BK : (long)C::BK * p.ldb;      // one K tile further in B
+  const uint16_t* Bk = p.B + (long)kt_begin * b_step;
 
   // ---- main loop, software pipelined by hand (one wave per SIMD has nobody to hide behind):
   //  * fragments are double buffered in registers: the LDS reads of k16-step kk+1 are issued
@@ -638,13 +685,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     for (int i = 0; i < C::TM; ++i)
       af[set][i] = read_a(stage, kk, i);
 #pragma unroll
-    for (int t = 0; t < C::TN; ++t) {
-      const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + 4 * C::B_ROW_BYTES));
-      const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-      bfr[set][t] = __builtin_bit_cast(bf16x8, v);
-    }
+    for (int t = 0; t < C::TN; ++t) bfr[set][t] = read_b1(stage, kk, t);
   };
   auto mfma_step = [&](int set) {
 #pragma unroll
@@ -655,7 +696,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   };
   // scheduling hint for one pipelined step: alternate one MFMA with one LDS read until the
   // reads are all issued, so that the matrix pipe never waits for the whole batch of reads
-  constexpr int N_DS = C::TM + 2 * C::TN, N_MFMA = C::TM * C::TN;
+  constexpr int N_DS = C::TM + (C::TRANSB ? 1 : 2) * C::TN, N_MFMA = C::TM * C::TN;
   auto interleave_hint = [&]() {
 #pragma unroll
     for (int x = 0; x < (N_DS < N_MFMA ? N_DS : N_MFMA); ++x) {
@@ -791,13 +832,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
 #pragma unroll
         for (int i = 0; i < C::TM; ++i) a[kk][i] = read_a(stage, kk, i);
 #pragma unroll
-        for (int t = 0; t < C::TN; ++t) {
-          const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + 4 * C::B_ROW_BYTES));
-          const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-          b[kk][t] = __builtin_bit_cast(bf16x8, v);
-        }
+        for (int t = 0; t < C::TN; ++t) b[kk][t] = read_b1(stage, kk, t);
       }
     };
     auto mfma_tile = [&](const bf16x8 (&a)[C::KS][C::TM], const bf16x8 (&b)[C::KS][C::TN]) {
@@ -862,14 +897,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
 #pragma unroll
       for (int x = 0; x < (NR > 8 ? NR : 8); ++x) {
         if (x < C::TM) af[set][x] = read_a(stage, kk, x);
-        else if (x < NR) {
-          const int t = x - C::TM;
-          const char* bp = stage + b_off[t] + (16 * kk) * C::B_ROW_BYTES;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + 4 * C::B_ROW_BYTES));
-          const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-          bfr[set][t] = __builtin_bit_cast(bf16x8, v);
-        }
+        else if (x < NR) bfr[set][x - C::TM] = read_b1(stage, kk, x - C::TM);
         if (x < nx) {
           if (which == 1) ld.issue_a_one(x, src, dst_lds, wave);
           else ld.issue_b_one(x, src, dst_lds, wave);
@@ -896,7 +924,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
         mfma_step(0);
         interleave_hint();
 #pragma unroll
-        for (int kk = 1; kk < 3; ++kk) {
+        for (int kk = 1; kk < C::KS - 1; ++kk) {
           read_frags(cur, kk + 1, (kk + 1) & 1);
           mfma_step(kk & 1);
           interleave_hint();
@@ -904,7 +932,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
         wait_vmcnt<(D - 1) * PER_TILE>();    // tile kt+1 has landed
         barrier_lds();                       // ... for every wave, and every wave is done reading tile kt
         read_frags_issue(smem + nstage * C::STAGE_BYTES, 0, 0, 1, tile_a(kt + 1 + D), lds0 + stage * C::STAGE_BYTES);
-        mfma_step(1);                        // k16-step 3 of tile kt covers the latencies above
+        mfma_step(1);                        // the last k16-step of tile kt covers the latencies above
         interleave_hint();
         stage = nstage;
       }
@@ -917,7 +945,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
         mfma_step(0);
         interleave_hint();
 #pragma unroll
-        for (int kk = 1; kk < 3; ++kk) {
+        for (int kk = 1; kk < C::KS - 1; ++kk) {
           read_frags(cur, kk + 1, (kk + 1) & 1);
           mfma_step(kk & 1);
           interleave_hint();
@@ -946,7 +974,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
         const char* cur = smem + (kt & 1) * C::STAGE_BYTES;
         char* nxt = smem + ((kt + 1) & 1) * C::STAGE_BYTES;
 #pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
+        for (int kk = 0; kk < C::KS - 1; ++kk) {
           read_frags(cur, kk + 1, (kk + 1) & 1);
           mfma_step(kk & 1);
           interleave_hint();
@@ -960,7 +988,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
       {
         const char* cur = smem + (last & 1) * C::STAGE_BYTES;
 #pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
+        for (int kk = 0; kk < C::KS - 1; ++kk) {
           read_frags(cur, kk + 1, (kk + 1) & 1);
           mfma_step(kk & 1);
           interleave_hint();
@@ -1126,12 +1154,12 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
 //     half-size output passes (43 us against 39 us).
 template <class C>
 __global__ void __launch_bounds__(C::THREADS) tf_bgemm_persist_kernel(const GemmParams p) {
-  static_assert(C::TRANSA && C::DIRECT && C::WK == 1 && !C::ABYPASS && C::STAGES >= 3, "transposed staging, direct, three buffers or more");
+  static_assert(C::TRANSA && !C::TRANSB && C::DIRECT && C::WK == 1 && !C::ABYPASS && C::STAGES >= 3, "transposed staging, direct, three buffers or more");
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int D = C::STAGES - 1;
   // the loading half of the waves moves the tiles exactly as a work-group of half as many wave columns would
   static_assert(C::WN % 2 == 0, "an even number of wave columns");
-  using CL = LdsCfg<C::BM, C::BN, C::WM, C::WN / 2, C::STAGES, true, false, 1, true>;
+  using CL = LdsCfg<C::BM, C::BN, C::BK, C::WM, C::WN / 2, C::STAGES, true, false, 1, true>;
   constexpr int LW = CL::NWAVES, STORE_THREADS = C::THREADS - LW * 64;
   static_assert(CL::STAGE_BYTES == C::STAGE_BYTES && CL::A_BYTES == C::A_BYTES, "same ring layout");
   constexpr int PER_TILE = CL::A_PER_WAVE + CL::B_PER_WAVE;
@@ -1225,7 +1253,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_bgemm_persist_kernel(const Gemm
     issue_next();                  // step f + D into that buffer
     const char* cur = smem + c_stage * C::STAGE_BYTES;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int kk = 0; kk < C::KSTEPS; ++kk) {
       bf16x8 af[C::TM], bfr[C::TN];
 #pragma unroll
       for (int i = 0; i < C::TM; ++i) af[i] = read_tr(cur + a_toff[i] + (16 * kk) * C::A_ROW_BYTES, C::A_ROW_BYTES);
@@ -1298,6 +1326,7 @@ static LdsKernelInfo make_info() {
   LdsKernelInfo k;
   k.bm = C::BM; k.bn = C::BN; k.bk = C::BK; k.waves_m = C::WM; k.waves_n = C::WN; k.waves_k = C::WK;
   k.stages = C::STAGES; k.direct_to_lds = C::DIRECT ? 1 : 0; k.a_bypass_lds = C::ABYPASS ? 1 : 0; k.trans_a = C::TRANSA ? 1 : 0;
+  k.trans_b = C::TRANSB ? 1 : 0;
   k.threads = C::THREADS; k.lds_bytes = C::LDS_BYTES; k.fused_ok = C::FUSED_OK ? 1 : 0;
   k.persistent = 0; k.stream_k = C::SEGMENTS ? 1 : 0;
   k.func = (const void*)tf_gemm_lds_kernel<C>;
@@ -1315,43 +1344,66 @@ static LdsKernelInfo make_persist_info() {
   return k;
 }
 
-//                         BM   BN  WM WN ST  direct
-using K256x128_d2 = LdsCfg<256, 128, 2, 2, 2, true>;
-using K128x256_d2 = LdsCfg<128, 256, 2, 2, 2, true>;
-using K128x128_d2 = LdsCfg<128, 128, 2, 2, 2, true>;
-using K128x128_d3 = LdsCfg<128, 128, 2, 2, 3, true>;
-using K128x128_r2 = LdsCfg<128, 128, 2, 2, 2, false>;
-using K64x64_r2   = LdsCfg< 64,  64, 2, 2, 2, false>;
-using K64x64_d3   = LdsCfg< 64,  64, 2, 2, 3, true>;
-using K32x128_d3  = LdsCfg< 32, 128, 1, 4, 3, true>;
-using K32x64_d4   = LdsCfg< 32,  64, 1, 2, 4, true>;
-using K32x128_r2  = LdsCfg< 32, 128, 1, 4, 2, false>;
-using K32x128_d6  = LdsCfg< 32, 128, 1, 4, 6, true>;
-using K32x64_d8   = LdsCfg< 32,  64, 1, 2, 8, true>;
-using K32x256_d4  = LdsCfg< 32, 256, 1, 4, 4, true>;
-using K32x32_d4   = LdsCfg< 32,  32, 1, 1, 4, true>;
-using K32x32_d8   = LdsCfg< 32,  32, 1, 1, 8, true>;
-using K128x128_w8a = LdsCfg<128, 128, 2, 4, 3, true>;   // eight waves: two per SIMD cover each other's overheads
-using K128x128_w8b = LdsCfg<128, 128, 4, 2, 3, true>;
-using K128x128_w8c = LdsCfg<128, 128, 2, 4, 4, true>;
-using K128x256_ab = LdsCfg<128, 256, 4, 1, 2, true, true>;
-using K128x128_k2a = LdsCfg<128, 128, 2, 2, 3, true, false, 2>;   // two k groups of 2x2 waves
-using K128x128_k2b = LdsCfg<128, 128, 2, 2, 4, true, false, 2>;
+//                         BM   BN   BK  WM WN ST  direct
+using K256x128_d2 = LdsCfg<256, 128, 64, 2, 2, 2, true>;
+using K128x256_d2 = LdsCfg<128, 256, 64, 2, 2, 2, true>;
+using K128x128_d2 = LdsCfg<128, 128, 64, 2, 2, 2, true>;
+using K128x128_d3 = LdsCfg<128, 128, 64, 2, 2, 3, true>;
+using K128x128_r2 = LdsCfg<128, 128, 64, 2, 2, 2, false>;
+using K64x64_r2   = LdsCfg< 64,  64, 64, 2, 2, 2, false>;
+using K64x64_d3   = LdsCfg< 64,  64, 64, 2, 2, 3, true>;
+using K32x128_d3  = LdsCfg< 32, 128, 64, 1, 4, 3, true>;
+using K32x64_d4   = LdsCfg< 32,  64, 64, 1, 2, 4, true>;
+using K32x128_r2  = LdsCfg< 32, 128, 64, 1, 4, 2, false>;
+using K32x128_d6  = LdsCfg< 32, 128, 64, 1, 4, 6, true>;
+using K32x64_d8   = LdsCfg< 32,  64, 64, 1, 2, 8, true>;
+using K32x256_d4  = LdsCfg< 32, 256, 64, 1, 4, 4, true>;
+using K32x32_d4   = LdsCfg< 32,  32, 64, 1, 1, 4, true>;
+using K32x32_d8   = LdsCfg< 32,  32, 64, 1, 1, 8, true>;
+using K128x128_w8a = LdsCfg<128, 128, 64, 2, 4, 3, true>;   // eight waves: two per SIMD cover each other's overheads
+using K128x128_w8b = LdsCfg<128, 128, 64, 4, 2, 3, true>;
+using K128x128_w8c = LdsCfg<128, 128, 64, 2, 4, 4, true>;
+using K128x256_ab = LdsCfg<128, 256, 64, 4, 1, 2, true, true>;
+using K128x128_k2a = LdsCfg<128, 128, 64, 2, 2, 3, true, false, 2>;   // two k groups of 2x2 waves
+using K128x128_k2b = LdsCfg<128, 128, 64, 2, 2, 4, true, false, 2>;
 // first operand transposed in memory ([K][M])
-using T128x128_w8  = LdsCfg<128, 128, 2, 4, 3, true, false, 1, true>;
-using T128x128_d3  = LdsCfg<128, 128, 2, 2, 3, true, false, 1, true>;
-using T128x128_d2  = LdsCfg<128, 128, 2, 2, 2, true, false, 1, true>;
-using T256x256_w8  = LdsCfg<256, 256, 4, 2, 2, true, false, 1, true>;
-using T256x128_d2  = LdsCfg<256, 128, 2, 2, 2, true, false, 1, true>;
-using T64x64_d3    = LdsCfg< 64,  64, 2, 2, 3, true, false, 1, true>;
+using T128x128_w8  = LdsCfg<128, 128, 64, 2, 4, 3, true, false, 1, true>;
+using T128x128_d3  = LdsCfg<128, 128, 64, 2, 2, 3, true, false, 1, true>;
+using T128x128_d2  = LdsCfg<128, 128, 64, 2, 2, 2, true, false, 1, true>;
+using T256x256_w8  = LdsCfg<256, 256, 64, 4, 2, 2, true, false, 1, true>;
+using T256x128_d2  = LdsCfg<256, 128, 64, 2, 2, 2, true, false, 1, true>;
+using T64x64_d3    = LdsCfg< 64,  64, 64, 2, 2, 3, true, false, 1, true>;
 // two buffers only: short K (a chunk) means few K steps per tile, and several work-groups per CU
 // cover each other's start-up better than a deeper ring in one
-using T128x128_w8s2 = LdsCfg<128, 128, 2, 4, 2, true, false, 1, true>;
-using T128x64_d2   = LdsCfg<128,  64, 2, 2, 2, true, false, 1, true>;
-using T64x128_d2   = LdsCfg< 64, 128, 2, 2, 2, true, false, 1, true>;
-using T64x64_d2    = LdsCfg< 64,  64, 2, 2, 2, true, false, 1, true>;
-using K256x256_w8a = LdsCfg<256, 256, 2, 4, 2, true>;   // eight waves on the big tile: 128x64 or 64x128 per wave
-using K256x256_w8b = LdsCfg<256, 256, 4, 2, 2, true>;
+using T128x128_w8s2 = LdsCfg<128, 128, 64, 2, 4, 2, true, false, 1, true>;
+using T128x64_d2   = LdsCfg<128,  64, 64, 2, 2, 2, true, false, 1, true>;
+using T64x128_d2   = LdsCfg< 64, 128, 64, 2, 2, 2, true, false, 1, true>;
+using T64x64_d2    = LdsCfg< 64,  64, 64, 2, 2, 2, true, false, 1, true>;
+using K256x256_w8a = LdsCfg<256, 256, 64, 2, 4, 2, true>;   // eight waves on the big tile: 128x64 or 64x128 per wave
+using K256x256_w8b = LdsCfg<256, 256, 64, 4, 2, 2, true>;
+// other K tiles. 128 wide: half as many hand-over barriers per K and 256-byte row pieces from memory, two buffers of
+// 64 KB; 32 wide: four buffers of 32 KB behind the big tile, three K tiles in flight instead of one
+using K128x128x128_w8a = LdsCfg<128, 128, 128, 2, 4, 2, true>;
+using K128x128x128_w8b = LdsCfg<128, 128, 128, 4, 2, 2, true>;
+using K128x128x128_k2  = LdsCfg<128, 128, 128, 2, 2, 2, true, false, 2>;
+using K256x256x32_w8a  = LdsCfg<256, 256,  32, 2, 4, 4, true>;
+using K256x256x32_w8b  = LdsCfg<256, 256,  32, 4, 2, 4, true>;
+using K64x64x128_d3    = LdsCfg< 64,  64, 128, 2, 2, 3, true>;
+using K32x64x128_d4    = LdsCfg< 32,  64, 128, 1, 2, 4, true>;
+// eight waves of 64 x 64 on the rectangular tiles, three buffers of 48 KB
+using K256x128_w8 = LdsCfg<256, 128, 64, 4, 2, 3, true>;
+using K128x256_w8 = LdsCfg<128, 256, 64, 2, 4, 3, true>;
+// second operand given as [N][K], k contiguous: staged and read like the A tile
+using N256x256_w8a = LdsCfg<256, 256, 64, 2, 4, 2, true, false, 1, false, true>;
+using N256x256_w8b = LdsCfg<256, 256, 64, 4, 2, 2, true, false, 1, false, true>;
+using N128x128_w8a = LdsCfg<128, 128, 64, 2, 4, 3, true, false, 1, false, true>;
+using N128x128_w8b = LdsCfg<128, 128, 64, 4, 2, 3, true, false, 1, false, true>;
+using N128x128_d2  = LdsCfg<128, 128, 64, 2, 2, 2, true, false, 1, false, true>;
+using N128x128x128 = LdsCfg<128, 128, 128, 2, 4, 2, true, false, 1, false, true>;
+using N64x64_d3    = LdsCfg< 64,  64, 64, 2, 2, 3, true, false, 1, false, true>;
+using N32x64_d4    = LdsCfg< 32,  64, 64, 1, 2, 4, true, false, 1, false, true>;
+using N32x128_d3   = LdsCfg< 32, 128, 64, 1, 4, 3, true, false, 1, false, true>;
+using N32x32_d4    = LdsCfg< 32,  32, 64, 1, 1, 4, true, false, 1, false, true>;
 
 static LdsKernelInfo g_table[] = {
     make_info<K256x128_d2>(), make_info<K128x256_d2>(),
@@ -1368,6 +1420,12 @@ static LdsKernelInfo g_table[] = {
     make_info<K256x256_w8a>(), make_info<K256x256_w8b>(),
     make_persist_info<T128x128_w8>(), make_persist_info<T128x128_d3>(),
     make_info<StreamKCfg<K128x128_w8a>>(), make_info<StreamKCfg<K128x128_w8b>>(), make_info<StreamKCfg<K128x128_k2a>>(),
+    make_info<K128x128x128_w8a>(), make_info<K128x128x128_w8b>(), make_info<K128x128x128_k2>(),
+    make_info<K256x256x32_w8a>(), make_info<K256x256x32_w8b>(), make_info<K64x64x128_d3>(), make_info<K32x64x128_d4>(),
+    make_info<K256x128_w8>(), make_info<K128x256_w8>(),
+    make_info<N256x256_w8a>(), make_info<N256x256_w8b>(), make_info<N128x128_w8a>(), make_info<N128x128_w8b>(),
+    make_info<N128x128_d2>(), make_info<N128x128x128>(), make_info<N64x64_d3>(), make_info<N32x64_d4>(),
+    make_info<N32x128_d3>(), make_info<N32x32_d4>(),
 };
 
 int lds_kernel_count() { return (int)(sizeof(g_table) / sizeof(g_table[0])); }

@@ -14,10 +14,12 @@ __global__ void __launch_bounds__(256) tf_gemm_naive_kernel(const GemmParams p) 
   const int m = blockIdx.y * 4 + (threadIdx.x >> 6);
   if (m >= p.M || n >= p.N) return;
   const uint16_t* a = p.A + (size_t)m * p.lda;
-  const uint16_t* b = p.B + n;
+  // B as [K][ldb] (consecutive k are ldb apart) or, trans_b, as [N][ldb] (k contiguous)
+  const uint16_t* b = p.trans_b ? p.B + (size_t)n * p.ldb : p.B + n;
+  const size_t bstep = p.trans_b ? 1 : (size_t)p.ldb;
   float acc = 0.0f;
   for (int k = 0; k < p.K; ++k)
-    acc = __builtin_fmaf(bf16_bits_to_f32(a[k]), bf16_bits_to_f32(b[(size_t)k * p.ldb]), acc);
+    acc = __builtin_fmaf(bf16_bits_to_f32(a[k]), bf16_bits_to_f32(b[(size_t)k * bstep]), acc);
   const float z = acc + bf16_bits_to_f32(p.bias[n]);
   if (p.epi == TF_EPI_NONE_F32) ((float*)p.Y)[(size_t)m * p.ldy + n] = z;
   else ((uint16_t*)p.Y)[(size_t)m * p.ldy + n] = f32_to_bf16_bits(activate(z, p.epi));
@@ -40,7 +42,7 @@ __global__ void __launch_bounds__(64) tf_gemm_mfma_direct_kernel(const GemmParam
       const int k = k0 + 8 * g + e;
       const bool kin = k < p.K;
       av[e] = (kin && am < p.M) ? (short)p.A[(size_t)am * p.lda + k] : (short)0;
-      bv[e] = (kin && bn < p.N) ? (short)p.B[(size_t)k * p.ldb + bn] : (short)0;
+      bv[e] = (kin && bn < p.N) ? (short)p.B[p.trans_b ? (size_t)bn * p.ldb + k : (size_t)k * p.ldb + bn] : (short)0;
     }
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
   }

@@ -34,12 +34,14 @@ struct GemmParams {
   int batch_xcd;          // batched problems: 1 = all tiles of a batch item on one XCD (batch a multiple of 8)
   int ws_vec16;           // 1: the split-K workspace starts on a 16-byte boundary (its rows of N floats then do too)
   int y_vec16;            // 1: every row of Y (of every batch item) starts on a 16-byte boundary
+  int trans_b;            // 1: B is [N][ldb] with k contiguous (the unstaged kernels read it that way; tile kernels are compiled for one layout)
 };
 
 // One compiled kernel of the LDS-staged MFMA family.
 struct LdsKernelInfo {
   int bm, bn, bk, waves_m, waves_n, waves_k, stages, direct_to_lds, a_bypass_lds;
   int trans_a;            // 1: A is [K][lda] with m contiguous (staged and read like the B tile)
+  int trans_b;            // 1: B is [N][ldb] with k contiguous (staged and read like the A tile)
   int threads, lds_bytes;
   int fused_ok;           // 1: the kernel contains the in-kernel split-K reduction (fused_reduce 1 and 2)
   int stream_k;           // 1: instance with the loop over (tile, K range) segments compiled in (stream-K variants only)

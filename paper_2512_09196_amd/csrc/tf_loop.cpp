@@ -195,7 +195,9 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   }
   const int resident = tf_resident_wgs(hw, v);
   const long slots = (long)hw->cus * resident;
-  const long ktiles = cdiv(cdiv(pr->K, 64), v->split_k);
+  const int bk = v->bk > 0 ? v->bk : 64;
+  const double kr = bk / 64.0;                      // the figures below are per 64 of K: a tile of bk is kr of them
+  const long ktiles = cdiv(cdiv(pr->K, bk), v->split_k);
   const int mn_waves = v->waves_m * v->waves_n, wg_waves = mn_waves * (v->waves_k > 1 ? v->waves_k : 1);
   // Cycles one CU spends on one K tile (64 wide) of one work-group. The constants are fits to
   // this family's measured times on MI355X (2048^3, 4096 x 11008 x 4096 and 1024^2 x 16384):
@@ -207,20 +209,27 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   //  * per K step a chain of barrier, transfer issue, first fragment reads and first MFMA is
   //    exposed: about 800 cycles with two buffers, 250 with three or more, and a second wave per
   //    SIMD hides 70 % of it; register staging adds 300, the A-bypass loads 400.
-  const double mfma = v->bm * (double)v->bn / 32.0 * (36.0 / 32.0);
-  const double stage_bytes = (v->a_bypass_lds ? v->bn : v->bm + v->bn) * 128.0;
+  const double mfma = kr * v->bm * (double)v->bn / 32.0 * (36.0 / 32.0);
+  const double stage_bytes = kr * (v->a_bypass_lds ? v->bn : v->bm + v->bn) * 128.0;
   const double lds_w = stage_bytes / 85.0;
   long co_resident = cdiv(v->grid, hw->cus);       // work-groups really sharing a CU, not how many would fit
   if (co_resident > resident) co_resident = resident;
   const double cu_waves = (double)wg_waves * co_resident;
   const double a_rows = v->a_bypass_lds ? 0.0 : (double)(v->bm / v->waves_m);
-  const double lds_r = mn_waves * (a_rows + (v->bn / v->waves_n)) * 128.0 / 256.0;
-  const double ta = (v->bm + v->bn) * 128.0 / 85.0;              // global -> CU
+  const double lds_r = kr * mn_waves * (a_rows + (v->bn / v->waves_n)) * 128.0 / 256.0;
+  const double ta = kr * (v->bm + v->bn) * 128.0 / 85.0;         // global -> CU
   double chain = v->stages >= 3 ? 250.0 : 800.0;
   if (cu_waves >= 8) chain *= v->waves_k > 1 ? 0.7 : 0.3;       // k groups: half the MFMAs per wave and step to hide it behind
+  // a K tile of 32 has only two 16-wide steps of MFMAs between two hand-overs to hide the chain behind (measured:
+  // 256 x 256 x 32 with four buffers is 5 % slower than 256 x 256 x 64 with two)
+  if (bk < 64) chain *= 64.0 / bk * 2.0;
   if (!v->direct_to_lds) chain += 300.0;
   if (v->a_bypass_lds) chain += 400.0;
-  double ktile = fmax(fmax(mfma, lds_w + lds_r), ta) + chain;
+  // the tile transfers are never fully hidden behind the matrix pipes: they share the LDS port with the fragment
+  // reads and the L2 with the other CUs, and most of their time shows (measured: the 256 x 128 and 128 x 256
+  // tiles, whose other figures match the 256 x 256 tile's, need 12-15 % more time per flop; they move 1.5 times
+  // the bytes per flop)
+  double ktile = fmax(fmax(mfma, lds_w + lds_r), ta) + chain + 0.7 * ta;
   // the in-kernel reductions keep the slices of a tile side by side, so the work-groups of an XCD work on
   // different K ranges and share fewer operand panels in its L2 than in the slice-by-slice order of the
   // two-kernel reduction (measured: about a quarter more time per K step)
@@ -275,7 +284,10 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   // K order rotated by XCD: measured 2-4 % faster on 2048^3, between equal and 10 % faster on
   // 4096 x 11008 x 4096 depending on the kernel and the chip: proposed first, the plain order right behind
   const double rot = v->k_rotate ? 0.98 : 1.0;
-  return fmax(us * rot, (hbm_us + ws_us) / (0.75 * inflight)) + 4.0 + reduce_us + fused_tail_us;
+  // B given as [N][K] behind a separate transposing pass: one more launch that reads and writes all of B
+  const double pretrans_us = (pr->op == TF_OP_GEMM_EPILOGUE && pr->trans_b && !v->trans_b)
+                                 ? 3.0 + 4.0 * (double)pr->K * pr->N / (0.6 * hw->hbm_gbs_peak * 1e3) : 0.0;
+  return fmax(us * rot, (hbm_us + ws_us) / (0.75 * inflight)) + 4.0 + reduce_us + fused_tail_us + pretrans_us;
 }
 
 // ------------------------------------------------------------------ Proposal
@@ -294,8 +306,8 @@ static bool matches_hint(int bn, const tf_hw* hw, const tf_variant_desc* b, cons
       return v->direct_to_lds != b->direct_to_lds || v->bn != b->bn;
     case TF_BN_OCCUPANCY:     // fewer registers / less LDS per work-group
       return area_v < area_b || (area_v == area_b && v->lds_bytes < b->lds_bytes);
-    case TF_BN_LATENCY:       // deeper staging, or bigger tiles to amortise it
-      return v->stages > b->stages || (v->direct_to_lds && !b->direct_to_lds) || area_v > area_b;
+    case TF_BN_LATENCY:       // deeper staging (more buffers, or a longer K tile: fewer hand-overs), or bigger tiles to amortise it
+      return v->stages > b->stages || v->bk > b->bk || (v->direct_to_lds && !b->direct_to_lds) || area_v > area_b;
     default:
       return true;
   }

@@ -36,13 +36,13 @@ class ProblemDesc(_Struct):
     _fields_ = [("M", C.c_int32), ("N", C.c_int32), ("K", C.c_int32),
                 ("lda", C.c_int64), ("ldb", C.c_int64), ("ldy", C.c_int64),
                 ("epi", C.c_int32), ("device", C.c_int32), ("op", C.c_int32), ("batch", C.c_int32),
-                ("stride_a", C.c_int64), ("stride_b", C.c_int64), ("stride_y", C.c_int64)]
+                ("stride_a", C.c_int64), ("stride_b", C.c_int64), ("stride_y", C.c_int64), ("trans_b", C.c_int32)]
 
 
 class VariantDesc(_Struct):
     _fields_ = [("id", C.c_int32), ("kind", C.c_int32), ("bm", C.c_int32), ("bn", C.c_int32), ("bk", C.c_int32),
                 ("waves_m", C.c_int32), ("waves_n", C.c_int32), ("waves_k", C.c_int32), ("stages", C.c_int32), ("split_k", C.c_int32), ("fused_reduce", C.c_int32),
-                ("direct_to_lds", C.c_int32), ("a_bypass_lds", C.c_int32), ("trans_a", C.c_int32), ("stream_k", C.c_int32), ("k_rotate", C.c_int32), ("persistent", C.c_int32), ("nontemporal", C.c_int32), ("xcd_swizzle", C.c_int32), ("group_m", C.c_int32),
+                ("direct_to_lds", C.c_int32), ("a_bypass_lds", C.c_int32), ("trans_a", C.c_int32), ("trans_b", C.c_int32), ("stream_k", C.c_int32), ("k_rotate", C.c_int32), ("persistent", C.c_int32), ("nontemporal", C.c_int32), ("xcd_swizzle", C.c_int32), ("group_m", C.c_int32),
                 ("threads", C.c_int32), ("lds_bytes", C.c_int32), ("grid", C.c_int32),
                 ("workspace_bytes", C.c_int64), ("name", C.c_char * 64)]
 
@@ -281,6 +281,27 @@ def gate_count_bad(Y, zref, norm_a, norm_b, K: int, epi: int, norm_b_row_stride:
     return int(r)
 
 
+def kernel_substr(v: VariantDesc):
+    """The part of the kernel's name in a profiler's output that identifies the compiled kernel behind variant v
+    (variants that differ only in launch parameters, such as K slices or the K order, share a kernel), or None."""
+    b = lambda x: "true" if x else "false"
+    if v.kind == TF_KIND_NAIVE:
+        return "tf_gemm_naive_kernel"
+    if v.kind == TF_KIND_MFMA_DIRECT:
+        return "tf_gemm_mfma_direct_kernel"
+    if v.kind == TF_KIND_MFMA_LDS:
+        cfg = "tf::LdsCfg<%d, %d, %d, %d, %d, %d, %s, %s, %d, %s, %s>" % (v.bm, v.bn, v.bk, v.waves_m, v.waves_n, v.stages, b(v.direct_to_lds),
+                                                                     b(v.a_bypass_lds), v.waves_k, b(v.trans_a), b(v.trans_b))
+        if v.persistent:
+            return "tf_bgemm_persist_kernel<" + cfg
+        if v.stream_k:
+            return "tf_gemm_lds_kernel<tf::StreamKCfg<" + cfg
+        return "tf_gemm_lds_kernel<" + cfg
+    if v.kind == TF_KIND_MFMA_STREAM:
+        return "tf_gemm_stream_kernel<tf::StreamCfg<%d, %d, %d, %d>" % (v.bm // 16, v.waves_k, v.stages, v.bn // 16)
+    return None
+
+
 def report_set_counters(report: Report, hw: Hw, csv_path: str, kernel_substr: str) -> None:
     _check(lib().tf_report_set_counters(C.byref(report), C.byref(hw), csv_path.encode(), kernel_substr.encode()))
 
@@ -289,8 +310,8 @@ class Problem:
     """tf_problem handle: one (M, N, K, strides, epilogue) instance of the tile kernel."""
 
     def __init__(self, M, N, K, lda=None, ldb=None, ldy=None, epi=TF_EPI_BIAS_GELU_ERF, device=0,
-                 op=TF_OP_GEMM_EPILOGUE, batch=1, stride_a=None, stride_b=None, stride_y=None):
-        lda_default, ldb_default = K, N
+                 op=TF_OP_GEMM_EPILOGUE, batch=1, stride_a=None, stride_b=None, stride_y=None, trans_b=0):
+        lda_default, ldb_default = K, (K if trans_b else N)
         if op == TF_OP_BATCHED_VECMAT:
             # C[m, n] = sum_k A[m, k] B[m, n, k]: B rows are K long, the output is fp32
             ldb_default, epi = K, TF_EPI_NONE_F32
@@ -305,7 +326,7 @@ class Problem:
         ldy = N if ldy is None else ldy
         self.desc = ProblemDesc(M, N, K, lda, ldb, ldy, epi, device, op, batch,
                                 K * lda if stride_a is None else stride_a, K * ldb if stride_b is None else stride_b,
-                                M * ldy if stride_y is None else stride_y)
+                                M * ldy if stride_y is None else stride_y, 1 if trans_b else 0)
         self._h = C.c_void_p()
         _check(lib().tf_problem_create(C.byref(self.desc), C.byref(self._h)))
 

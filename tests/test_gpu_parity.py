@@ -21,21 +21,22 @@ def variants_by_kind(prob):
     return prob.variants()
 
 
-def check_all_variants(M, N, K, A, B, bias, lda=None, ldb=None, ldy=None, only=None):
-    """Every variant enumerated for the shape against the oracle, with both epilogues."""
-    y, z, s = orc.gemm_bias_gelu(A, B, bias)
+def check_all_variants(M, N, K, A, B, bias, lda=None, ldb=None, ldy=None, only=None, trans_b=False):
+    """Every variant enumerated for the shape against the oracle, with both epilogues.
+    trans_b: B is handed over as [N, K] (k contiguous) and checked against the oracle written for that layout."""
+    y, z, s = orc.gemm_nt_bias_gelu(A, B, bias) if trans_b else orc.gemm_bias_gelu(A, B, bias)
     dA = gu.to_dev(A if lda is None else gu.strided(A, lda))
     dB = gu.to_dev(B if ldb is None else gu.strided(B, ldb))
     dbias = gu.to_dev(bias)
     ran = []
     for epi, f32 in ((tf.TF_EPI_BIAS_GELU_ERF, False), (tf.TF_EPI_NONE_F32, True)):
         out = gu.OutBuf(M, N, ldy=ldy, f32=f32)
-        with tf.Problem(M, N, K, lda=lda, ldb=ldb, ldy=ldy, epi=epi) as prob:
+        with tf.Problem(M, N, K, lda=lda, ldb=ldb, ldy=ldy, epi=epi, trans_b=trans_b) as prob:
             for v in prob.variants():
                 if only is not None and not only(v):
                     continue
                 name = v.name.decode()
-                print("case", (M, N, K), "epi", epi, "variant", name, flush=True)
+                print("case", (M, N, K), "trans_b" if trans_b else "", "epi", epi, "variant", name, flush=True)
                 got, intact, _ = gu.run_variant(prob, v.id, dA, dB, dbias, out)
                 assert intact, "%s wrote outside Y" % name
                 assert not np.isnan(got).any(), "%s left elements unwritten" % name
@@ -360,3 +361,71 @@ def test_caller_workspace_and_errors():
             prob.run(lds.id, dA.data_ptr() + 2, dB, dbias, out.ptr)      # misaligned A
         assert e.value.status == tf.TF_E_UNSUPPORTED
         torch.cuda.synchronize()
+
+
+def make_nk(M, N, K, seed, **kw):
+    """Operands of the custom recipe with B laid out as [N, K]."""
+    A, B, bias = wl.make_custom(M, N, K, seed=seed, **kw)
+    return A, np.ascontiguousarray(B.T), bias
+
+
+@pytest.mark.parametrize("shape", [(256, 256, 256), (300, 520, 448), (130, 264, 192), (33, 72, 64), (16, 512, 2048),
+                                   (257, 136, 1024), (512, 512, 1024)])
+def test_b_given_as_n_by_k(shape):
+    # every variant offered for the [N][K] layout: kernels that stage B as it lies (names with _bnk), ordinary kernels
+    # behind a transposing pass (_pretransB), and the two unstaged kernels; whole and ragged tiles, split-K
+    M, N, K = shape
+    A, Bt, bias = make_nk(M, N, K, seed=300 + M)
+    ran = check_all_variants(M, N, K, A, Bt, bias, trans_b=True)
+    assert any("_bnk_" in n for n in ran) and any("_pretransB_" in n for n in ran)
+    assert "naive_1elem_per_thread" in ran and "mfma32_direct_1wave" in ran
+    assert not any(n.startswith("stream_") for n in ran)
+    if K >= 1024:
+        assert any("_bnk_sk2" in n or "_bnk_sk4" in n for n in ran)
+
+
+def test_b_given_as_n_by_k_strided_ragged_k_and_exact():
+    # leading dimensions with padding (NaN patterns behind every row end)
+    M, N, K = 150, 200, 320
+    A, Bt, bias = make_nk(M, N, K, seed=317)
+    ran = check_all_variants(M, N, K, A, Bt, bias, lda=K + 24, ldb=K + 8, ldy=N + 16, trans_b=True)
+    assert any("_bnk_" in n for n in ran)
+    # K not a multiple of the K tile: only the unstaged kernels can run it
+    M, N, K = 70, 80, 200
+    A, Bt, bias = make_nk(M, N, K, seed=318)
+    ran = check_all_variants(M, N, K, A, Bt, bias, trans_b=True)
+    assert "naive_1elem_per_thread" in ran and not any(n.startswith("lds_") for n in ran)
+    # integer operands: every partial sum is exact in fp32, so the pre-activation must equal the oracle bit for bit
+    for (M, N, K) in ((192, 320, 1024), (130, 264, 4096), (32, 128, 2048)):
+        A = wl.small_int_bf16(43, 0, (M, K))
+        Bt = wl.small_int_bf16(43, 1, (N, K))
+        bias = wl.small_int_bf16(43, 2, (N,), -3, 3)
+        _, z, _ = orc.gemm_nt_bias_gelu(A, Bt, bias)
+        zf = z.astype(np.float32)
+        dA, dB, dbias = gu.to_dev(A), gu.to_dev(Bt), gu.to_dev(bias)
+        out = gu.OutBuf(M, N, f32=True)
+        with tf.Problem(M, N, K, epi=tf.TF_EPI_NONE_F32, trans_b=1) as prob:
+            vs = prob.variants()
+            assert any(v.split_k > 1 and v.trans_b for v in vs)
+            for v in vs:
+                print("exact nk", (M, N, K), v.name.decode(), flush=True)
+                _, intact, raw = gu.run_variant(prob, v.id, dA, dB, dbias, out)
+                assert intact
+                assert np.array_equal(raw, zf), v.name.decode()
+
+
+def test_loop_on_b_given_as_n_by_k():
+    torch = gu.torch_mod()
+    M, N, K = 1024, 1024, 1024
+    A, Bt, bias = make_nk(M, N, K, seed=321)
+    y, z, s = orc.gemm_nt_bias_gelu(A, Bt, bias)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(Bt), gu.to_dev(bias)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    with tf.Problem(M, N, K, trans_b=1) as prob:
+        best, rep, log = prob.tune(dA, dB, dbias, Y)
+        names = [prob.variants()[r.variant_id].name.decode() for r in log]
+        print("loop on [N][K]:", names, "->", names[[r.variant_id for r in log].index(best)], "%.2f us" % rep.t_med_us, flush=True)
+        assert best != 0 and rep.parity_ok == 1
+        assert all(r.parity_ok == 1 for r in log if r.status == 0)
+        got = Y.float().double().cpu().numpy()
+        assert np.all(np.abs(got - y) <= gu.strict_bound(y, z, s, K))

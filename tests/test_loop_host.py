@@ -13,7 +13,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "case_study3_rounds.t
 REPORT_KEYS = ["status", "parity_ok", "t_med_us", "t_min_us", "grid_fill", "arithmetic_intensity", "pct_mfma_peak",
                "pct_hbm_peak", "occupancy_pct", "have_counters", "mfma_busy_pct", "hbm_read_gbs", "hbm_write_gbs",
                "lds_bank_conflict_pct"]
-VARIANT_KEYS = ["kind", "bm", "bn", "stages", "split_k", "direct_to_lds", "lds_bytes", "grid"]
+VARIANT_KEYS = ["kind", "bm", "bn", "bk", "stages", "split_k", "direct_to_lds", "lds_bytes", "grid"]
 
 
 def c_report(d):
@@ -28,7 +28,6 @@ def c_variant(d, i):
     for k in VARIANT_KEYS:
         setattr(v, k, d[k])
     v.id = i
-    v.bk = 64
     v.waves_m = v.waves_n = 2
     v.waves_k = 1
     v.threads = 256
@@ -52,7 +51,7 @@ def rand_report(rng):
 def rand_variant(rng, kind=None):
     bm, bn = rng.choice([32, 64, 128, 256]), rng.choice([64, 128, 256])
     st = rng.choice([2, 3, 4])
-    return dict(kind=rng.choice([1, 2, 2, 2]) if kind is None else kind, bm=bm, bn=bn, stages=st,
+    return dict(kind=rng.choice([1, 2, 2, 2]) if kind is None else kind, bm=bm, bn=bn, bk=rng.choice([32, 64, 64, 128]), stages=st,
                 split_k=rng.choice([1, 2, 4, 8]), direct_to_lds=rng.randint(0, 1), lds_bytes=st * (bm + bn) * 128,
                 grid=rng.choice([16, 64, 128, 256, 688, 1024, 2752]))
 
@@ -129,8 +128,8 @@ def test_case_study3_replay_through_the_library():
                  have_counters=0, pct_mfma_peak=float(f[5]), pct_hbm_peak=float(f[4]), occupancy_pct=float(f[6]),
                  arithmetic_intensity=1000.0)
         reps.append(c_report(d))
-    fam = [c_variant(dict(kind=0, bm=4, bn=64, stages=0, split_k=1, direct_to_lds=0, lds_bytes=0, grid=4096), 0)]
-    fam += [c_variant(dict(kind=2, bm=128, bn=128, stages=2, split_k=1, direct_to_lds=1, lds_bytes=65536, grid=64), i)
+    fam = [c_variant(dict(kind=0, bm=4, bn=64, bk=1, stages=0, split_k=1, direct_to_lds=0, lds_bytes=0, grid=4096), 0)]
+    fam += [c_variant(dict(kind=2, bm=128, bn=128, bk=64, stages=2, split_k=1, direct_to_lds=1, lds_bytes=65536, grid=64), i)
             for i in range(1, 5)]
     bv, best, log = tf.tune_replay(desc, hw, fam, reps, th)
     assert bv == 0 and best.t_med_us == pytest.approx(9690.0)
@@ -160,7 +159,7 @@ def test_cost_model_orders_the_obvious_cases():
         for v in p.variants():
             if v.kind == tf.TF_KIND_MFMA_LDS and v.bm == 256 and v.bn == 256:
                 assert tf.resident_wgs(hw, v) == 1
-            if v.kind == tf.TF_KIND_MFMA_LDS and v.bm == 64 and v.bn == 64:
+            if v.kind == tf.TF_KIND_MFMA_LDS and v.bm == 64 and v.bn == 64 and v.bk == 64:
                 assert tf.resident_wgs(hw, v) == (3 if v.stages == 3 else 4)
             f = tf.grid_fill(hw, v)
             assert 0.0 < f <= 1.0
@@ -189,10 +188,10 @@ def test_case_study2_and_the_papers_two_hints_through_the_library():
     assert tf.arbiter(after, before, th, True, 0, 1) == tf.TF_DEC_ACCEPT
     # "memory stalls => improve tiling or staging", "low occupancy => adjust register pressure":
     # the next proposal from a 128x128 two-buffer kernel
-    fam = [c_variant(dict(kind=0, bm=4, bn=64, stages=0, split_k=1, direct_to_lds=0, lds_bytes=0, grid=4096), 0),
-           c_variant(dict(kind=2, bm=128, bn=128, stages=2, split_k=1, direct_to_lds=1, lds_bytes=65536, grid=256), 1),
-           c_variant(dict(kind=2, bm=128, bn=128, stages=3, split_k=1, direct_to_lds=1, lds_bytes=98304, grid=256), 2),
-           c_variant(dict(kind=2, bm=64, bn=64, stages=2, split_k=1, direct_to_lds=1, lds_bytes=32768, grid=1024), 3)]
+    fam = [c_variant(dict(kind=0, bm=4, bn=64, bk=1, stages=0, split_k=1, direct_to_lds=0, lds_bytes=0, grid=4096), 0),
+           c_variant(dict(kind=2, bm=128, bn=128, bk=64, stages=2, split_k=1, direct_to_lds=1, lds_bytes=65536, grid=256), 1),
+           c_variant(dict(kind=2, bm=128, bn=128, bk=64, stages=3, split_k=1, direct_to_lds=1, lds_bytes=98304, grid=256), 2),
+           c_variant(dict(kind=2, bm=64, bn=64, bk=64, stages=2, split_k=1, direct_to_lds=1, lds_bytes=32768, grid=1024), 3)]
     pred = [1000.0, 10.0, 20.0, 20.0]
     tried = [True, True, False, False]
     stalled = rep(100.0, 20.0, 30.0, 50.0, intensity=1000.0)

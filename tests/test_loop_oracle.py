@@ -21,8 +21,8 @@ def report(t_med, **kw):
     return r
 
 
-def variant(kind=lo.MFMA_LDS, bm=128, bn=128, stages=2, split_k=1, direct=1, lds=65536, grid=256):
-    return dict(kind=kind, bm=bm, bn=bn, stages=stages, split_k=split_k, direct_to_lds=direct, lds_bytes=lds,
+def variant(kind=lo.MFMA_LDS, bm=128, bn=128, stages=2, split_k=1, direct=1, lds=65536, grid=256, bk=64):
+    return dict(kind=kind, bm=bm, bn=bn, bk=bk, stages=stages, split_k=split_k, direct_to_lds=direct, lds_bytes=lds,
                 grid=grid)
 
 
