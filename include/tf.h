@@ -170,6 +170,12 @@ typedef struct {
   int32_t persistent;      /* TF_OP_BATCHED_GEMM_TN tile kernels: 1 = one work-group per CU walks through many output
                               tiles and fetches the next tile's K steps while the current one multiplies and
                               writes out (whole tiles, at least stages - 1 K steps per tile); grid = work-groups */
+  int32_t bn_tail;         /* tile kernels: > 0 = a launch with a lighter last round. Whole rounds of bm x bn tiles (one
+                              per CU and round) cover the leading columns; one more round of exactly one work-group
+                              per CU shares out the remaining columns of every row panel in tiles of which only
+                              bn_tail columns are multiplied, so every CU gets the same number of tiles and nearly
+                              the same work (offered when the rows make a whole number of CUs per row panel and the
+                              remaining columns fit such a round; names with `tail`); 0 = all tiles alike */
   int32_t nontemporal;     /* TF_KIND_SIN: 1 = loads and stores marked non-temporal (each element is touched once) */
   int32_t xcd_swizzle;     /* 1: work-group ids renumbered so that neighbouring tiles share an XCD L2 */
   int32_t group_m;         /* tile rows per group in the tile order */

@@ -38,6 +38,7 @@ struct VariantImpl {
   int tiles_m, tiles_n;
   size_t counter_bytes;   // leading part of the workspace
   int sk_first, sk_tiles; // stream-K: tiles computed whole (= first shared work-group), tiles whose K steps are shared
+  int mix_tiles, mix_blocks;   // lighter last round: its tiles per row panel, the blocks of 32 columns they share (tiles_n = tile columns of the wide part)
 };
 
 }  // namespace
@@ -131,7 +132,7 @@ void build_bgemm_family(tf_problem* p) {
   for (int pass = 0; pass < 2; ++pass) {          // 0: transposed staging, 1: separate transposing pass
     for (int i = 0; i < tf::lds_kernel_count(); ++i) {
       const tf::LdsKernelInfo& k = tab[i];
-      if (!k.direct_to_lds || k.a_bypass_lds || k.waves_k != 1 || k.stream_k || k.trans_b || k.bk != 64) continue;
+      if (!k.direct_to_lds || k.a_bypass_lds || k.waves_k != 1 || k.stream_k || k.trans_b || k.bk != 64 || k.bn_tail) continue;
       if (pass == 0 && !k.trans_a) continue;
       // the persistent kernel: whole tiles, enough K steps to keep its ring busy across a tile's output
       if (k.persistent && (pass == 1 || d.M % k.bm || d.N % k.bn || d.K / 64 < k.stages - 1)) continue;
@@ -252,6 +253,33 @@ void build_family(tf_problem* p) {
     }
     const long ktiles = cdivl(d.K, k.bk);
     if (k.direct_to_lds && d.K % k.bk != 0) continue;      // no zero fill on the direct path
+    if (k.bn_tail > 0) {
+      // a lighter last round: the row panels must take a whole number of CUs each, the leading columns make whole
+      // rounds of wide tiles, and what remains is between (bn_tail - 64) and bn_tail columns per CU of a row panel
+      if (pass != 0 || tb || k.lds_bytes > p->hw.lds_bytes_per_cu) continue;
+      const long tm = cdivl(d.M, k.bm);
+      if (tm > cus || cus % tm != 0) continue;
+      const long c = cus / tm, nb = cdivl(d.N, 32), wide = k.bn / 32, tail = k.bn_tail / 32;
+      const long rounds = nb / (wide * c), rest = nb - rounds * wide * c;
+      if (rounds < 1 || rest <= (tail - 2) * c || rest > tail * c) continue;
+      for (int kr = 0; kr < (ktiles * k.bk >= 512 ? 2 : 1); ++kr) {
+        tf_variant_desc v;
+        memset(&v, 0, sizeof(v));
+        v.k_rotate = kr;
+        v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n; v.waves_k = k.waves_k;
+        v.stages = k.stages; v.split_k = 1; v.direct_to_lds = 1; v.xcd_swizzle = 1; v.bn_tail = k.bn_tail;
+        v.group_m = (int32_t)std::min<long>(tm, 8);
+        v.threads = k.threads; v.lds_bytes = k.lds_bytes;
+        v.grid = (int32_t)(cus * rounds + cus);
+        VariantImpl im{};
+        im.lds_index = i; im.ktiles_per_split = (int)ktiles; im.tiles_m = (int)tm; im.tiles_n = (int)(c * rounds);
+        im.mix_tiles = (int)c; im.mix_blocks = (int)rest;
+        snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d_s%d_direct_tail%d_sk1%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n, k.stages,
+                 k.bn_tail, kr ? "x" : "");
+        add_variant(p, v, im);
+      }
+      continue;
+    }
     if (k.stream_k) {
       // stream-K: more tiles than CUs, not a whole number of rounds, and enough K steps to be worth sharing
       const long tm = cdivl(d.M, k.bm), tn = cdivl(d.N, k.bn), T = tm * tn;
@@ -533,6 +561,10 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
       tf::launch_transpose(g.B, (uint16_t*)ws, d.N, d.K, d.ldb, 0, d.N, 0, 1, stream);
       g.B = (const uint16_t*)ws; g.ldb = d.N;
       if (p->zeroed_ws == ws) { p->zeroed_ws = nullptr; p->zeroed_bytes = 0; }     // the counter area of this buffer has been written over
+    }
+    if (v.bn_tail > 0) {
+      g.mix_main_wgs = im.tiles_m * im.tiles_n; g.mix_tiles = im.mix_tiles; g.mix_blocks = im.mix_blocks;
+      g.mix_n_origin = im.tiles_n * v.bn;
     }
     if (v.stream_k) {
       // two contributors per shared tile exchange partial tiles like two split-K slices, through memory

@@ -24,8 +24,13 @@
 namespace tf {
 
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int STAGES_, bool DIRECT_, bool ABYPASS_ = false, int WK_ = 1, bool TRANSA_ = false,
-          bool TRANSB_ = false>
+          bool TRANSB_ = false, int BN_ACT_ = BN_>
 struct LdsCfg {
+  // BN_ACT < BN: a narrower tile that shares everything else with the BN-wide one. The B tile is staged BN wide as
+  // always (same ring, same transfers), but only the first BN_ACT columns are multiplied and written out: the
+  // tiles of a last, deliberately lighter round of a launch (see tf_gemm_mixed_kernel).
+  static constexpr int BN_ACT = BN_ACT_;
+  static_assert(BN_ACT_ <= BN_ && BN_ACT_ % (32 * WN_) == 0, "active width: whole 32-column blocks per wave column");
   // TRANSA: A is given transposed, [K][lda] with m contiguous (the dO^T A product of the paper's
   // Case Study 3). Its tile is then staged exactly like the B tile, [64][BM] row-major with the
   // same 64-byte piece swizzle, and its MFMA operands come from the transposing LDS read too:
@@ -54,7 +59,7 @@ struct LdsCfg {
   // staged. This halves the LDS write traffic, which is what bounds the two-operand scheme.
   static constexpr bool ABYPASS = ABYPASS_;
   static constexpr int NWAVES = WM * WN * WK, THREADS = NWAVES * 64;
-  static constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
+  static constexpr int WTM = BM / WM, WTN = BN_ACT / WN;   // wave tile
   static constexpr int TM = WTM / 32, TN = WTN / 32;       // 32x32 MFMA blocks per wave
   static constexpr int A_BYTES = ABYPASS ? 0 : BM * BK * 2, B_BYTES = BK * BN * 2;
   static_assert(!ABYPASS || (WN == 1 && DIRECT && STAGES == 2 && WK_ == 1 && BK == 64 && !TRANSB_), "A bypass: one wave column, direct B staging, two buffers, K tile of 64");
@@ -92,7 +97,7 @@ struct LdsCfg {
   // (not behind wave tiles of 256 accumulator registers: the extra code makes the compiler spill there)
   // the persistent kernel's fp32 staging area lies behind the ring
   static constexpr int PERSIST_LDS_BYTES = RING_BYTES + ST_ROWS * (BN * 4 + 16);
-  static constexpr bool stage_ok(int esz) { return TM * TN <= 8 && ST_ROWS * (BN * esz + 16) <= RING_BYTES; }
+  static constexpr bool stage_ok(int esz) { return TM * TN <= 8 && ST_ROWS * (BN_ACT * esz + 16) <= RING_BYTES; }
   // 32-row tiles serve problems of few rows, where every B element is read by one work-group only: its
   // loads are marked non-temporal
   static constexpr bool B_NT = BM <= 32;
@@ -334,8 +339,11 @@ __device__ __forceinline__ void store_partial(const f32x16 (&acc)[C::TM][C::TN],
 template <class C, bool FULL, bool THROUGH>
 __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0) {
   const size_t slice = (size_t)p.M * p.N;
-  if constexpr (THROUGH && FULL) {
-    // whole tiles: 16-byte device-scope loads, a slice's worth in flight at a time
+  if constexpr (FULL) {
+    // whole tiles: 16-byte loads (device scope, or plain ones for slices that sit in this XCD's L2), a slice's
+    // worth in flight at a time: written slice by slice, because a loop over the slices per element would be
+    // one long chain of dependent trips (the accumulator registers are free by now: their contents have been
+    // published)
     constexpr int NV = C::TM_OUT * C::TN * 4;
     static_assert(NV % 4 == 0 && NV <= 16, "register budget of the exchange");
     f32x4 sum[NV];
@@ -346,10 +354,14 @@ __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const 
 #pragma unroll
       for (int x = 0; x < NV; ++x) {
         const int i = x / (C::TN * 4), t = (x / 4) % C::TN, q = x % 4;
-        load_through_f32x4(v[x], p.ws + (size_t)sidx * slice + (size_t)(wm0 + 32 * i) * p.N + (wn0 + 32 * t + 8 * q));
+        const float* src = p.ws + (size_t)sidx * slice + (size_t)(wm0 + 32 * i) * p.N + (wn0 + 32 * t + 8 * q);
+        if constexpr (THROUGH) load_through_f32x4(v[x], src);
+        else v[x] = *(const f32x4*)src;
       }
+      if constexpr (THROUGH) {
 #pragma unroll
-      for (int x = 0; x < NV; x += 4) wait_through(v[x], v[x + 1], v[x + 2], v[x + 3]);
+        for (int x = 0; x < NV; x += 4) wait_through(v[x], v[x + 1], v[x + 2], v[x + 3]);
+      }
 #pragma unroll
       for (int x = 0; x < NV; ++x) sum[x] += v[x];
     }
@@ -399,13 +411,13 @@ template <int E> struct EpiTag { static constexpr int value = E; };
 // bias_lds: this lane's first four bias values in LDS (columns wn0 .. wn0 + 3 of the tile's copy)
 template <class C, bool FULL, int EPI>
 __device__ __forceinline__ void epilogue(const f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0,
-                                         const char* bias_lds) {
+                                         const char* bias_lds, int n_end) {
 #pragma unroll
   for (int t = 0; t < C::TN; ++t) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int n = wn0 + 32 * t + 8 * q;
-      const bool n_ok = FULL || n < p.N;
+      const bool n_ok = FULL || n < n_end;
       const u32x2 braw = *(const u32x2*)(bias_lds + (32 * t + 8 * q) * 2);   // (columns past N hold values nobody stores)
       const float b0 = __builtin_bit_cast(float, braw[0] << 16), b1 = __builtin_bit_cast(float, braw[0] & 0xffff0000u);
       const float b2 = __builtin_bit_cast(float, braw[1] << 16), b3 = __builtin_bit_cast(float, braw[1] & 0xffff0000u);
@@ -443,11 +455,12 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[C::TM][C::TN], cons
 template <class C, int EPI, bool PARTIAL = false>
 __device__ __forceinline__ void epilogue_staged(const f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, char* smem, int m0,
                                                 int n0, int tid, int wave_m, int wave_n, int wave_k, int lane_m, int lane_g,
-                                                char* dst, size_t ld) {
+                                                char* dst, size_t ld, int ncols = C::BN_ACT) {
+  // ncols: columns of the tile that exist / belong to it (a multiple of 8); pieces past them are not stored
   static_assert(!PARTIAL || EPI == TF_EPI_NONE_F32, "partial sums are fp32");
   constexpr int ESZ = EPI == TF_EPI_NONE_F32 ? 4 : 2;
-  constexpr int ROWB = C::BN * ESZ + 16;                 // staged row, padded: the 32 rows a store hits spread over the banks
-  constexpr int CPR = C::BN * ESZ / 16;                  // 16-byte pieces per row
+  constexpr int ROWB = C::BN_ACT * ESZ + 16;             // staged row, padded: the 32 rows a store hits spread over the banks
+  constexpr int CPR = C::BN_ACT * ESZ / 16;              // 16-byte pieces per row
   constexpr int PER_THREAD = C::ST_ROWS * CPR / C::THREADS;
   static_assert(C::ST_ROWS * CPR % C::THREADS == 0, "pieces divide over the threads");
   const char* bias_lds = smem + C::BIAS_OFF + (wave_n * C::WTN + 4 * lane_g) * 2;
@@ -487,13 +500,13 @@ __device__ __forceinline__ void epilogue_staged(const f32x16 (&acc)[C::TM][C::TN
       const int g = rs >> 5;                               // wave row and k group the staged row came from
       const int m = m0 + (g / C::WK) * C::WTM + (g % C::WK) * 32 * (C::TM / 2) + 32 * i + (rs & 31);
       const u32x4 v = *(const u32x4*)(smem + rs * ROWB + cc * 16);
-      __builtin_nontemporal_store(v, (u32x4*)(dst + ((size_t)m * ld + n0) * ESZ + cc * 16));
+      if (cc * 16 < ncols * ESZ) __builtin_nontemporal_store(v, (u32x4*)(dst + ((size_t)m * ld + n0) * ESZ + cc * 16));
     }
   }
 }
 
 template <class C>
-__global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParams p_in) {
+__device__ __forceinline__ void gemm_tile_body(const GemmParams& p_in) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   // batched problems: blockIdx.y is the batch item, whose operands are a stride away
   GemmParams p = p_in;
@@ -546,7 +559,25 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   TileCoord tc;
   int kt_begin, kt_end;
   bool split = p.split_k > 1;      // this segment is one of several contributions to its tile
-  if (!stream_k) {
+  int n0_mixed = -1, n_end = p.N;  // (mixed grid) origin of a tile of the narrow round; first column that is not the tile's
+  if (p.mix_main_wgs > 0) {
+    // A launch of whole rounds of BN-wide tiles over the first columns, then one round of narrower tiles that
+    // share out the remaining columns of every row panel evenly (see tf_gemm_mixed_kernel). No K slices.
+    if constexpr (C::BN_ACT == C::BN) {
+      tc = tile_at(p, xcd_run(tile_id, p.mix_main_wgs));          // p.tiles_n = tile columns of the wide part
+    } else {
+      const int t = xcd_run(tile_id - p.mix_main_wgs, p.tiles_m * p.mix_tiles);
+      tc.tm = t / p.mix_tiles; tc.tn = 0; tc.ks = 0;
+      const int j = t - tc.tm * p.mix_tiles;
+      // tile j of the row panel starts at block floor(j R / T) of the remaining R blocks of 32 columns and owns the
+      // blocks up to the start of tile j + 1 (at most BN_ACT / 32 of them; the host checked)
+      const int b0 = (int)((long)j * p.mix_blocks / p.mix_tiles), b1 = (int)((long)(j + 1) * p.mix_blocks / p.mix_tiles);
+      n0_mixed = p.mix_n_origin + 32 * b0;
+      const int lim = p.mix_n_origin + 32 * b1;
+      n_end = lim < p.N ? lim : p.N;
+    }
+    kt_begin = 0; kt_end = ktiles_total; split = false; more = false;
+  } else if (!stream_k) {
     tc = map_tile(p, tile_id);
     kt_begin = tc.ks * p.ktiles_per_split;
     kt_end = kt_begin + p.ktiles_per_split;
@@ -567,7 +598,7 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     sk_cur += kt_end - kt_begin;
     more = sk_cur < sk_end;
   }
-  const int m0 = tc.tm * C::BM, n0 = tc.tn * C::BN;
+  const int m0 = tc.tm * C::BM, n0 = n0_mixed >= 0 ? n0_mixed : tc.tn * C::BN;
   const int nkt = kt_end - kt_begin;   // may be <= 0 for a trailing empty slice: contributes zeros
 
   // ---- LDS read offsets of this lane (bytes inside a stage)
@@ -1041,7 +1072,9 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
   }
   const int wm0 = m0 + wave_m * C::WTM + lane_m + (C::WK == 2 ? wave_k * 32 * (C::TM / 2) : 0);   // + 32 i
   const int wn0 = n0 + wave_n * C::WTN + 4 * lane_g;          // + 32 t + 8 q
-  const bool full = (m0 + C::BM <= p.M) && (n0 + C::BN <= p.N);
+  const int ncols = n_end - n0 < C::BN_ACT ? n_end - n0 : C::BN_ACT;     // columns this tile writes (a multiple of 8)
+  const bool rows_full = m0 + C::BM <= p.M;
+  const bool full = rows_full && ncols == C::BN_ACT;
 
   if (split) {
     // publish the partial tile; the last slice to arrive sums all slices in slice order
@@ -1115,21 +1148,42 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParam
     __syncthreads();
   }
   const char* bias_lds = smem + C::BIAS_OFF + (wave_n * C::WTN + 4 * lane_g) * 2;
-  const bool staged = full && p.y_vec16;      // the same for every wave of the work-group
+  // whole rows of the tile go out coalesced through LDS, also when the tile's last columns do not exist or belong
+  // to its neighbour (their pieces are skipped)
+  const bool staged = rows_full && ncols > 0 && p.y_vec16;      // the same for every wave of the work-group
   auto finish = [&](auto tag) {
     constexpr int EPI = decltype(tag)::value;
     constexpr int ESZ = EPI == TF_EPI_NONE_F32 ? 4 : 2;
     if (C::stage_ok(ESZ) && staged) {
       if constexpr (C::stage_ok(ESZ))
-        epilogue_staged<C, EPI>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g, (char*)p.Y, (size_t)p.ldy);
-    } else if (full) epilogue<C, true, EPI>(acc, p, wm0, wn0, bias_lds);
-    else epilogue<C, false, EPI>(acc, p, wm0, wn0, bias_lds);
+        epilogue_staged<C, EPI>(acc, p, smem, m0, n0, tid, wave_m, wave_n, wave_k, lane_m, lane_g, (char*)p.Y, (size_t)p.ldy, ncols);
+    } else if (full) epilogue<C, true, EPI>(acc, p, wm0, wn0, bias_lds, n_end);
+    else epilogue<C, false, EPI>(acc, p, wm0, wn0, bias_lds, n_end);
   };
   if (p.epi == TF_EPI_BIAS_GELU_ERF) finish(EpiTag<TF_EPI_BIAS_GELU_ERF>{});
   else if (p.epi == TF_EPI_NONE_F32) finish(EpiTag<TF_EPI_NONE_F32>{});
   else if (p.epi == TF_EPI_BIAS) finish(EpiTag<TF_EPI_BIAS>{});
   else finish(EpiTag<TF_EPI_BIAS_GELU_TANH>{});
   }   // segments
+}
+
+template <class C>
+__global__ void __launch_bounds__(C::THREADS) tf_gemm_lds_kernel(const GemmParams p) {
+  gemm_tile_body<C>(p);
+}
+
+// A launch with a lighter last round. Equal tiles leave the chip badly filled whenever the tile count is a little
+// above a multiple of the CU count (688 tiles on 256 CUs: the third round runs on 176 of them). Here the first
+// work-groups (whole rounds) compute BN-wide tiles over the leading columns, and one more round of exactly one
+// work-group per CU shares out the remaining columns of every row panel in narrower tiles (CN: the same staging,
+// fewer columns multiplied): every CU gets the same number of tiles and nearly the same work. Work-groups are
+// handed to the CUs in id order, so the narrow round comes last.
+template <class CM, class CN>
+__global__ void __launch_bounds__(CM::THREADS) tf_gemm_mixed_kernel(const GemmParams p) {
+  static_assert(CM::THREADS == CN::THREADS && CM::LDS_BYTES == CN::LDS_BYTES && CM::BM == CN::BM && CM::BN == CN::BN &&
+                CM::BK == CN::BK && CN::BN_ACT < CN::BN, "the two tile shapes share the work-group shape and the staging");
+  if ((int)blockIdx.x < p.mix_main_wgs) gemm_tile_body<CM>(p);
+  else gemm_tile_body<CN>(p);
 }
 
 // Persistent kernel for the batched transposed-operand product with few K steps per tile
@@ -1316,6 +1370,10 @@ template <class C>
 static void launch_lds(const GemmParams& p, dim3 grid, hipStream_t stream) {
   hipLaunchKernelGGL(tf_gemm_lds_kernel<C>, grid, dim3(C::THREADS), C::LDS_BYTES, stream, p);
 }
+template <class CM, class CN>
+static void launch_mixed(const GemmParams& p, dim3 grid, hipStream_t stream) {
+  hipLaunchKernelGGL((tf_gemm_mixed_kernel<CM, CN>), grid, dim3(CM::THREADS), CM::LDS_BYTES, stream, p);
+}
 
 // The same kernel with the loop over segments compiled in: work-groups may take several (tile, K range) pieces.
 template <class Base>
@@ -1328,9 +1386,18 @@ static LdsKernelInfo make_info() {
   k.stages = C::STAGES; k.direct_to_lds = C::DIRECT ? 1 : 0; k.a_bypass_lds = C::ABYPASS ? 1 : 0; k.trans_a = C::TRANSA ? 1 : 0;
   k.trans_b = C::TRANSB ? 1 : 0;
   k.threads = C::THREADS; k.lds_bytes = C::LDS_BYTES; k.fused_ok = C::FUSED_OK ? 1 : 0;
-  k.persistent = 0; k.stream_k = C::SEGMENTS ? 1 : 0;
+  k.persistent = 0; k.stream_k = C::SEGMENTS ? 1 : 0; k.bn_tail = 0;
   k.func = (const void*)tf_gemm_lds_kernel<C>;
   k.launch = launch_lds<C>;
+  return k;
+}
+
+template <class CM, class CN>
+static LdsKernelInfo make_mixed_info() {
+  LdsKernelInfo k = make_info<CM>();
+  k.bn_tail = CN::BN_ACT;
+  k.func = (const void*)tf_gemm_mixed_kernel<CM, CN>;
+  k.launch = launch_mixed<CM, CN>;
   return k;
 }
 
@@ -1404,6 +1471,8 @@ using N64x64_d3    = LdsCfg< 64,  64, 64, 2, 2, 3, true, false, 1, false, true>;
 using N32x64_d4    = LdsCfg< 32,  64, 64, 1, 2, 4, true, false, 1, false, true>;
 using N32x128_d3   = LdsCfg< 32, 128, 64, 1, 4, 3, true, false, 1, false, true>;
 using N32x32_d4    = LdsCfg< 32,  32, 64, 1, 1, 4, true, false, 1, false, true>;
+// the big tile with only 192 of its 256 columns multiplied (4 x 2 waves of 64 x 96): the lighter last round
+using K256x192_w8b = LdsCfg<256, 256, 64, 4, 2, 2, true, false, 1, false, false, 192>;
 
 static LdsKernelInfo g_table[] = {
     make_info<K256x128_d2>(), make_info<K128x256_d2>(),
@@ -1426,6 +1495,7 @@ static LdsKernelInfo g_table[] = {
     make_info<N256x256_w8a>(), make_info<N256x256_w8b>(), make_info<N128x128_w8a>(), make_info<N128x128_w8b>(),
     make_info<N128x128_d2>(), make_info<N128x128x128>(), make_info<N64x64_d3>(), make_info<N32x64_d4>(),
     make_info<N32x128_d3>(), make_info<N32x32_d4>(),
+    make_mixed_info<K256x256_w8a, K256x192_w8b>(), make_mixed_info<K256x256_w8b, K256x192_w8b>(),
 };
 
 int lds_kernel_count() { return (int)(sizeof(g_table) / sizeof(g_table[0])); }

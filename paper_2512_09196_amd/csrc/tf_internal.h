@@ -35,6 +35,9 @@ struct GemmParams {
   int ws_vec16;           // 1: the split-K workspace starts on a 16-byte boundary (its rows of N floats then do too)
   int y_vec16;            // 1: every row of Y (of every batch item) starts on a 16-byte boundary
   int trans_b;            // 1: B is [N][ldb] with k contiguous (the unstaged kernels read it that way; tile kernels are compiled for one layout)
+  // mixed grid (tf_gemm_mixed_kernel): the first mix_main_wgs work-groups compute BN-wide tiles (tiles_m x tiles_n of them),
+  // then tiles_m x mix_tiles work-groups share out the mix_blocks blocks of 32 columns that begin at column mix_n_origin
+  int mix_main_wgs, mix_tiles, mix_blocks, mix_n_origin;
 };
 
 // One compiled kernel of the LDS-staged MFMA family.
@@ -46,6 +49,7 @@ struct LdsKernelInfo {
   int fused_ok;           // 1: the kernel contains the in-kernel split-K reduction (fused_reduce 1 and 2)
   int stream_k;           // 1: instance with the loop over (tile, K range) segments compiled in (stream-K variants only)
   int persistent;         // 1: tf_bgemm_persist_kernel (one work-group per CU walks through many tiles; grid.x = work-groups)
+  int bn_tail;            // > 0: tf_gemm_mixed_kernel, width of the tiles of its lighter last round
   const void* func;       // kernel symbol, for hipFuncGetAttributes / occupancy queries
   void (*launch)(const GemmParams&, dim3 grid, hipStream_t);
 };

@@ -264,6 +264,8 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   // number of work-groups per slot, plus a ragged end
   double rounds = (double)v->grid / (double)slots;
   rounds = rounds <= 1.0 ? 1.0 : rounds + 0.25;
+  // a lighter last round: whole rounds of full tiles, then one of tiles that multiply bn_tail of their bn columns
+  if (v->bn_tail > 0 && v->bn > 0) rounds = (double)v->grid / (double)slots - 1.0 + (double)v->bn_tail / v->bn + 0.05;
   if (v->stream_k) {
     // every CU gets the same number of K steps: the tile count over the CU count, no ragged last round. But the
     // shares start at arbitrary K offsets, so the work-groups of an XCD no longer walk through K together and

@@ -42,7 +42,7 @@ class ProblemDesc(_Struct):
 class VariantDesc(_Struct):
     _fields_ = [("id", C.c_int32), ("kind", C.c_int32), ("bm", C.c_int32), ("bn", C.c_int32), ("bk", C.c_int32),
                 ("waves_m", C.c_int32), ("waves_n", C.c_int32), ("waves_k", C.c_int32), ("stages", C.c_int32), ("split_k", C.c_int32), ("fused_reduce", C.c_int32),
-                ("direct_to_lds", C.c_int32), ("a_bypass_lds", C.c_int32), ("trans_a", C.c_int32), ("trans_b", C.c_int32), ("stream_k", C.c_int32), ("k_rotate", C.c_int32), ("persistent", C.c_int32), ("nontemporal", C.c_int32), ("xcd_swizzle", C.c_int32), ("group_m", C.c_int32),
+                ("direct_to_lds", C.c_int32), ("a_bypass_lds", C.c_int32), ("trans_a", C.c_int32), ("trans_b", C.c_int32), ("stream_k", C.c_int32), ("k_rotate", C.c_int32), ("persistent", C.c_int32), ("bn_tail", C.c_int32), ("nontemporal", C.c_int32), ("xcd_swizzle", C.c_int32), ("group_m", C.c_int32),
                 ("threads", C.c_int32), ("lds_bytes", C.c_int32), ("grid", C.c_int32),
                 ("workspace_bytes", C.c_int64), ("name", C.c_char * 64)]
 
@@ -290,8 +290,10 @@ def kernel_substr(v: VariantDesc):
     if v.kind == TF_KIND_MFMA_DIRECT:
         return "tf_gemm_mfma_direct_kernel"
     if v.kind == TF_KIND_MFMA_LDS:
-        cfg = "tf::LdsCfg<%d, %d, %d, %d, %d, %d, %s, %s, %d, %s, %s>" % (v.bm, v.bn, v.bk, v.waves_m, v.waves_n, v.stages, b(v.direct_to_lds),
-                                                                     b(v.a_bypass_lds), v.waves_k, b(v.trans_a), b(v.trans_b))
+        cfg = "tf::LdsCfg<%d, %d, %d, %d, %d, %d, %s, %s, %d, %s, %s, " % (v.bm, v.bn, v.bk, v.waves_m, v.waves_n, v.stages, b(v.direct_to_lds),
+                                                                      b(v.a_bypass_lds), v.waves_k, b(v.trans_a), b(v.trans_b))
+        if v.bn_tail:
+            return "tf_gemm_mixed_kernel<" + cfg
         if v.persistent:
             return "tf_bgemm_persist_kernel<" + cfg
         if v.stream_k:

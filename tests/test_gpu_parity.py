@@ -429,3 +429,32 @@ def test_loop_on_b_given_as_n_by_k():
         assert all(r.parity_ok == 1 for r in log if r.status == 0)
         got = Y.float().double().cpu().numpy()
         assert np.all(np.abs(got - y) <= gu.strict_bound(y, z, s, K))
+
+
+@pytest.mark.parametrize("shape", [(2048, 13824, 128), (2048, 13784, 192), (2024, 13824, 64), (4096, 6912, 64)])
+def test_launch_with_a_lighter_last_round(shape):
+    # whole rounds of 256 x 256 tiles over the leading columns, then one round of tiles that multiply 192 of their 256
+    # columns and share out the rest of every row panel: five or six blocks of 32 columns each, the last one possibly
+    # cut by N, the last row panel possibly ragged; integer operands, so every element must be exact, and every
+    # element must be written exactly by the tile it belongs to
+    M, N, K = shape
+    A = wl.small_int_bf16(77, 0, (M, K))
+    B = wl.small_int_bf16(77, 1, (K, N))
+    bias = wl.small_int_bf16(77, 2, (N,), -3, 3)
+    _, z, _ = orc.gemm_bias_gelu(A, B, bias)
+    zf = z.astype(np.float32)
+    assert np.array_equal(zf.astype(np.float64), z)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    out = gu.OutBuf(M, N, f32=True)
+    with tf.Problem(M, N, K, epi=tf.TF_EPI_NONE_F32) as prob:
+        tail = [v for v in prob.variants() if v.bn_tail]
+        assert len(tail) >= 2 and all(v.grid % 256 == 0 and v.bn_tail == 192 for v in tail)
+        for v in tail:
+            print("tail", shape, v.name.decode(), flush=True)
+            _, intact, raw = gu.run_variant(prob, v.id, dA, dB, dbias, out)
+            assert intact
+            assert np.array_equal(raw, zf), v.name.decode()
+    # the bf16 epilogue through the same variants, against the oracle's bound, on the workload recipe
+    A, B, bias = wl.make_custom(M, N, K, seed=78)
+    ran = check_all_variants(M, N, K, A, B, bias, only=lambda v: v.bn_tail > 0)
+    assert len(ran) >= 4
