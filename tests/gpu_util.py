@@ -66,6 +66,29 @@ class OutBuf:
         return wl.bf16_bits_to_f32(raw).astype(np.float64), intact, raw
 
 
+def oracle_parallel(A, B, bias, threads=None, block=16, trans_b=False):
+    """The unchanged oracle on disjoint row blocks from several host threads (rows are independent; the C function
+    holds no state and ctypes releases the interpreter lock). Returns (y, z, s) float64 [M, N] like the oracle."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import gemm_oracle as orc
+    fn = orc.gemm_nt_bias_gelu if trans_b else orc.gemm_bias_gelu
+    M = A.shape[0]
+    N = B.shape[0] if trans_b else B.shape[1]
+    threads = threads or max(1, min(16, os.cpu_count() or 1))
+    y = np.empty((M, N), np.float64)
+    z = np.empty((M, N), np.float64)
+    s = np.empty((M, N), np.float64)
+
+    def work(r0):
+        r1 = min(M, r0 + block)
+        yy, zz, ss = fn(A[r0:r1], B, bias)
+        y[r0:r1], z[r0:r1], s[r0:r1] = yy, zz, ss
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(work, range(0, M, block)))
+    return y, z, s
+
+
 def gamma(n):
     u = 2.0 ** -24
     return n * u / (1.0 - n * u)

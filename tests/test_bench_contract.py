@@ -38,3 +38,23 @@ def test_one_json_line_with_roofline_and_cpu_baseline(workload):
     assert rf["frac"] == pytest.approx(rf["achieved"] / rf["peak"]) and 0 < rf["frac"] < 1 and "traffic" in rf
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] == 1 and cb["value"] > 0 and cb["sample"]
+
+
+@pytest.mark.gpu
+def test_default_run_is_the_largest_workload_with_all_five_listed():
+    r = run_bench("--steps", "20", "--warmup", "5", "--no-cpu", timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert d["config"]["workload"].startswith("C3") and d["roofline"]["bound"] == "mfma" and d["unit"] == "TFLOP/s"
+    assert d["roofline"]["target_frac"] == 0.6 and d["roofline"]["met"] in (True, False)
+    pc = d["per_config"]
+    assert [c["workload"][:2] for c in pc] == ["C1", "C2", "C3", "C4", "C5"]
+    for c in pc:
+        assert c["avg_launch_us"] > 0 and c["tflops"] > 0 and 0 < c["frac"] < 1 and c["tuned_vs_naive"] >= 1.05
+        assert c["bound"] == ("hbm" if c["workload"].startswith("C4") else "mfma")
+        assert c["variant"] != "naive_1elem_per_thread"
+    assert pc[2]["variant"] == d["config"]["variant"]
+    assert d["tune"]["selected"] == d["config"]["variant"] and d["tune"]["log"][0]["variant"] == "naive_1elem_per_thread"
+    assert all(r["parity_ok"] == 1 for r in d["tune"]["log"] if r["status"] == 0)

@@ -1,6 +1,5 @@
 """Parity at the full sizes of the five workloads, in the launch configuration the benchmark
-times: sampled outputs against the oracle (one dot product each), all variants against each
-other on the whole output, and the GPU-driven variant loop."""
+times: every element of the output against the whole oracle, and the GPU-driven variant loop."""
 import numpy as np
 import pytest
 
@@ -31,47 +30,69 @@ def sample_positions(M, N, n_random=1500, seed=0):
     return np.array(rows, np.int32), np.array(cols, np.int32)
 
 
+def tile_shape(v):
+    return (v.kind, v.bm, v.bn, v.bk, v.waves_m, v.waves_n, v.waves_k, v.stages, v.direct_to_lds, v.a_bypass_lds, v.bn_tail,
+            v.stream_k)
+
+
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
-def test_full_size_sampled_parity_and_variant_agreement(name):
+def test_full_size_every_element_against_the_whole_oracle(name):
+    """Every element of the output at the full size of the workload, in the launch configuration the benchmark
+    times, against the whole oracle (run unchanged on disjoint row blocks from the host's cores): the strict
+    a-priori bound for the bf16 epilogue, the summation bound for the fp32 pre-activation. C2, C4, C5: every
+    variant; C3 (45 M outputs, a launch of the baseline kernel takes 0.1 s): the kernel the loop selects, one
+    variant per compiled tile kernel, and the baseline."""
     torch = gu.torch_mod()
     w = wl.WORKLOADS[name]
     A, B, bias = inputs(name)
-    rows, cols = sample_positions(w.M, w.N, seed=w.seed)
-    y, z, s = orc.gemm_bias_gelu_at(A, B, bias, rows, cols)
+    y, z, s = gu.oracle_parallel(A, B, bias)
+    print(name, "oracle done", flush=True)
     dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
-    r_t = torch.from_numpy(rows.astype(np.int64)).cuda()
-    c_t = torch.from_numpy(cols.astype(np.int64)).cuda()
+    # the bounds, evaluated once in float64 on the device (test arithmetic, not the library's)
+    ty, tz, ts = (torch.from_numpy(x).cuda() for x in (y, z, s))
+    g = gu.gamma(w.K + 1)
+    strict = 2.0 ** -8 * ty.abs() + 1.13 * 2.0 * g * ts + 1e-6 * (1.0 + tz.abs())
+    official = 1e-2 * (1.0 + ty.abs())
+    preact = 2.0 * g * ts + 2.0 ** -23 * tz.abs() + 1e-30
+    del ts
+    checked = 0
     for epi, f32 in ((tf.TF_EPI_BIAS_GELU_ERF, False), (tf.TF_EPI_NONE_F32, True)):
         Y = torch.empty((w.M, w.N), dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
-        ref = None
         with tf.Problem(w.M, w.N, w.K, epi=epi) as prob:
             vs = prob.variants()
-            # the slow unstaged kernels only once per workload (bf16 epilogue), every tile kernel always
-            todo = [v for v in vs if v.kind == tf.TF_KIND_MFMA_LDS or not f32]
+            if name == "C3":
+                best, rep, log = prob.tune(dA, dB, dbias, Y)
+                todo, seen = [vs[best]], {tile_shape(vs[best])}
+                for v in vs:
+                    if v.kind == tf.TF_KIND_MFMA_DIRECT or (v.kind == tf.TF_KIND_NAIVE and f32) or tile_shape(v) in seen:
+                        continue
+                    seen.add(tile_shape(v))
+                    todo.append(v)
+            else:
+                # the slow unstaged kernels only once per workload (bf16 epilogue), every tile kernel always
+                todo = [v for v in vs if v.kind in (tf.TF_KIND_MFMA_LDS, tf.TF_KIND_MFMA_STREAM) or not f32]
             assert len(todo) >= 3
             for v in todo:
                 print(name, "epi", epi, v.name.decode(), flush=True)
                 Y.fill_(float("nan"))
                 prob.run(v.id, dA, dB, dbias, Y)
                 torch.cuda.synchronize()
-                Yf = Y.float()
-                assert not torch.isnan(Yf).any().item(), v.name.decode() + " left NaN / unwritten elements"
-                got = Yf[r_t, c_t].double().cpu().numpy()
+                got = Y.double()
+                assert not torch.isnan(got).any().item(), v.name.decode() + " left NaN / unwritten elements"
                 if f32:
-                    assert np.all(np.abs(got - z) <= gu.preact_bound(z, s, w.K)), v.name.decode()
+                    bad = ((got - tz).abs() > preact).sum().item()
+                    assert bad == 0, "%s: %d pre-activations outside the summation bound" % (v.name.decode(), bad)
                 else:
-                    assert gu.official_ok(got, y), v.name.decode()
-                    assert np.all(np.abs(got - y) <= gu.strict_bound(y, z, s, w.K)), v.name.decode()
-                if ref is None:
-                    ref = Yf.clone()
-                else:
-                    # two correct kernels differ by summation order only: far inside the official bar,
-                    # and (bf16 output) by at most one rounding step of the larger value
-                    d = (Yf - ref).abs()
-                    lim = 1e-2 * (1.0 + ref.abs())
-                    assert bool((d <= lim).all().item()), v.name.decode()
-                del Yf
-        del Y, ref
+                    err = (got - ty).abs()
+                    assert (err > official).sum().item() == 0, v.name.decode()
+                    bad = (err > strict).sum().item()
+                    assert bad == 0, "%s: %d elements outside the strict bound" % (v.name.decode(), bad)
+                    del err
+                del got
+                checked += 1
+            prob.workspace_status()
+        del Y
+    assert checked >= 6
 
 
 def test_tune_on_gpu_c1_and_c2():
