@@ -379,6 +379,8 @@ def main():
     ap.add_argument("--no-library-context", action="store_true", help="skip the vendor-library matrix product timed for context")
     ap.add_argument("--counters", action="append", default=[],
                     help="rocprofv3 --pmc counter CSV (repeatable, one per profiler pass): attach to the loop's rounds and print the round table")
+    ap.add_argument("--read-calibration", type=float, default=0,
+                    help="launch a plain streaming read of this many bytes per launch instead (--steps launches): the chip's rate at that size")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="launch a plain device copy of known size instead (reference reading for the HBM traffic counters)")
     args = ap.parse_args()
@@ -405,6 +407,17 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": True, "launches": args.warmup + args.steps,
                           "bytes_read_per_launch": 2 * n, "bytes_written_per_launch": 2 * n}))
+        return
+    if args.read_calibration:
+        # a plain streaming read of that many bytes per launch, from buffers that rotate past the memory-side cache:
+        # what the chip delivers at the size of a memory-bound workload (C4: 134.76 MB), beside the kernel's own rate
+        nbytes = int(args.read_calibration) // 16 * 16
+        nb = max(3, -(-2 * MALL_BYTES // nbytes) + 1)
+        bufs = [torch.ones(nbytes // 2, dtype=torch.int16, device="cuda") for _ in range(nb)]
+        torch.cuda.synchronize()
+        gbs = tf.hw_read_rate(bufs, nbytes, args.steps)
+        print(json.dumps({"read_calibration": True, "bytes_per_launch": nbytes, "buffers": nb, "launches": args.steps,
+                          "gbs": gbs, "us_per_launch": nbytes / gbs * 1e-3, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}))
         return
     default_run = args.workload is None
     name = "C3" if default_run else args.workload

@@ -245,6 +245,14 @@ void tf_hw_nominal(tf_hw* out);
  * fractions, which are quoted against the published peaks. */
 tf_status tf_hw_measure(int32_t device, void* hip_stream, double* mfma_tflops, double* hbm_read_gbs);
 
+/* The rate of a plain streaming read at a given size, for comparison with a memory-bound kernel of that size:
+ * `launches` launches of a kernel that reads `bytes` bytes once, launch i from buffers[i % n_buffers] (a host
+ * array of device pointers to caller-owned buffers of at least `bytes` bytes each, 16-byte aligned; rotate over
+ * more than the memory-side cache holds to read from HBM every time). *gbs (host pointer) gets the average rate
+ * per launch between two events on hip_stream, which is synchronised. */
+tf_status tf_hw_read_rate(int32_t device, void* hip_stream, const void* const* buffers, int32_t n_buffers,
+                          int64_t bytes, int32_t launches, double* gbs);
+
 /* Validates desc (host pointer) and creates the problem. M, N, K >= 0. */
 tf_status tf_problem_create(const tf_problem_desc* desc, tf_problem** out);
 void tf_problem_destroy(tf_problem* p);

@@ -246,7 +246,7 @@ void build_family(tf_problem* p) {
     if (pass == 0 && (k.trans_b != 0) != tb) continue;
     if (pass == 1) {
       // a few representative kernels behind the transposing pass
-      const bool pick = !k.trans_b && k.direct_to_lds && !k.a_bypass_lds && !k.stream_k && k.waves_k == 1 && k.bk == 64 &&
+      const bool pick = !k.trans_b && k.direct_to_lds && !k.a_bypass_lds && !k.stream_k && k.waves_k == 1 && k.bk == 64 && !k.bn_tail &&
                         ((k.bm == 256 && k.bn == 256) || (k.bm == 128 && k.bn == 128 && k.threads == 512 && k.stages == 3) ||
                          (k.bm == 64 && k.bn == 64) || (k.bm == 32 && k.bn == 64 && k.stages == 4));
       if (!pick) continue;
@@ -1047,6 +1047,32 @@ extern "C" tf_status tf_hw_measure(int32_t device, void* hip_stream, double* mfm
     *hbm_read_gbs = best;
   }
   cleanup();
+  TF_HIP(hipGetLastError());
+  return TF_OK;
+}
+
+extern "C" tf_status tf_hw_read_rate(int32_t device, void* hip_stream, const void* const* buffers, int32_t n_buffers,
+                                     int64_t bytes, int32_t launches, double* gbs) {
+  if (!buffers || n_buffers < 1 || bytes < 16 || launches < 1 || !gbs) return fail(TF_E_INVALID, "bad argument");
+  for (int i = 0; i < n_buffers; ++i)
+    if (!buffers[i] || ((uintptr_t)buffers[i] & 15u)) return fail(TF_E_INVALID, "buffer %d is null or not 16-byte aligned", i);
+  tf_hw hw;
+  tf_status st = tf_hw_query(device, &hw);
+  if (st != TF_OK) return st;
+  TF_HIP(hipSetDevice(device));
+  hipStream_t stream = (hipStream_t)hip_stream;
+  void* sink = nullptr;
+  if (hipMalloc(&sink, 256) != hipSuccess) return fail(TF_E_NOMEM, "cannot allocate the sink");
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) { (void)hipFree(sink); return fail(TF_E_LAUNCH, "hipEventCreate failed"); }
+  for (int i = 0; i < std::min(launches, n_buffers); ++i) tf::launch_calib_read(buffers[i % n_buffers], (size_t)bytes, (unsigned*)sink, hw.cus * 8, stream);
+  float ms = 0.f;
+  bool ok = hipEventRecord(e0, stream) == hipSuccess;
+  for (int i = 0; i < launches; ++i) tf::launch_calib_read(buffers[i % n_buffers], (size_t)bytes, (unsigned*)sink, hw.cus * 8, stream);
+  ok = ok && hipEventRecord(e1, stream) == hipSuccess && hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipFree(sink);
+  if (!ok || ms <= 0.f) return fail(TF_E_LAUNCH, "read-rate launches failed");
+  *gbs = (double)bytes * launches / (ms * 1e-3) * 1e-9;
   TF_HIP(hipGetLastError());
   return TF_OK;
 }

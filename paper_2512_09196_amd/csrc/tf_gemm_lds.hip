@@ -500,7 +500,12 @@ __device__ __forceinline__ void epilogue_staged(const f32x16 (&acc)[C::TM][C::TN
       const int g = rs >> 5;                               // wave row and k group the staged row came from
       const int m = m0 + (g / C::WK) * C::WTM + (g % C::WK) * 32 * (C::TM / 2) + 32 * i + (rs & 31);
       const u32x4 v = *(const u32x4*)(smem + rs * ROWB + cc * 16);
-      if (cc * 16 < ncols * ESZ) __builtin_nontemporal_store(v, (u32x4*)(dst + ((size_t)m * ld + n0) * ESZ + cc * 16));
+      if (cc * 16 < ncols * ESZ) {
+        // the output is not read again by this launch: non-temporal; a partial tile is read back at once by the
+        // reduction: ordinary stores, so that it may stay in the caches on the way
+        if constexpr (PARTIAL) *(u32x4*)(dst + ((size_t)m * ld + n0) * ESZ + cc * 16) = v;
+        else __builtin_nontemporal_store(v, (u32x4*)(dst + ((size_t)m * ld + n0) * ESZ + cc * 16));
+      }
     }
   }
 }

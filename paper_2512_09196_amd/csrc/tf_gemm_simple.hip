@@ -172,7 +172,7 @@ __global__ void __launch_bounds__(256) tf_splitk_reduce_kernel(const GemmParams 
   const float* src = p.ws + m * p.N + n;
   f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
   // the partial sums are read once and the output written once: neither needs to stay in the caches
-  for (int s = 0; s < p.split_k; ++s) sum += __builtin_nontemporal_load((const f32x4*)(src + (size_t)s * slice));
+  for (int s = 0; s < p.split_k; ++s) sum += *(const f32x4*)(src + (size_t)s * slice);
   const u32x2 braw = *(const u32x2*)(p.bias + n);
   const float z0 = sum[0] + __builtin_bit_cast(float, braw[0] << 16);
   const float z1 = sum[1] + __builtin_bit_cast(float, braw[0] & 0xffff0000u);

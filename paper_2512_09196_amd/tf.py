@@ -84,6 +84,7 @@ SIGNATURES = {
     "tf_hw_query": (C.c_int32, [C.c_int32, _P(Hw)]),
     "tf_hw_nominal": (None, [_P(Hw)]),
     "tf_hw_measure": (C.c_int32, [C.c_int32, C.c_void_p, _P(C.c_double), _P(C.c_double)]),
+    "tf_hw_read_rate": (C.c_int32, [C.c_int32, C.c_void_p, _P(C.c_void_p), C.c_int32, C.c_int64, C.c_int32, _P(C.c_double)]),
     "tf_problem_create": (C.c_int32, [_P(ProblemDesc), _P(C.c_void_p)]),
     "tf_problem_destroy": (None, [C.c_void_p]),
     "tf_variant_enumerate": (C.c_int32, [C.c_void_p, _P(VariantDesc), C.c_int32]),
@@ -205,6 +206,14 @@ def hw_measure(device: int = 0, stream=None):
     return a.value, b.value
 
 
+def hw_read_rate(buffers, nbytes: int, launches: int, device: int = 0, stream=None) -> float:
+    """GB/s of a plain streaming read of nbytes per launch, rotating over the given device tensors."""
+    arr = (C.c_void_p * len(buffers))(*[b.data_ptr() for b in buffers])
+    g = C.c_double(0.0)
+    _check(lib().tf_hw_read_rate(device, _stream(stream), arr, len(buffers), nbytes, launches, C.byref(g)))
+    return g.value
+
+
 def arbiter(cand: Report, best: Report, theta: Theta, best_is_baseline: bool, stall_rounds: int, rnd: int) -> int:
     return lib().tf_arbiter(C.byref(cand), C.byref(best), C.byref(theta), int(best_is_baseline), stall_rounds, rnd)
 
@@ -290,8 +299,8 @@ def kernel_substr(v: VariantDesc):
     if v.kind == TF_KIND_MFMA_DIRECT:
         return "tf_gemm_mfma_direct_kernel"
     if v.kind == TF_KIND_MFMA_LDS:
-        cfg = "tf::LdsCfg<%d, %d, %d, %d, %d, %d, %s, %s, %d, %s, %s, " % (v.bm, v.bn, v.bk, v.waves_m, v.waves_n, v.stages, b(v.direct_to_lds),
-                                                                      b(v.a_bypass_lds), v.waves_k, b(v.trans_a), b(v.trans_b))
+        cfg = "tf::LdsCfg<%d, %d, %d, %d, %d, %d, %s, %s, %d, %s, %s, %d>" % (v.bm, v.bn, v.bk, v.waves_m, v.waves_n, v.stages, b(v.direct_to_lds),
+                                                                         b(v.a_bypass_lds), v.waves_k, b(v.trans_a), b(v.trans_b), v.bn)
         if v.bn_tail:
             return "tf_gemm_mixed_kernel<" + cfg
         if v.persistent:

@@ -102,8 +102,11 @@ def official_ok(got, y):
 def strict_bound(y, z, s, K):
     """A-priori bound for a correct fp32-accumulating kernel with bf16 output:
     bf16 rounding (half an ulp, 2^-9 relative; 2^-8 taken) + any-order fp32 summation
-    (gamma_{K+1} s, doubled for the MFMA's internal order) through GELU (slope <= 1.13) +
-    the erfc approximation and fp32 evaluation of the epilogue."""
+    (gamma_{K+1} s, doubled: the matrix instruction adds sixteen products to the accumulator in an
+    order and with an intermediate rounding that are not documented, so each of its additions is
+    allowed a whole unit in the last place instead of half of one) through GELU (slope <= 1.13) +
+    the kernel's own evaluation of the activation in fp32 (a polynomial for log2 Phi and one exp2,
+    within 3.8e-7 (1 + |z|) of the definition; 1e-6 (1 + |z|) taken)."""
     return 2.0 ** -8 * np.abs(y) + 1.13 * 2.0 * gamma(K + 1) * s + 1e-6 * (1.0 + np.abs(z))
 
 
