@@ -56,16 +56,17 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(w, A, B, bias, budget_s=12.0):
+def cpu_baseline(w, A, B, bias, budget_s=12.0, b_as_nk=False):
     """The oracle as it stands, single thread, on the first rows of the same workload."""
     from oracle import gemm_oracle as orc
+    fn = orc.gemm_nt_bias_gelu if b_as_nk else orc.gemm_bias_gelu
     probe_rows = max(1, min(w.M, int(2e7 // max(1, w.N * w.K)) or 1))
     t0 = time.perf_counter()
-    orc.gemm_bias_gelu(A[:probe_rows], B, bias)
+    fn(A[:probe_rows], B, bias)
     dt = time.perf_counter() - t0
     rows = int(max(probe_rows, min(w.M, probe_rows * budget_s / max(dt, 1e-6))))
     t0 = time.perf_counter()
-    orc.gemm_bias_gelu(A[:rows], B, bias)
+    fn(A[:rows], B, bias)
     dt = time.perf_counter() - t0
     flops = 2.0 * rows * w.N * w.K
     return {"value": flops / dt * 1e-12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
@@ -215,6 +216,8 @@ def measure(args, name, steps, warmup, headline):
             bias = None
         else:
             A, B, bias = wl.make_inputs(w)
+            if args.b_as_nk:
+                B = np.ascontiguousarray(B.T)       # the same numbers, handed over output-major: [N][K], k contiguous
     set_bytes = w.algorithmic_bytes
     nbuf = max(2, min(24, -(-2 * MALL_BYTES // set_bytes)))
     log("buffer sets: %d x %.1f MB" % (nbuf, set_bytes / 1e6))
@@ -234,7 +237,7 @@ def measure(args, name, steps, warmup, headline):
     else:
         epi = {"gelu_erf": tf.TF_EPI_BIAS_GELU_ERF, "gelu_tanh": tf.TF_EPI_BIAS_GELU_TANH, "bias": tf.TF_EPI_BIAS}[args.epilogue]
         prob = tf.Problem(w.M, w.N, w.K, op=tf.TF_OP_BATCHED_VECMAT if vecmat else tf.TF_OP_GEMM_EPILOGUE,
-                          epi=tf.TF_EPI_NONE_F32 if vecmat else epi)
+                          epi=tf.TF_EPI_NONE_F32 if vecmat else epi, trans_b=1 if args.b_as_nk and not vecmat else 0)
     variants = prob.variants()
     names = [v.name.decode() for v in variants]
     tune = None
@@ -324,7 +327,7 @@ def measure(args, name, steps, warmup, headline):
     if not args.no_library_context and not nobias:
         try:
             a16 = [x.view(torch.bfloat16) for x in dA]
-            b16 = [x.view(torch.bfloat16) for x in dB]
+            b16 = [x.view(torch.bfloat16).t() if args.b_as_nk else x.view(torch.bfloat16) for x in dB]
             n_lib = max(20, min(steps, 200))
             for i in range(5):
                 torch.matmul(a16[i % nbuf], b16[i % nbuf], out=dY[i % nbuf])
@@ -341,7 +344,8 @@ def measure(args, name, steps, warmup, headline):
     if sin:
         workload = "%s: n=%d fp32, N(0, 10) inputs, seed %d" % (w.name, w.n, w.seed)
     else:
-        workload = "%s: %sM=%d N=%d K=%d bf16, seed %d" % (w.name, "batch=%d " % w.batch if bgemm else "", w.M, w.N, w.K, w.seed)
+        workload = "%s: %sM=%d N=%d K=%d bf16, seed %d%s" % (w.name, "batch=%d " % w.batch if bgemm else "", w.M, w.N, w.K, w.seed,
+                                                              ", B given as [N][K]" if args.b_as_nk and not (vecmat or bgemm) else "")
     rec = {"workload": workload, "variant": names[vid], "grid": v.grid, "split_k": v.split_k, "buffer_sets": nbuf,
            "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "avg_launch_us": kern_us,
            "tflops": tflops, "gbs_algorithmic": w.algorithmic_bytes / (ms_per_step * 1e-3) * 1e-9,
@@ -372,6 +376,9 @@ def main():
                          "T1, T2: batched transposed-operand product C[b] = A[b]^T B[b]; E1, E2: element-wise sine y = sin(x), fp32")
     ap.add_argument("--epilogue", default="gelu_erf", choices=["gelu_erf", "gelu_tanh", "bias"],
                     help="C1..C5 only: the bf16 epilogue (the headline metric is gelu_erf)")
+    ap.add_argument("--b-as-nk", action="store_true",
+                    help="C1..C5 only: hand B over as [N][K] (weights stored output-major); the loop then chooses among the kernels "
+                         "that stage B as it lies and a transposing pass ahead of an ordinary kernel")
     ap.add_argument("--variant", default=None, help="time this variant instead of the loop's choice")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-tune", action="store_true", help="skip the loop (needs --variant)")
@@ -469,7 +476,7 @@ def main():
         log("timing the CPU oracle on a bounded sample ...")
         A, B, bias = x["A"], x["B"], x["bias"]
         out["cpu_baseline"] = (cpu_baseline_sin(w, A.view(np.float32)) if sin else cpu_baseline_vecmat(w, A, B) if vecmat else cpu_baseline_bgemm(w, A, B) if bgemm
-                               else cpu_baseline(w, A, B, bias))
+                               else cpu_baseline(w, A, B, bias, b_as_nk=args.b_as_nk))
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))

@@ -58,3 +58,14 @@ def test_default_run_is_the_largest_workload_with_all_five_listed():
     assert pc[2]["variant"] == d["config"]["variant"]
     assert d["tune"]["selected"] == d["config"]["variant"] and d["tune"]["log"][0]["variant"] == "naive_1elem_per_thread"
     assert all(r["parity_ok"] == 1 for r in d["tune"]["log"] if r["status"] == 0)
+
+
+@pytest.mark.gpu
+def test_b_given_as_n_by_k_is_a_bench_workload():
+    r = run_bench("--workload", "C1", "--b-as-nk", "--steps", "20", "--warmup", "5")
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads([l for l in r.stdout.splitlines() if l.strip()][0])
+    assert "B given as [N][K]" in d["config"]["workload"]
+    assert "_bnk_" in d["config"]["variant"] or "_pretransB_" in d["config"]["variant"]
+    assert all(r["parity_ok"] == 1 for r in d["tune"]["log"] if r["status"] == 0)
+    assert d["cpu_baseline"]["value"] > 0
