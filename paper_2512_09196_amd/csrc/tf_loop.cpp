@@ -199,53 +199,57 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   const double kr = bk / 64.0;                      // the figures below are per 64 of K: a tile of bk is kr of them
   const long ktiles = cdiv(cdiv(pr->K, bk), v->split_k);
   const int mn_waves = v->waves_m * v->waves_n, wg_waves = mn_waves * (v->waves_k > 1 ? v->waves_k : 1);
-  // Cycles one CU spends on one K tile (64 wide) of one work-group. The constants are fits to
-  // this family's measured times on MI355X (2048^3, 4096 x 11008 x 4096 and 1024^2 x 16384):
-  //  * the clock under MFMA load is about 1650 MHz, whatever the nominal figure says; all
+  // Cycles one CU spends on one K tile (64 wide) of one work-group. The form of each term is what the kernels
+  // do; the constants are a least-squares fit (of log predicted / measured, variants within 1.5x of the best) to
+  // this family's measured times on MI355X on eight shapes (2048^3, 4096 x 11008 x 4096, 16 x 8192^2,
+  // 1024^2 x 16384, 3072^3, 1024 x 8192 x 4096, 256 x 8192^2, 4096 x 2048^2) and were then checked on eight others:
+  //  * the clock under MFMA load with every CU busy is about 1650 MHz, whatever the nominal figure says (the board
+  //    is power limited); with fewer work-groups than CUs it is higher, by about 0.38 of the idle share; all
   //    cycle counts below are at that clock;
-  //  * an MFMA 32x32x16 issues every 36 cycles, not 32;
-  //  * tiles enter LDS at 140 B/ns per CU (85 B/clk) on either staging path, fragments leave it
-  //    at about 256 B/clk; reads and writes take turns;
+  //  * an MFMA 32x32x16 costs 36.5 cycles of its pipe, not 32;
+  //  * tiles enter LDS at about 167 B/clk, fragments leave it at about 203 B/clk; reads and writes take turns;
+  //  * a CU receives A tiles (short row pieces) at 82 B/clk and B tiles (long ones) at 52 B/clk when all CUs
+  //    ask at once; 0.38 of that time is not hidden behind the matrix pipes;
   //  * per K step a chain of barrier, transfer issue, first fragment reads and first MFMA is
-  //    exposed: about 800 cycles with two buffers, 250 with three or more, and a second wave per
-  //    SIMD hides 70 % of it; register staging adds 300, the A-bypass loads 400.
-  const double mfma = kr * v->bm * (double)v->bn / 32.0 * (36.0 / 32.0);
+  //    exposed: about 490 cycles with two buffers, 237 with three or more, and a second wave per
+  //    SIMD hides nearly all of it; register staging adds 300, the A-bypass loads 400.
+  const double mfma = kr * v->bm * (double)v->bn / 32.0 * 1.14;
   const double stage_bytes = kr * (v->a_bypass_lds ? v->bn : v->bm + v->bn) * 128.0;
-  const double lds_w = stage_bytes / 85.0;
+  const double lds_w = stage_bytes / 167.0;
   long co_resident = cdiv(v->grid, hw->cus);       // work-groups really sharing a CU, not how many would fit
   if (co_resident > resident) co_resident = resident;
   const double cu_waves = (double)wg_waves * co_resident;
   const double a_rows = v->a_bypass_lds ? 0.0 : (double)(v->bm / v->waves_m);
-  const double lds_r = kr * mn_waves * (a_rows + (v->bn / v->waves_n)) * 128.0 / 256.0;
-  const double ta = kr * (v->bm + v->bn) * 128.0 / 85.0;         // global -> CU
-  double chain = v->stages >= 3 ? 250.0 : 800.0;
-  if (cu_waves >= 8) chain *= v->waves_k > 1 ? 0.7 : 0.3;       // k groups: half the MFMAs per wave and step to hide it behind
-  // a K tile of 32 has only two 16-wide steps of MFMAs between two hand-overs to hide the chain behind (measured:
-  // 256 x 256 x 32 with four buffers is 5 % slower than 256 x 256 x 64 with two)
-  if (bk < 64) chain *= 64.0 / bk * 2.0;
+  const double lds_r = kr * mn_waves * (a_rows + (v->bn / v->waves_n)) * 128.0 / 203.0;
+  const double ta = kr * (v->bm * 128.0 / 82.0 + v->bn * 128.0 / 52.0);         // global -> CU
+  double chain = v->stages >= 3 ? 237.0 : 490.0;
+  if (cu_waves >= 8) chain *= v->waves_k > 1 ? 0.455 : 0.05;    // k groups: half the MFMAs per wave and step to hide it behind
+  // a K tile of 32 pays the chain twice per 64 of K
+  if (bk < 64) chain *= 64.0 / bk;
   if (!v->direct_to_lds) chain += 300.0;
   if (v->a_bypass_lds) chain += 400.0;
   // the tile transfers are never fully hidden behind the matrix pipes: they share the LDS port with the fragment
   // reads and the L2 with the other CUs, and most of their time shows (measured: the 256 x 128 and 128 x 256
   // tiles, whose other figures match the 256 x 256 tile's, need 12-15 % more time per flop; they move 1.5 times
   // the bytes per flop)
-  double ktile = fmax(fmax(mfma, lds_w + lds_r), ta) + chain + 0.7 * ta;
+  double ktile = fmax(fmax(mfma, lds_w + lds_r), ta) + chain + 0.376 * ta;
   // the in-kernel reductions keep the slices of a tile side by side, so the work-groups of an XCD work on
   // different K ranges and share fewer operand panels in its L2 than in the slice-by-slice order of the
   // two-kernel reduction (measured: about a quarter more time per K step)
   // (big tiles; the skinny tiles' operands are read once anyway)
   const double big = fmin(1.0, v->bm * (double)v->bn / 16384.0);
-  if (v->split_k > 1 && v->fused_reduce) ktile *= 1.0 + 0.25 * big;
-  // per tile: pipeline fill (first tiles from memory), then bias + GELU + pack at about 22 VALU
+  if (v->split_k > 1 && v->fused_reduce) ktile *= 1.0 + 0.166 * big;
+  // per tile: pipeline fill (first tiles from memory), then bias + GELU + pack at about 11 VALU
   // issue slots per element, or the fp32 partial tile at 32 B/clk when a second kernel reduces
-  const double fill = 2500.0 / (double)co_resident;
+  const double fill = 2900.0 / (double)co_resident;
   // (the raw fp32 output has no activation to evaluate: 16-byte stores at about 64 B/clk)
-  // VALU instructions per output element of the epilogue: erf-GELU 22, tanh-GELU 14, plain conversions 4
-  const double epi_valu = pr->epi == TF_EPI_BIAS_GELU_ERF ? 22.0 : pr->epi == TF_EPI_BIAS_GELU_TANH ? 14.0 : 4.0;
+  // VALU issue slots per output element of the epilogue: erf-GELU 11, tanh-GELU 7, plain conversions 2
+  const double epi_valu = pr->epi == TF_EPI_BIAS_GELU_ERF ? 11.0 : pr->epi == TF_EPI_BIAS_GELU_TANH ? 7.0 : 2.0;
   double tile_end = v->bm * (double)v->bn * epi_valu / 64.0;
   if (v->waves_k > 1) tile_end += v->bm * (double)v->bn * 4.0 * (1.0 / 85.0 + 1.0 / 256.0) / 2.0 * v->waves_k;   // accumulator exchange
   double reduce_us = 0.0, fused_tail_us = 0.0;
-  const double mhz = hw->clock_mhz < 1650.0 ? hw->clock_mhz : 1650.0;
+  const double active = v->grid < hw->cus ? (double)v->grid / hw->cus : 1.0;
+  const double mhz = (hw->clock_mhz < 1650.0 ? hw->clock_mhz : 1650.0) * (1.0 + 0.38 * (1.0 - active));
   if (v->split_k > 1) {
     if (v->fused_reduce == 2) {
       // partial tiles stay in the L2 the slices share: 16-byte stores and loads, one round of tickets
@@ -257,13 +261,19 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
       fused_tail_us = 4.0 + 2.5 * v->split_k + v->bm * (double)v->bn * 4.0 * (1.0 + v->split_k) / 32.0 / mhz;
     } else {
       tile_end = v->bm * (double)v->bn * 4.0 / 32.0;
-      reduce_us = 3.7 + (v->split_k + 0.5) * 4.0 * pr->M * (double)pr->N / (0.4 * hw->hbm_gbs_peak * 1e3);
+      reduce_us = 4.5 + (v->split_k + 0.5) * 4.0 * pr->M * (double)pr->N / (0.686 * hw->hbm_gbs_peak * 1e3);
     }
   }
-  // CUs take the next work-group as they finish one: the makespan is close to the average
-  // number of work-groups per slot, plus a ragged end
+  // CUs take the next work-group as they finish one: whole rounds, then a last round that takes between half a
+  // round's time (few work-groups left: they have the chip's memory system and power budget to themselves)
+  // and all of it, plus a ragged end
   double rounds = (double)v->grid / (double)slots;
-  rounds = rounds <= 1.0 ? 1.0 : rounds + 0.25;
+  if (rounds <= 1.0) {
+    rounds = 1.0;
+  } else {
+    const double whole = floor(rounds + 1e-9), part = rounds - whole;
+    rounds = whole + (part < 1e-9 ? 0.0 : 0.51 + 0.49 * part) + 0.09;
+  }
   // a lighter last round: whole rounds of full tiles, then one of tiles that multiply bn_tail of their bn columns
   if (v->bn_tail > 0 && v->bn > 0) rounds = (double)v->grid / (double)slots - 1.0 + (double)v->bn_tail / v->bn + 0.05;
   if (v->stream_k) {
@@ -282,14 +292,15 @@ extern "C" double tf_predict_us(const tf_problem_desc* pr, const tf_hw* hw, cons
   // (prefetched tiles of all co-resident work-groups), in proportion below that
   double inflight = (double)co_resident * (v->stages - 1) * stage_bytes / 32768.0;
   if (inflight > 1.0) inflight = 1.0;
-  // launch, first tile from HBM and drain: about 4 us per launch
+  // launch, first tile from HBM and drain: about 3.6 us per launch
   // K order rotated by XCD: measured 2-4 % faster on 2048^3, between equal and 10 % faster on
   // 4096 x 11008 x 4096 depending on the kernel and the chip: proposed first, the plain order right behind
-  const double rot = v->k_rotate ? 0.98 : 1.0;
+  // (the eight-wave 256 x 128 and 128 x 256 tiles were 0-8 % slower with it on five other shapes)
+  const double rot = !v->k_rotate ? 1.0 : ((long)v->bm * v->bn == 32768 && wg_waves == 8) ? 1.02 : 0.98;
   // B given as [N][K] behind a separate transposing pass: one more launch that reads and writes all of B
   const double pretrans_us = (pr->op == TF_OP_GEMM_EPILOGUE && pr->trans_b && !v->trans_b)
                                  ? 3.0 + 4.0 * (double)pr->K * pr->N / (0.6 * hw->hbm_gbs_peak * 1e3) : 0.0;
-  return fmax(us * rot, (hbm_us + ws_us) / (0.75 * inflight)) + 4.0 + reduce_us + fused_tail_us + pretrans_us;
+  return fmax(us * rot, (hbm_us + ws_us) / (0.75 * inflight)) + 3.6 + reduce_us + fused_tail_us + pretrans_us;
 }
 
 // ------------------------------------------------------------------ Proposal
