@@ -397,7 +397,10 @@ int64_t tf_gate_count_bad(const void* Y, int64_t ldy, const float* zref, const f
  * report per round; *n_log their number. *best_variant / *best get K* and R*. Y is filled with
  * NaN before every candidate's BuildRun, so an element a candidate does not write fails the gate.
  * parity may be NULL: the library then compares every candidate with the baseline kernel's fp32
- * pre-activation by the rule of tf_gate_count_bad (on the device). */
+ * pre-activation by the rule of tf_gate_count_bad (on the device). Profile here is Sec. 3.4's
+ * 3 warm-up + 5 timed iterations, each timed iteration a batch of launches of about 3 ms, after
+ * further untimed launches until 60 ms have been spent on the candidate (the clock needs that
+ * long to settle after a change of load), on rotating copies of the operands (theta->cold_bytes). */
 tf_status tf_tune(tf_problem* p, const void* A, const void* B, const void* bias, void* Y,
                   void* workspace, size_t workspace_bytes, void* hip_stream,
                   const tf_theta* theta, tf_parity_fn parity, void* parity_user,

@@ -890,13 +890,20 @@ tf_status profile_impl(tf_problem* p, int id, const void* A, const void* B, cons
   double t = 0.0;
   for (int w = 0; w < warmup && st == TF_OK; ++w) st = timed(1, &t);
   // The variant loop (rot != null) times what a caller running the kernel continuously would see:
-  // clocks and memory settle over milliseconds, so the warm-up goes on until 3 ms have been
-  // spent and every timed batch lasts about 3 ms. Otherwise batches of about a millisecond, so
-  // that one launch's overhead does not dominate short kernels.
+  // the board's clock takes tens of milliseconds to settle when the load changes (the first tile kernel
+  // timed after the slow baseline kernel read 8 % slow with a warm-up of 3 ms: 343 us against 313 us in
+  // steady state, enough to lose to a worse kernel timed later), so the warm-up goes on until 60 ms
+  // have been spent and every timed batch lasts about 3 ms. Otherwise batches of about a
+  // millisecond, so that one launch's overhead does not dominate short kernels.
   const double batch_us = rot ? 3000.0 : 1000.0;
   if (st == TF_OK && rot) {
     double spent = 0.0;
-    for (int w = 0; w < 4000 && spent < 3000.0 && st == TF_OK; ++w) { st = timed(1, &t); spent += t > 0.0 ? t : 1.0; }
+    int n = 1;                            // then batches of about 3 ms, as in the timed iterations
+    for (int w = 0; w < 1000 && spent < 60000.0 && st == TF_OK; ++w) {
+      st = timed(n, &t);
+      spent += (t > 0.0 ? t : 1.0) * n;
+      n = t > 0.0 ? std::max(1, std::min((int)ceil(3000.0 / t), 2000)) : 1000;
+    }
   }
   if (st == TF_OK && lpi == 0) {
     st = timed(1, &t);
