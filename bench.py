@@ -263,11 +263,13 @@ def measure(args, name, steps, warmup, headline):
     vid = None
     use_variant = args.variant if headline else None
     if not (args.no_tune and headline):
+        if headline and args.counters:
+            prob.set_counter_files(args.counters)       # the hints of the loop below then read the profiler's figures
         t0 = time.perf_counter()
         best, rep, rlog = prob.tune(dA[0], dB[0], db[0], dY[0], stream=stream)
         tune_s = time.perf_counter() - t0
         rounds = [{"variant": names[r.variant_id], "t_med_us": round(r.t_med_us, 3), "status": r.status,
-                   "parity_ok": r.parity_ok, "bottleneck": tf.BOTTLENECK_NAMES[r.bottleneck],
+                   "parity_ok": r.parity_ok, "bottleneck": tf.BOTTLENECK_NAMES[r.bottleneck], "have_counters": r.have_counters,
                    "pct_mfma_peak": round(r.pct_mfma_peak, 2), "pct_hbm_peak": round(r.pct_hbm_peak, 2),
                    "static_occupancy_pct": round(r.occupancy_pct, 1)} for r in rlog]
         for r in rounds:

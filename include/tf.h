@@ -330,6 +330,24 @@ tf_status tf_variant_profile(tf_problem* p, int32_t variant_id, const void* A, c
 tf_status tf_report_set_counters(tf_report* r, const tf_hw* hw, const char* csv_path,
                                  const char* kernel_substr);
 
+/* The part of a kernel's name in profiler output that identifies the compiled kernel behind variant v
+ * (variants that differ only in launch parameters, such as K slices or the K order, share a kernel),
+ * written to buf (host pointer, cap bytes, NUL-terminated): the kernel_substr for
+ * tf_report_set_counters. Returns its length, 0 for kernels whose template arguments the
+ * descriptor does not spell out (buf is then empty), TF_E_RANGE if cap is too small. Needs no GPU. */
+int32_t tf_variant_kernel_name(const tf_variant_desc* v, char* buf, int32_t cap);
+
+/* Hands the loop what a profiler measured (Sec. 3.4 "Profiling": the report that RefineHint reads
+ * carries the profiler's figures): csv_paths[0..n) (host pointers, copied) are rocprofv3 counter
+ * CSVs of earlier passes over this problem's kernels, one per counter set, e.g. of a command that
+ * launches every variant the loop may visit. tf_tune then fills the counter fields of every
+ * round's report from the rows of that round's kernel (tf_report_set_counters with
+ * tf_variant_kernel_name) before RefineHint classifies it, so that the hint rests on matrix-pipe
+ * busy, HBM and LDS-conflict figures instead of rates derived from the time; a kernel that no file
+ * holds keeps have_counters = 0. Pass the matrix-pipe and the memory passes together: a figure no
+ * file holds reads zero. n = 0 forgets the files. TF_E_INVALID if a file cannot be opened. */
+tf_status tf_problem_set_counter_files(tf_problem* p, const char* const* csv_paths, int32_t n);
+
 /* ---- the loop's host logic: pure functions, callable without a GPU ---------------------- */
 
 /* Performance-Arbiter: decision for candidate report `cand` against best-so-far `best`.

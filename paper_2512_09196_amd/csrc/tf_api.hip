@@ -54,6 +54,7 @@ struct tf_problem {
   void* zeroed_ws;        // workspace whose counters are known to be zero
   size_t zeroed_bytes;
   std::vector<char> attr_done;   // per LDS kernel: dynamic-LDS attribute set on this device
+  std::vector<std::string> counter_files;   // profiler output of an earlier pass: attached to the loop's reports
 };
 
 namespace {
@@ -849,6 +850,13 @@ tf_status tune_profile(void* user, int32_t id, tf_report* out) {
   st = profile_impl(p, id, c->A, c->B, c->bias, c->Y, c->ws, c->ws_bytes, c->stream, 3, 5, 0, out, c->rot);
   if (st != TF_OK) { out->status = st; return TF_OK; }
   out->parity_ok = ok;
+  // what the profiler measured for this kernel in an earlier pass, if the caller handed its output in: the
+  // hint that follows then reads matrix-pipe, memory and LDS figures instead of rates derived from the time
+  if (!p->counter_files.empty() && p->have_hw) {
+    char name[192];
+    if (tf_variant_kernel_name(&p->family[id], name, (int32_t)sizeof(name)) > 0)
+      for (const std::string& f : p->counter_files) (void)tf_report_set_counters(out, &p->hw, f.c_str(), name);   // (a pass without this kernel adds nothing)
+  }
   return TF_OK;
 }
 
@@ -1135,6 +1143,45 @@ extern "C" void tf_problem_destroy(tf_problem* p) {
   if (!p) return;
   if (p->own_ws) (void)hipFree(p->own_ws);
   delete p;
+}
+
+extern "C" int32_t tf_variant_kernel_name(const tf_variant_desc* v, char* buf, int32_t cap) {
+  if (!v || !buf || cap < 1) return fail(TF_E_INVALID, "null argument");
+  auto b = [](int x) { return x ? "true" : "false"; };
+  char cfg[128];
+  int n = 0;
+  switch (v->kind) {
+    case TF_KIND_NAIVE: n = snprintf(buf, cap, "tf_gemm_naive_kernel"); break;
+    case TF_KIND_MFMA_DIRECT: n = snprintf(buf, cap, "tf_gemm_mfma_direct_kernel"); break;
+    case TF_KIND_MFMA_LDS:
+      snprintf(cfg, sizeof(cfg), "tf::LdsCfg<%d, %d, %d, %d, %d, %d, %s, %s, %d, %s, %s, %d>", v->bm, v->bn, v->bk, v->waves_m,
+               v->waves_n, v->stages, b(v->direct_to_lds), b(v->a_bypass_lds), v->waves_k, b(v->trans_a), b(v->trans_b), v->bn);
+      n = snprintf(buf, cap, "%s%s", v->bn_tail ? "tf_gemm_mixed_kernel<" : v->persistent ? "tf_bgemm_persist_kernel<"
+                                     : v->stream_k ? "tf_gemm_lds_kernel<tf::StreamKCfg<" : "tf_gemm_lds_kernel<", cfg);
+      break;
+    case TF_KIND_MFMA_STREAM:
+      n = snprintf(buf, cap, "tf_gemm_stream_kernel<tf::StreamCfg<%d, %d, %d, %d>", v->bm / 16, v->waves_k, v->stages, v->bn / 16);
+      break;
+    case TF_KIND_VECMAT_NAIVE: n = snprintf(buf, cap, "tf_vecmat_naive_kernel"); break;
+    case TF_KIND_BGEMM_TN_NAIVE: n = snprintf(buf, cap, "tf_bgemm_tn_naive_kernel"); break;
+    default: buf[0] = 0; return 0;       // kernels whose template arguments the descriptor does not spell out
+  }
+  if (n < 0 || n >= cap) return fail(TF_E_RANGE, "kernel name needs %d bytes", n + 1);
+  return n;
+}
+
+extern "C" tf_status tf_problem_set_counter_files(tf_problem* p, const char* const* csv_paths, int32_t n) {
+  if (!p || n < 0 || n > 16 || (n > 0 && !csv_paths)) return fail(TF_E_INVALID, "0..16 counter files");
+  std::vector<std::string> files;
+  for (int i = 0; i < n; ++i) {
+    if (!csv_paths[i]) return fail(TF_E_INVALID, "null path");
+    FILE* f = fopen(csv_paths[i], "r");
+    if (!f) return fail(TF_E_INVALID, "cannot open %s", csv_paths[i]);
+    fclose(f);
+    files.emplace_back(csv_paths[i]);
+  }
+  p->counter_files.swap(files);
+  return TF_OK;
 }
 
 extern "C" int32_t tf_variant_enumerate(const tf_problem* p, tf_variant_desc* out, int32_t cap) {

@@ -101,6 +101,8 @@ SIGNATURES = {
     "tf_gate_count_bad": (C.c_int64, [C.c_void_p, C.c_int64, _P(C.c_float), _P(C.c_float), _P(C.c_float), C.c_int64,
                                       C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "tf_report_set_counters": (C.c_int32, [_P(Report), _P(Hw), C.c_char_p, C.c_char_p]),
+    "tf_variant_kernel_name": (C.c_int32, [_P(VariantDesc), C.c_char_p, C.c_int32]),
+    "tf_problem_set_counter_files": (C.c_int32, [C.c_void_p, _P(C.c_char_p), C.c_int32]),
     "tf_arbiter": (C.c_int32, [_P(Report), _P(Report), _P(Theta), C.c_int32, C.c_int32, C.c_int32]),
     "tf_refine_hint": (C.c_int32, [_P(Report), _P(Report), _P(Hw)]),
     "tf_proposal": (C.c_int32, [_P(ProblemDesc), _P(Hw), _P(VariantDesc), C.c_int32, _P(C.c_uint8), C.c_int32,
@@ -293,24 +295,11 @@ def gate_count_bad(Y, zref, norm_a, norm_b, K: int, epi: int, norm_b_row_stride:
 def kernel_substr(v: VariantDesc):
     """The part of the kernel's name in a profiler's output that identifies the compiled kernel behind variant v
     (variants that differ only in launch parameters, such as K slices or the K order, share a kernel), or None."""
-    b = lambda x: "true" if x else "false"
-    if v.kind == TF_KIND_NAIVE:
-        return "tf_gemm_naive_kernel"
-    if v.kind == TF_KIND_MFMA_DIRECT:
-        return "tf_gemm_mfma_direct_kernel"
-    if v.kind == TF_KIND_MFMA_LDS:
-        cfg = "tf::LdsCfg<%d, %d, %d, %d, %d, %d, %s, %s, %d, %s, %s, %d>" % (v.bm, v.bn, v.bk, v.waves_m, v.waves_n, v.stages, b(v.direct_to_lds),
-                                                                         b(v.a_bypass_lds), v.waves_k, b(v.trans_a), b(v.trans_b), v.bn)
-        if v.bn_tail:
-            return "tf_gemm_mixed_kernel<" + cfg
-        if v.persistent:
-            return "tf_bgemm_persist_kernel<" + cfg
-        if v.stream_k:
-            return "tf_gemm_lds_kernel<tf::StreamKCfg<" + cfg
-        return "tf_gemm_lds_kernel<" + cfg
-    if v.kind == TF_KIND_MFMA_STREAM:
-        return "tf_gemm_stream_kernel<tf::StreamCfg<%d, %d, %d, %d>" % (v.bm // 16, v.waves_k, v.stages, v.bn // 16)
-    return None
+    buf = C.create_string_buffer(256)
+    n = lib().tf_variant_kernel_name(C.byref(v), buf, 256)
+    if n < 0:
+        _check(int(n))
+    return buf.value.decode() if n > 0 else None
 
 
 def report_set_counters(report: Report, hw: Hw, csv_path: str, kernel_substr: str) -> None:
@@ -375,6 +364,11 @@ class Problem:
     def run_static(self, variant_id, A, B, bias, Y, stream=None):
         """tf_variant_run on the workspace that is part of the library's device image: allocates nothing."""
         _check(lib().tf_variant_run_static(self._h, variant_id, _ptr(A), _ptr(B), _ptr(bias), _ptr(Y), _stream(stream)))
+
+    def set_counter_files(self, paths):
+        """Profiler counter CSVs of earlier passes: tune() then attaches them to every round's report before the hint."""
+        arr = (C.c_char_p * max(1, len(paths)))(*[p.encode() for p in paths])
+        _check(lib().tf_problem_set_counter_files(self._h, arr, len(paths)))
 
     def workspace_status(self, workspace=None, stream=None):
         """Synchronises the stream; raises TfError(TF_E_LAUNCH) if an L2-local reduction reported a misplaced slice."""

@@ -103,3 +103,65 @@ def test_counter_file_errors(tmp_path):
     r = blank_report(t_med_us=100.0)
     tf.report_set_counters(r, hw, str(plain), "LdsCfg<128, 128, 2, 4>")
     assert r.hbm_write_gbs == pytest.approx(2000.0 * 1024 / 100.0 * 1e-3, rel=1e-9)
+
+
+LOOP_SQ_C3 = os.path.join(G, "rocprofv3_pmc_sq_loop_C3.csv")
+
+
+def kernels_in(path):
+    import csv
+    with open(path, newline="") as f:
+        return sorted({r["Kernel_Name"] for r in csv.DictReader(f)})
+
+
+def test_kernel_name_of_a_variant_finds_its_rows_in_profiler_output():
+    """rocprofv3_pmc_sq_loop_C3.csv: one dispatch each of five kernels from a profiler pass over the loop on
+    4096 x 11008 x 4096. tf_variant_kernel_name must lead every variant to the rows of its own compiled kernel and
+    to no other's."""
+    kernels = kernels_in(LOOP_SQ_C3)
+    assert len(kernels) == 5
+    hw = tf.hw_nominal()
+    with tf.Problem(4096, 11008, 4096) as p:
+        vs = {v.name.decode(): v for v in p.variants()}
+    expect = {
+        "naive_1elem_per_thread": "tf_gemm_naive_kernel",
+        "lds_256x256x64_w2x4_s2_direct_tail192_sk1x": "tf_gemm_mixed_kernel<tf::LdsCfg<256, 256, 64, 2, 4, 2, true, false, 1, false, false, 256>",
+        "lds_256x256x64_w2x4_s2_direct_sk1": "tf_gemm_lds_kernel<tf::LdsCfg<256, 256, 64, 2, 4, 2, true, false, 1, false, false, 256>",
+        "lds_256x256x32_w2x4_s4_direct_sk1x": "tf_gemm_lds_kernel<tf::LdsCfg<256, 256, 32, 2, 4, 4, true, false, 1, false, false, 256>",
+        "lds_256x128x64_w4x2_s3_direct_sk1": "tf_gemm_lds_kernel<tf::LdsCfg<256, 128, 64, 4, 2, 3, true, false, 1, false, false, 128>",
+    }
+    for name, sub in expect.items():
+        got = tf.kernel_substr(vs[name])
+        assert got == sub
+        hits = [k for k in kernels if got in k]
+        assert len(hits) == 1, (name, hits)
+        r = blank_report()
+        tf.report_set_counters(r, hw, LOOP_SQ_C3, got)
+        assert r.have_counters == 1 and r.achieved_occupancy_pct > 0
+        assert (r.mfma_busy_pct == 0.0) == (name == "naive_1elem_per_thread")
+    # the rotated K order is a run-time argument of the same kernel; a kernel that is not in the file is not found
+    assert tf.kernel_substr(vs["lds_256x256x64_w2x4_s2_direct_sk1x"]) == tf.kernel_substr(vs["lds_256x256x64_w2x4_s2_direct_sk1"])
+    other = tf.kernel_substr(vs["lds_128x128x64_w2x4_s3_direct_sk1"])
+    assert not [k for k in kernels if other in k]
+    with pytest.raises(tf.TfError):
+        tf.report_set_counters(blank_report(), hw, LOOP_SQ_C3, other)
+    # every variant of the family has a kernel name, and different compiled kernels have different names
+    subs = {}
+    for v in vs.values():
+        s = tf.kernel_substr(v)
+        assert s, v.name
+        key = (v.kind, v.bm, v.bn, v.bk, v.waves_m, v.waves_n, v.waves_k, v.stages, v.direct_to_lds, v.a_bypass_lds, v.bn_tail > 0, v.stream_k)
+        subs.setdefault(s, set()).add(key)
+    assert all(len(k) == 1 for k in subs.values())
+    # the large-tile kernel in steady state: 4096 MFMAs per SIMD and tile, 2.69 tiles per CU, hand-computed from the rows
+    r = blank_report()
+    tf.report_set_counters(r, hw, LOOP_SQ_C3, expect["lds_256x256x64_w2x4_s2_direct_tail192_sk1x"])
+    assert 55.0 < r.mfma_busy_pct < 70.0 and 1.0 < r.lds_bank_conflict_pct < 3.0
+
+
+def test_counter_files_handed_to_a_problem_are_checked():
+    with tf.Problem(256, 256, 256) as p:
+        p.set_counter_files([SQ_C3, TCC_C3])
+        p.set_counter_files([])
+        with pytest.raises(tf.TfError):
+            p.set_counter_files([os.path.join(G, "no_such_file.csv")])

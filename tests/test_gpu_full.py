@@ -95,6 +95,40 @@ def test_full_size_every_element_against_the_whole_oracle(name):
     assert checked >= 6
 
 
+def test_tune_attaches_the_profilers_counters_to_its_rounds():
+    """The loop on C3 with a profiler pass handed in (tests/golden/rocprofv3_pmc_sq_loop_C3.csv: one dispatch each of
+    the baseline kernel and of four tile kernels): the reports of the rounds whose kernel the file holds carry its
+    counters when the hint is taken, the others do not."""
+    import os
+    torch = gu.torch_mod()
+    w = wl.WORKLOADS["C3"]
+    A, B, bias = inputs("C3")
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
+    Y = torch.empty((w.M, w.N), dtype=torch.bfloat16, device="cuda")
+    fixture = os.path.join(os.path.dirname(__file__), "golden", "rocprofv3_pmc_sq_loop_C3.csv")
+    held = ("tf_gemm_naive_kernel", "tf_gemm_mixed_kernel<tf::LdsCfg<256, 256, 64, 2, 4, 2,", "tf_gemm_lds_kernel<tf::LdsCfg<256, 256, 32, 2, 4, 4,",
+            "tf_gemm_lds_kernel<tf::LdsCfg<256, 128, 64, 4, 2, 3,", "tf_gemm_lds_kernel<tf::LdsCfg<256, 256, 64, 2, 4, 2,")
+    with tf.Problem(w.M, w.N, w.K) as prob:
+        vs = prob.variants()
+        prob.set_counter_files([fixture])
+        best, rep, log = prob.tune(dA, dB, dbias, Y)
+        assert log[0].variant_id == 0 and log[0].have_counters == 1 and log[0].mfma_busy_pct == 0.0
+        seen = 0
+        for r in log[1:]:
+            name = tf.kernel_substr(vs[r.variant_id])
+            in_file = any(name.startswith(h) for h in held)
+            print(vs[r.variant_id].name.decode(), "counters" if r.have_counters else "-", "%.1f" % r.mfma_busy_pct, flush=True)
+            assert r.have_counters == (1 if in_file else 0)
+            if in_file:
+                seen += 1
+                assert 40.0 < r.mfma_busy_pct < 75.0 and r.achieved_occupancy_pct > 15.0
+                assert r.bottleneck in (tf.TF_BN_LATENCY, tf.TF_BN_OCCUPANCY)     # pipes 50-65 % busy: not "MFMA-bound"
+        assert seen >= 1          # the first proposal on this shape is a large-tile kernel
+        prob.set_counter_files([])
+        best2, rep2, log2 = prob.tune(dA, dB, dbias, Y)
+        assert all(r.have_counters == 0 for r in log2)
+
+
 def test_tune_on_gpu_c1_and_c2():
     torch = gu.torch_mod()
     for name in ("C1", "C2"):

@@ -17,20 +17,27 @@ def pick(prob, pred):
     return vs[0]
 
 
-@pytest.mark.parametrize("which", ["plain", "split_two_kernel", "split_in_kernel", "stream"])
+@pytest.mark.parametrize("which", ["plain", "split_two_kernel", "split_in_kernel", "split_l2_local", "stream", "b_as_nk_staged",
+                                   "b_as_nk_transposing_pass"])
 def test_captured_launches_replay_to_the_eager_result(which):
     torch = gu.torch_mod()
     M, N, K = (16, 512, 4096) if which == "stream" else (256, 256, 2048)
     A, B, bias = wl.make_custom(M, N, K, seed=7)
+    nk = which.startswith("b_as_nk")
+    if nk:
+        B = np.ascontiguousarray(B.T)
     dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
     Y_eager = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
     Y_graph = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
-    with tf.Problem(M, N, K) as prob:
+    with tf.Problem(M, N, K, trans_b=1 if nk else 0) as prob:
         v = pick(prob, {
             "plain": lambda v: v.kind == tf.TF_KIND_MFMA_LDS and v.split_k == 1,
             "split_two_kernel": lambda v: v.kind == tf.TF_KIND_MFMA_LDS and v.split_k > 1 and v.fused_reduce == 0,
             "split_in_kernel": lambda v: v.kind == tf.TF_KIND_MFMA_LDS and v.split_k > 1 and v.fused_reduce == 1,
+            "split_l2_local": lambda v: v.kind == tf.TF_KIND_MFMA_LDS and v.split_k > 1 and v.fused_reduce == 2,
             "stream": lambda v: v.kind == tf.TF_KIND_MFMA_STREAM and v.split_k > 1,
+            "b_as_nk_staged": lambda v: v.kind == tf.TF_KIND_MFMA_LDS and v.trans_b == 1,
+            "b_as_nk_transposing_pass": lambda v: b"_pretransB_" in v.name,
         }[which])
         print(which, v.name.decode(), flush=True)
         prob.run(v.id, dA, dB, dbias, Y_eager)                  # eager: first use allocates and sets attributes
