@@ -39,6 +39,7 @@ struct VariantImpl {
   size_t counter_bytes;   // leading part of the workspace
   int sk_first, sk_tiles; // stream-K: tiles computed whole (= first shared work-group), tiles whose K steps are shared
   int mix_tiles, mix_blocks;   // lighter last round: its tiles per row panel, the blocks of 32 columns they share (tiles_n = tile columns of the wide part)
+  size_t aux_off;         // B given as [N][K] behind a transposing pass: where B^T lies in the workspace (behind the family's counter area)
 };
 
 }  // namespace
@@ -400,6 +401,11 @@ void build_family(tf_problem* p) {
       const size_t slices = p->family[i].stream_k ? 2 : (size_t)p->family[i].split_k;
       p->impl[i].counter_bytes = maxc;
       p->family[i].workspace_bytes = (int64_t)(maxc + slices * d.M * d.N * 4);
+    } else if (d.trans_b && p->family[i].kind == TF_KIND_MFMA_LDS && !p->family[i].trans_b) {
+      // the transposed copy of B lies behind the counters and the status word, which other variants of the
+      // family keep in the same buffer
+      p->impl[i].aux_off = maxc;
+      p->family[i].workspace_bytes += (int64_t)maxc;
     }
   }
 }
@@ -559,9 +565,9 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
         return fail(TF_E_UNSUPPORTED, "workspace of %zu bytes, variant %s needs %lld", ws_bytes, v.name, (long long)v.workspace_bytes);
       if ((uintptr_t)ws & 255u) return fail(TF_E_UNSUPPORTED, "workspace must be 256-byte aligned");
       // B is [N][ldb]: N rows of K -> [K][N]
-      tf::launch_transpose(g.B, (uint16_t*)ws, d.N, d.K, d.ldb, 0, d.N, 0, 1, stream);
-      g.B = (const uint16_t*)ws; g.ldb = d.N;
-      if (p->zeroed_ws == ws) { p->zeroed_ws = nullptr; p->zeroed_bytes = 0; }     // the counter area of this buffer has been written over
+      uint16_t* bt = (uint16_t*)((char*)ws + im.aux_off);
+      tf::launch_transpose(g.B, bt, d.N, d.K, d.ldb, 0, d.N, 0, 1, stream);
+      g.B = bt; g.ldb = d.N;
     }
     if (v.bn_tail > 0) {
       g.mix_main_wgs = im.tiles_m * im.tiles_n; g.mix_tiles = im.mix_tiles; g.mix_blocks = im.mix_blocks;

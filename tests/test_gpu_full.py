@@ -35,17 +35,21 @@ def tile_shape(v):
             v.stream_k)
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
-def test_full_size_every_element_against_the_whole_oracle(name):
+@pytest.mark.parametrize("name,b_as_nk", [("C2", False), ("C3", False), ("C4", False), ("C5", False), ("C2", True), ("C4", True)])
+def test_full_size_every_element_against_the_whole_oracle(name, b_as_nk):
     """Every element of the output at the full size of the workload, in the launch configuration the benchmark
     times, against the whole oracle (run unchanged on disjoint row blocks from the host's cores): the strict
     a-priori bound for the bf16 epilogue, the summation bound for the fp32 pre-activation. C2, C4, C5: every
     variant; C3 (45 M outputs, a launch of the baseline kernel takes 0.1 s): the kernel the loop selects, one
-    variant per compiled tile kernel, and the baseline."""
+    variant per compiled tile kernel, and the baseline. b_as_nk: the same numbers with B handed over as [N][K], against
+    the oracle written for that layout (every variant: the kernels that stage B as it lies, the transposing pass ahead
+    of an ordinary kernel, the unstaged kernels)."""
     torch = gu.torch_mod()
     w = wl.WORKLOADS[name]
     A, B, bias = inputs(name)
-    y, z, s = gu.oracle_parallel(A, B, bias)
+    if b_as_nk:
+        B = np.ascontiguousarray(B.T)
+    y, z, s = gu.oracle_parallel(A, B, bias, trans_b=b_as_nk)
     print(name, "oracle done", flush=True)
     dA, dB, dbias = gu.to_dev(A), gu.to_dev(B), gu.to_dev(bias)
     # the bounds, evaluated once in float64 on the device (test arithmetic, not the library's)
@@ -58,8 +62,10 @@ def test_full_size_every_element_against_the_whole_oracle(name):
     checked = 0
     for epi, f32 in ((tf.TF_EPI_BIAS_GELU_ERF, False), (tf.TF_EPI_NONE_F32, True)):
         Y = torch.empty((w.M, w.N), dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
-        with tf.Problem(w.M, w.N, w.K, epi=epi) as prob:
+        with tf.Problem(w.M, w.N, w.K, epi=epi, trans_b=1 if b_as_nk else 0) as prob:
             vs = prob.variants()
+            if b_as_nk:
+                assert any(v.trans_b for v in vs) and any(b"_pretransB_" in v.name for v in vs)
             if name == "C3":
                 best, rep, log = prob.tune(dA, dB, dbias, Y)
                 todo, seen = [vs[best]], {tile_shape(vs[best])}

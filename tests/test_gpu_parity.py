@@ -49,6 +49,9 @@ def check_all_variants(M, N, K, A, B, bias, lda=None, ldb=None, ldy=None, only=N
                     bound = gu.strict_bound(y, z, s, K)
                     assert np.all(err <= bound), "%s: worst excess %g" % (name, (err - bound).max())
                 ran.append(name)
+                # whatever ran last (a transposing pass into the workspace, a reduction that left its counters
+                # behind), the status word of the workspace must still read "no misplaced slice"
+                prob.workspace_status()
     return ran
 
 
