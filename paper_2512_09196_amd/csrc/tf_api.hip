@@ -258,7 +258,7 @@ void build_family(tf_problem* p) {
     if (k.bn_tail > 0) {
       // a lighter last round: the row panels must take a whole number of CUs each, the leading columns make whole
       // rounds of wide tiles, and what remains is between (bn_tail - 64) and bn_tail columns per CU of a row panel
-      if (pass != 0 || tb || k.lds_bytes > p->hw.lds_bytes_per_cu) continue;
+      if (pass != 0 || k.lds_bytes > p->hw.lds_bytes_per_cu) continue;      // (pass 0 has already matched the kernel's B layout to the problem's)
       const long tm = cdivl(d.M, k.bm);
       if (tm > cus || cus % tm != 0) continue;
       const long c = cus / tm, nb = cdivl(d.N, 32), wide = k.bn / 32, tail = k.bn_tail / 32;
@@ -269,15 +269,15 @@ void build_family(tf_problem* p) {
         memset(&v, 0, sizeof(v));
         v.k_rotate = kr;
         v.kind = TF_KIND_MFMA_LDS; v.bm = k.bm; v.bn = k.bn; v.bk = k.bk; v.waves_m = k.waves_m; v.waves_n = k.waves_n; v.waves_k = k.waves_k;
-        v.stages = k.stages; v.split_k = 1; v.direct_to_lds = 1; v.xcd_swizzle = 1; v.bn_tail = k.bn_tail;
+        v.stages = k.stages; v.split_k = 1; v.direct_to_lds = 1; v.xcd_swizzle = 1; v.bn_tail = k.bn_tail; v.trans_b = k.trans_b;
         v.group_m = (int32_t)std::min<long>(tm, 8);
         v.threads = k.threads; v.lds_bytes = k.lds_bytes;
         v.grid = (int32_t)(cus * rounds + cus);
         VariantImpl im{};
         im.lds_index = i; im.ktiles_per_split = (int)ktiles; im.tiles_m = (int)tm; im.tiles_n = (int)(c * rounds);
         im.mix_tiles = (int)c; im.mix_blocks = (int)rest;
-        snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d_s%d_direct_tail%d_sk1%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n, k.stages,
-                 k.bn_tail, kr ? "x" : "");
+        snprintf(v.name, sizeof(v.name), "lds_%dx%dx%d_w%dx%d_s%d_direct%s_tail%d_sk1%s", k.bm, k.bn, k.bk, k.waves_m, k.waves_n, k.stages,
+                 k.trans_b ? "_bnk" : "", k.bn_tail, kr ? "x" : "");
         add_variant(p, v, im);
       }
       continue;

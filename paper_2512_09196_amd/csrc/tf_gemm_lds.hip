@@ -1480,6 +1480,7 @@ using N256x128_w8 = LdsCfg<256, 128, 64, 4, 2, 3, true, false, 1, false, true>;
 using N128x256_w8 = LdsCfg<128, 256, 64, 2, 4, 3, true, false, 1, false, true>;
 // the big tile with only 192 of its 256 columns multiplied (4 x 2 waves of 64 x 96): the lighter last round
 using K256x192_w8b = LdsCfg<256, 256, 64, 4, 2, 2, true, false, 1, false, false, 192>;
+using N256x192_w8b = LdsCfg<256, 256, 64, 4, 2, 2, true, false, 1, false, true, 192>;     // the same with B staged as [n][k]
 
 static LdsKernelInfo g_table[] = {
     make_info<K256x128_d2>(), make_info<K128x256_d2>(),
@@ -1503,6 +1504,7 @@ static LdsKernelInfo g_table[] = {
     make_info<N128x128_d2>(), make_info<N128x128x128>(), make_info<N64x64_d3>(), make_info<N32x64_d4>(),
     make_info<N32x128_d3>(), make_info<N32x32_d4>(), make_info<N256x128_w8>(), make_info<N128x256_w8>(),
     make_mixed_info<K256x256_w8a, K256x192_w8b>(), make_mixed_info<K256x256_w8b, K256x192_w8b>(),
+    make_mixed_info<N256x256_w8a, N256x192_w8b>(), make_mixed_info<N256x256_w8b, N256x192_w8b>(),
 };
 
 int lds_kernel_count() { return (int)(sizeof(g_table) / sizeof(g_table[0])); }

@@ -461,3 +461,29 @@ def test_launch_with_a_lighter_last_round(shape):
     A, B, bias = wl.make_custom(M, N, K, seed=78)
     ran = check_all_variants(M, N, K, A, B, bias, only=lambda v: v.bn_tail > 0)
     assert len(ran) >= 4
+
+
+@pytest.mark.parametrize("shape", [(2048, 13824, 128), (2024, 13784, 64)])
+def test_launch_with_a_lighter_last_round_b_given_as_n_by_k(shape):
+    # the same launch with B handed over as [N][K] and staged as it lies: integer operands bit for bit, then the bf16
+    # epilogue against the oracle written for that layout
+    M, N, K = shape
+    A = wl.small_int_bf16(77, 0, (M, K))
+    Bt = np.ascontiguousarray(wl.small_int_bf16(77, 1, (K, N)).T)
+    bias = wl.small_int_bf16(77, 2, (N,), -3, 3)
+    _, z, _ = orc.gemm_nt_bias_gelu(A, Bt, bias)
+    zf = z.astype(np.float32)
+    assert np.array_equal(zf.astype(np.float64), z)
+    dA, dB, dbias = gu.to_dev(A), gu.to_dev(Bt), gu.to_dev(bias)
+    out = gu.OutBuf(M, N, f32=True)
+    with tf.Problem(M, N, K, epi=tf.TF_EPI_NONE_F32, trans_b=1) as prob:
+        tail = [v for v in prob.variants() if v.bn_tail]
+        assert len(tail) >= 2 and all(v.grid % 256 == 0 and v.bn_tail == 192 and v.trans_b == 1 and b"_bnk_" in v.name for v in tail)
+        for v in tail:
+            print("tail", shape, v.name.decode(), flush=True)
+            _, intact, raw = gu.run_variant(prob, v.id, dA, dB, dbias, out)
+            assert intact
+            assert np.array_equal(raw, zf), v.name.decode()
+    A, B, bias = wl.make_custom(M, N, K, seed=78)
+    ran = check_all_variants(M, N, K, A, np.ascontiguousarray(B.T), bias, only=lambda v: v.bn_tail > 0, trans_b=True)
+    assert len(ran) >= 4
