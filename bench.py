@@ -46,6 +46,11 @@ FETCH_SCALE, WRITE_SCALE = 262144.0 / 131084.9, 1.0
 TRAFFIC_SOURCE = "recorded: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, see profiles/"
 HBM_TRAFFIC_KIB = {
     ("C3", "lds_256x256x64_w2x4_s2_direct_tail192_sk1x"): (305585.0, 89131.7),
+    # the same compiled kernel with the plain K order, and the 4 x 2 wave arrangement (profiles/variant_loop_C3_...: the
+    # FETCH_SIZE and WRITE_SIZE passes of the loop with --also-launch hold every large-tile kernel)
+    ("C3", "lds_256x256x64_w2x4_s2_direct_tail192_sk1"): (305580.4, 89412.7),
+    ("C3", "lds_256x256x64_w4x2_s2_direct_tail192_sk1x"): (305593.8, 89317.6),
+    ("C3", "lds_256x256x64_w4x2_s2_direct_tail192_sk1"): (305593.8, 89317.6),
     ("C2", "lds_128x128x64_w2x4_s3_direct_sk1x"): (24699.8, 8192.0),
     ("C4", "lds_32x64x64_w1x2_s4_direct_sk2l"): (67547.7, 1290.9),
     ("C5", "lds_256x128x64_w4x2_s3_direct_sk8r"): (32862.6 + 16419.2, 32768.0 + 2048.0),     # main kernel + reduce kernel
