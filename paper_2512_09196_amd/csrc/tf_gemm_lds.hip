@@ -63,7 +63,7 @@ struct LdsCfg {
   static constexpr int TM = WTM / 32, TN = WTN / 32;       // 32x32 MFMA blocks per wave
   static constexpr int A_BYTES = ABYPASS ? 0 : BM * BK * 2, B_BYTES = BK * BN * 2;
   static_assert(!ABYPASS || (WN == 1 && DIRECT && STAGES == 2 && WK_ == 1 && BK == 64 && !TRANSB_), "A bypass: one wave column, direct B staging, two buffers, K tile of 64");
-  static_assert(DIRECT || (BK == 64 && !TRANSB_), "register staging: K tile of 64, B row-major");
+  static_assert(DIRECT || BK == 64, "register staging: K tile of 64");
   static_assert(!TRANSB_ || !TRANSA_, "one transposed operand at a time");
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int RING_BYTES = STAGES * STAGE_BYTES;
@@ -1477,6 +1477,10 @@ using N32x64_d4    = LdsCfg< 32,  64, 64, 1, 2, 4, true, false, 1, false, true>;
 using N32x128_d3   = LdsCfg< 32, 128, 64, 1, 4, 3, true, false, 1, false, true>;
 using N32x32_d4    = LdsCfg< 32,  32, 64, 1, 1, 4, true, false, 1, false, true>;
 using N256x128_w8 = LdsCfg<256, 128, 64, 4, 2, 3, true, false, 1, false, true>;
+// staged through registers: a ragged K tail is filled with zeros (K no multiple of the K tile)
+using N128x128_r2 = LdsCfg<128, 128, 64, 2, 2, 2, false, false, 1, false, true>;
+using N64x64_r2   = LdsCfg< 64,  64, 64, 2, 2, 2, false, false, 1, false, true>;
+using N32x128_r2  = LdsCfg< 32, 128, 64, 1, 4, 2, false, false, 1, false, true>;
 using N128x256_w8 = LdsCfg<128, 256, 64, 2, 4, 3, true, false, 1, false, true>;
 // the big tile with only 192 of its 256 columns multiplied (4 x 2 waves of 64 x 96): the lighter last round
 using K256x192_w8b = LdsCfg<256, 256, 64, 4, 2, 2, true, false, 1, false, false, 192>;
@@ -1505,6 +1509,7 @@ static LdsKernelInfo g_table[] = {
     make_info<N32x128_d3>(), make_info<N32x32_d4>(), make_info<N256x128_w8>(), make_info<N128x256_w8>(),
     make_mixed_info<K256x256_w8a, K256x192_w8b>(), make_mixed_info<K256x256_w8b, K256x192_w8b>(),
     make_mixed_info<N256x256_w8a, N256x192_w8b>(), make_mixed_info<N256x256_w8b, N256x192_w8b>(),
+    make_info<N128x128_r2>(), make_info<N64x64_r2>(), make_info<N32x128_r2>(),
 };
 
 int lds_kernel_count() { return (int)(sizeof(g_table) / sizeof(g_table[0])); }

@@ -393,11 +393,12 @@ def test_b_given_as_n_by_k_strided_ragged_k_and_exact():
     A, Bt, bias = make_nk(M, N, K, seed=317)
     ran = check_all_variants(M, N, K, A, Bt, bias, lda=K + 24, ldb=K + 8, ldy=N + 16, trans_b=True)
     assert any("_bnk_" in n for n in ran)
-    # K not a multiple of the K tile: only the unstaged kernels can run it
+    # K not a multiple of the K tile: the kernels that stage through registers fill the tail with zeros; the direct
+    # path is not offered
     M, N, K = 70, 80, 200
     A, Bt, bias = make_nk(M, N, K, seed=318)
     ran = check_all_variants(M, N, K, A, Bt, bias, trans_b=True)
-    assert "naive_1elem_per_thread" in ran and not any(n.startswith("lds_") for n in ran)
+    assert "naive_1elem_per_thread" in ran and any("_regs_bnk_" in n for n in ran) and not any(n.startswith("lds_") and "_direct" in n for n in ran)
     # integer operands: every partial sum is exact in fp32, so the pre-activation must equal the oracle bit for bit
     for (M, N, K) in ((192, 320, 1024), (130, 264, 4096), (32, 128, 2048)):
         A = wl.small_int_bf16(43, 0, (M, K))
@@ -487,3 +488,23 @@ def test_launch_with_a_lighter_last_round_b_given_as_n_by_k(shape):
     A, B, bias = wl.make_custom(M, N, K, seed=78)
     ran = check_all_variants(M, N, K, A, np.ascontiguousarray(B.T), bias, only=lambda v: v.bn_tail > 0, trans_b=True)
     assert len(ran) >= 4
+
+
+def test_seeded_random_shapes_every_variant_both_layouts():
+    # shapes drawn from a fixed seed: M anything, N and K multiples of 8 (what the tile kernels accept), sizes that
+    # span one to several tiles of every tile shape with ragged last tiles in all three dimensions
+    rng = np.random.default_rng(20251209)
+    total = 0
+    for case in range(10):
+        M = int(rng.integers(1, 600))
+        N = 8 * int(rng.integers(1, 80))
+        K = 8 * int(rng.integers(1, 160))
+        trans_b = bool(case % 2)
+        A, B, bias = wl.make_custom(M, N, K, seed=500 + case)
+        if trans_b:
+            B = np.ascontiguousarray(B.T)
+        ran = check_all_variants(M, N, K, A, B, bias, trans_b=trans_b)
+        assert len(ran) >= 4
+        total += len(ran)
+    print("variants checked:", total, flush=True)
+    assert total >= 200
