@@ -84,11 +84,16 @@ def refine_hint(r_prev, r_new, hw):
         return UNKNOWN
     c = classify(r_new, hw)
     if (r_prev is not None and r_prev["status"] == 0 and r_prev["t_med_us"] > 0
-            and r_new["t_med_us"] > 1.02 * r_prev["t_med_us"] and classify(r_prev, hw) == c):
-        if c == OCCUPANCY:
-            c = LATENCY
-        elif c == LATENCY:
-            c = OCCUPANCY
+            and r_new["t_med_us"] > 1.02 * r_prev["t_med_us"]):
+        # the hint r_new was proposed under: the one the previous report carries
+        followed = r_prev.get("bottleneck", UNKNOWN)
+        if followed == UNKNOWN:
+            followed = classify(r_prev, hw)
+        if followed == c:
+            if c == OCCUPANCY:
+                c = LATENCY
+            elif c == LATENCY:
+                c = OCCUPANCY
     return c
 
 

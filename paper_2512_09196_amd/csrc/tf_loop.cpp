@@ -67,14 +67,18 @@ extern "C" int32_t tf_refine_hint(const tf_report* prev, const tf_report* cand, 
   if (!cand || !hw) return TF_BN_UNKNOWN;
   if (cand->status != TF_OK || cand->t_med_us <= 0.0) return TF_BN_UNKNOWN;
   int c = classify(cand, hw);
-  // The delta against the previous report: when the last step made things slower and the
-  // diagnosis did not change, the remedy for that diagnosis has just failed; swap between the
-  // two "nothing is saturated" diagnoses so the next proposal goes the other way (the
-  // tile-size versus resident-work-groups trade-off of Case Study 3).
-  if (prev && prev->status == TF_OK && prev->t_med_us > 0.0 && cand->t_med_us > 1.02 * prev->t_med_us &&
-      classify(prev, hw) == c) {
-    if (c == TF_BN_OCCUPANCY) c = TF_BN_LATENCY;
-    else if (c == TF_BN_LATENCY) c = TF_BN_OCCUPANCY;
+  // The delta against the previous report: the candidate was proposed under the hint the previous report
+  // carries (its bottleneck field; a report without one is read by its own figures). When that step made
+  // things slower and the candidate's figures call for the same remedy again, the remedy has just failed:
+  // swap between the two "nothing is saturated" diagnoses so that the next proposal goes the other way.
+  // This reproduces the hints behind the rounds of Case Study 3 (Sec. 5): coalescing / staging, then lower
+  // register use, then deeper pipelining, then less shared memory per work-group, each after a slower round.
+  if (prev && prev->status == TF_OK && prev->t_med_us > 0.0 && cand->t_med_us > 1.02 * prev->t_med_us) {
+    const int followed = prev->bottleneck != TF_BN_UNKNOWN ? prev->bottleneck : classify(prev, hw);
+    if (followed == c) {
+      if (c == TF_BN_OCCUPANCY) c = TF_BN_LATENCY;
+      else if (c == TF_BN_LATENCY) c = TF_BN_OCCUPANCY;
+    }
   }
   return c;
 }

@@ -12,7 +12,7 @@ from paper_2512_09196_amd import tf
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "case_study3_rounds.txt")
 REPORT_KEYS = ["status", "parity_ok", "t_med_us", "t_min_us", "grid_fill", "arithmetic_intensity", "pct_mfma_peak",
                "pct_hbm_peak", "occupancy_pct", "have_counters", "mfma_busy_pct", "hbm_read_gbs", "hbm_write_gbs",
-               "lds_bank_conflict_pct"]
+               "lds_bank_conflict_pct", "bottleneck"]
 VARIANT_KEYS = ["kind", "bm", "bn", "bk", "stages", "split_k", "direct_to_lds", "lds_bytes", "grid"]
 
 
@@ -45,7 +45,8 @@ def rand_report(rng):
                 arithmetic_intensity=rng.choice([16.0, 85.0, 500.0, 1700.0]), pct_mfma_peak=rng.uniform(0, 95),
                 pct_hbm_peak=rng.uniform(0, 95), occupancy_pct=rng.choice([12.5, 25.0, 37.5, 50.0]),
                 have_counters=rng.randint(0, 1), mfma_busy_pct=rng.uniform(0, 100), hbm_read_gbs=rng.uniform(0, 6000),
-                hbm_write_gbs=rng.uniform(0, 2000), lds_bank_conflict_pct=rng.uniform(0, 12))
+                hbm_write_gbs=rng.uniform(0, 2000), lds_bank_conflict_pct=rng.uniform(0, 12),
+                bottleneck=rng.choice([0, 0, 1, 2, 3, 4, 5, 5, 6, 6]))       # the hint the report received (0: none)
 
 
 def rand_variant(rng, kind=None):
@@ -227,3 +228,24 @@ def test_cost_model_on_shapes_it_was_not_fitted_on():
         assert np.median(err) < 0.15, (shape, float(np.median(err)))
     assert max(picks) <= 1.10 and float(np.mean(picks)) <= 1.03, picks
     assert max(firsts) <= 1.02, firsts
+
+
+def test_case_study3_hint_sequence_through_the_library():
+    """The same pin as in test_loop_oracle.py (the hints behind the rounds of the paper's Case Study 3: staging,
+    occupancy, staging, occupancy), through tf_refine_hint with every report carrying the hint it received."""
+    from test_loop_oracle import case_study3_hint_sequence
+    hw = tf.hw_nominal()
+
+    def chain(r, h):
+        r = dict(r)
+        r["bottleneck"] = h
+        return r
+
+    def refine(prev, r):
+        r = dict(r)
+        r.setdefault("bottleneck", 0)
+        return tf.refine_hint(c_report(prev) if prev else None, c_report(r), hw)
+
+    hints = case_study3_hint_sequence(refine, chain)
+    assert hints[:4] == [tf.TF_BN_LATENCY, tf.TF_BN_OCCUPANCY, tf.TF_BN_LATENCY, tf.TF_BN_OCCUPANCY]
+    assert (tf.TF_BN_LATENCY, tf.TF_BN_OCCUPANCY) == (lo.LATENCY, lo.OCCUPANCY)

@@ -212,11 +212,49 @@ def test_the_two_hints_the_paper_spells_out():
     assert lo.moves_in_direction(hint, base, variant(bm=64, bn=64, stages=2, lds=16384), 1.0, 1.0)
     assert lo.moves_in_direction(hint, base, variant(bm=128, bn=128, stages=2, lds=32768), 1.0, 1.0)
     assert not lo.moves_in_direction(hint, base, variant(bm=256, bn=256, stages=2, lds=131072), 1.0, 1.0)
-    # Case Study 3, round 4 -> 5: the deep pipeline that left one resident work-group was the slowest round, and
-    # the next step went to a configuration with less shared memory: slower than before with an unchanged
-    # "nothing saturated" reading must turn the hint round (tile size against resident work-groups)
+
+
+def case_study3_hint_sequence(refine, chain):
+    """The hints RefineHint gives along the five rounds of Case Study 3, each report carrying the hint it received
+    (`chain(report, hint)`), the profile figures taken from the paper's table (a kernel above the ridge: a matrix
+    product)."""
     rows = load_case_study3()
-    r3 = report(rows[2]["total_ms"] * 1e3, pct_mfma_peak=rows[2]["sm"], pct_hbm_peak=rows[2]["mem"], occupancy_pct=rows[2]["occ"])
-    r4 = report(rows[3]["total_ms"] * 1e3, pct_mfma_peak=rows[3]["sm"], pct_hbm_peak=rows[3]["mem"], occupancy_pct=rows[3]["occ"])
-    assert lo.classify(r3, HW) == lo.classify(r4, HW)
-    assert lo.refine_hint(r3, r4, HW) != lo.classify(r4, HW)
+    hints, prev = [], None
+    for row in rows:
+        r = report(row["total_ms"] * 1e3, pct_mfma_peak=row["sm"], pct_hbm_peak=row["mem"], occupancy_pct=row["occ"])
+        h = refine(prev, r)
+        hints.append(h)
+        prev = chain(r, h)
+    return hints
+
+
+def test_case_study3_hints_follow_the_papers_rounds():
+    # Sec. 5, Case Study 3, what each round did after the profile of the one before:
+    #   round 2: a pre-transposed operand to get coalesced access      -> data movement / staging   (after round 1)
+    #   round 3: smaller tiles and fewer stages to lower register use   -> occupancy                 (after round 2, 4 % slower)
+    #   round 4: deep pipelining (four stages), full coalescing         -> staging again             (after round 3, slower still)
+    #   round 5: configurations with little shared memory, so that several work-groups stay resident -> occupancy (after round 4, the slowest)
+    # Every round after the first was slower than the one before it, and each time the paper's next move went the
+    # other way between "stage / tile differently" and "make room for more resident work-groups".
+    def chain(r, h):
+        r = dict(r)
+        r["bottleneck"] = h
+        return r
+    hints = case_study3_hint_sequence(lambda p, r: lo.refine_hint(p, r, HW), chain)
+    assert hints[:4] == [lo.LATENCY, lo.OCCUPANCY, lo.LATENCY, lo.OCCUPANCY]
+    # the moves the paper made lie in those directions: round 4 (four stages, about 140 KB of shared memory) from
+    # round 3's configuration (64 x 128 tiles, two stages); round 5 (under 76 KB, three stages) from round 4's
+    r3cfg = variant(bm=64, bn=128, stages=2, lds=32768)
+    r4cfg = variant(bm=64, bn=128, stages=4, lds=140 * 1024)
+    assert lo.moves_in_direction(hints[2], r3cfg, r4cfg, 1.0, 1.0)
+    assert not lo.moves_in_direction(hints[3], r3cfg, r4cfg, 1.0, 1.0)
+    r5cfg = variant(bm=64, bn=128, stages=3, lds=76 * 1024)
+    assert lo.moves_in_direction(hints[3], r4cfg, r5cfg, 1.0, 1.0)
+    assert not lo.moves_in_direction(hints[3], r5cfg, r4cfg, 1.0, 1.0)
+    # round 3's smaller tiles from a larger configuration
+    assert lo.moves_in_direction(hints[1], variant(bm=128, bn=128, stages=3, lds=98304), r3cfg, 1.0, 1.0)
+    # round 5 is faster than round 4: no turn, the hint is what its own figures say
+    rows = load_case_study3()
+    r4 = report(rows[3]["total_ms"] * 1e3, pct_mfma_peak=rows[3]["sm"], pct_hbm_peak=rows[3]["mem"], occupancy_pct=rows[3]["occ"], bottleneck=hints[3])
+    r5 = report(rows[4]["total_ms"] * 1e3, pct_mfma_peak=rows[4]["sm"], pct_hbm_peak=rows[4]["mem"], occupancy_pct=rows[4]["occ"])
+    assert lo.refine_hint(r4, r5, HW) == lo.classify(r5, HW)
