@@ -356,8 +356,12 @@ tf_status tf_problem_set_counter_files(tf_problem* p, const char* const* csv_pat
 int32_t tf_arbiter(const tf_report* cand, const tf_report* best, const tf_theta* theta,
                    int32_t best_is_baseline, int32_t stall_rounds, int32_t round);
 
-/* Targeted-Refinement-Hint: classifies the bottleneck of `cand` (tf_bottleneck). `prev` may be
- * NULL. */
+/* Targeted-Refinement-Hint (Sec. 3.3): classifies the bottleneck of `cand` (tf_bottleneck) from its
+ * counters if it has any, else from its achieved rates. `prev` (may be NULL) is the report of the
+ * round before, whose bottleneck field is the hint `cand` was proposed under (TF_BN_UNKNOWN: read
+ * from prev's own figures): if cand is more than 2 % slower than prev and its figures call for that
+ * same remedy again, the remedy has just failed and the hint turns round between "occupancy" and
+ * "latency" (the alternation of the rounds of Case Study 3, Sec. 5). */
 int32_t tf_refine_hint(const tf_report* prev, const tf_report* cand, const tf_hw* hw);
 
 /* Proposal: id of the next candidate among family[0..n), none of which has tried[id] != 0,
