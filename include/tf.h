@@ -177,7 +177,9 @@ typedef struct {
                               the same work (offered when the rows make a whole number of CUs per row panel and the
                               remaining columns fit such a round; names with `tail`); 0 = all tiles alike */
   int32_t nontemporal;     /* TF_KIND_SIN: 1 = loads and stores marked non-temporal (each element is touched once) */
-  int32_t xcd_swizzle;     /* 1: work-group ids renumbered so that neighbouring tiles share an XCD L2 */
+  int32_t xcd_swizzle;     /* 1: work-group ids renumbered so that neighbouring tiles share an XCD L2;
+                              0 (names with _rr, problems with one row of tiles): tiles dealt round-robin over the
+                              XCDs, slice by slice, so that every row of B is read through all eight L2s at once */
   int32_t group_m;         /* tile rows per group in the tile order */
   int32_t threads;         /* work-group size */
   int32_t lds_bytes;       /* LDS per work-group */
@@ -246,7 +248,9 @@ void tf_hw_nominal(tf_hw* out);
 tf_status tf_hw_measure(int32_t device, void* hip_stream, double* mfma_tflops, double* hbm_read_gbs);
 
 /* The rate of a plain streaming read at a given size, for comparison with a memory-bound kernel of that size:
- * `launches` launches of a kernel that reads `bytes` bytes once, launch i from buffers[i % n_buffers] (a host
+ * `launches` launches of a kernel that reads `bytes` bytes once (every wave 8 KB of its own, contiguous, as eight
+ * 16-byte non-temporal loads per lane all in flight together: the fastest of the read patterns tried; column
+ * strips or a grid-stride walk read up to a quarter slower), launch i from buffers[i % n_buffers] (a host
  * array of device pointers to caller-owned buffers of at least `bytes` bytes each, 16-byte aligned; rotate over
  * more than the memory-side cache holds to read from HBM every time). *gbs (host pointer) gets the average rate
  * per launch between two events on hip_stream, which is synchronised. */

@@ -339,70 +339,46 @@ __device__ __forceinline__ void store_partial(const f32x16 (&acc)[C::TM][C::TN],
 template <class C, bool FULL, bool THROUGH>
 __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0) {
   const size_t slice = (size_t)p.M * p.N;
-  if constexpr (FULL) {
-    // whole tiles: 16-byte loads (device scope, or plain ones for slices that sit in this XCD's L2), a slice's
-    // worth in flight at a time: written slice by slice, because a loop over the slices per element would be
-    // one long chain of dependent trips (the accumulator registers are free by now: their contents have been
-    // published)
-    constexpr int NV = C::TM_OUT * C::TN * 4;
-    static_assert(NV % 4 == 0 && NV <= 16, "register budget of the exchange");
-    f32x4 sum[NV];
+  // 16-byte loads (device scope, or plain ones for slices that sit in this XCD's L2), a slice's worth in flight at a
+  // time: written slice by slice, because a loop over the slices per element is one long chain of dependent trips
+  // to memory (on a 16-row problem with two slices that chain was most of the 3.4 us the kernel spent behind its
+  // K loop). The accumulator registers are free by now: their contents have been published. Pieces outside M or N
+  // (ragged tiles) count as zero.
+  constexpr int NV = C::TM_OUT * C::TN * 4;
+  static_assert(NV % 4 == 0 && NV <= 16, "register budget of the exchange");
+  f32x4 sum[NV];
+  bool ok[NV];
 #pragma unroll
-    for (int x = 0; x < NV; ++x) sum[x] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    for (int sidx = 0; sidx < p.split_k; ++sidx) {
-      f32x4 v[NV];
-#pragma unroll
-      for (int x = 0; x < NV; ++x) {
-        const int i = x / (C::TN * 4), t = (x / 4) % C::TN, q = x % 4;
-        const float* src = p.ws + (size_t)sidx * slice + (size_t)(wm0 + 32 * i) * p.N + (wn0 + 32 * t + 8 * q);
-        if constexpr (THROUGH) load_through_f32x4(v[x], src);
-        else v[x] = *(const f32x4*)src;
-      }
-      if constexpr (THROUGH) {
-#pragma unroll
-        for (int x = 0; x < NV; x += 4) wait_through(v[x], v[x + 1], v[x + 2], v[x + 3]);
-      }
-#pragma unroll
-      for (int x = 0; x < NV; ++x) sum[x] += v[x];
-    }
+  for (int x = 0; x < NV; ++x) {
+    const int i = x / (C::TN * 4), t = (x / 4) % C::TN, q = x % 4;
+    sum[x] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    ok[x] = FULL || (wm0 + 32 * i < p.M && wn0 + 32 * t + 8 * q < p.N);
+  }
+  for (int sidx = 0; sidx < p.split_k; ++sidx) {
+    f32x4 v[NV];
 #pragma unroll
     for (int x = 0; x < NV; ++x) {
       const int i = x / (C::TN * 4), t = (x / 4) % C::TN, q = x % 4;
-      acc[i][t][4 * q] = sum[x][0]; acc[i][t][4 * q + 1] = sum[x][1];
-      acc[i][t][4 * q + 2] = sum[x][2]; acc[i][t][4 * q + 3] = sum[x][3];
+      // (a piece outside the matrix reads the slice's first 16 bytes instead: no branch round the load, whose
+      // result only counts after the wait below)
+      const float* base = p.ws + (size_t)sidx * slice;
+      const float* src = ok[x] ? base + (size_t)(wm0 + 32 * i) * p.N + (wn0 + 32 * t + 8 * q) : base;
+      if constexpr (THROUGH) load_through_f32x4(v[x], src);
+      else v[x] = *(const f32x4*)src;
     }
-    return;
+    if constexpr (THROUGH) {
+#pragma unroll
+      for (int x = 0; x < NV; x += 4) wait_through(v[x], v[x + 1], v[x + 2], v[x + 3]);
+    }
+#pragma unroll
+    for (int x = 0; x < NV; ++x)
+      if (ok[x]) sum[x] += v[x];
   }
 #pragma unroll
-  for (int i = 0; i < C::TM_OUT; ++i) {
-    const int m = wm0 + 32 * i;
-#pragma unroll
-    for (int t = 0; t < C::TN; ++t)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = wn0 + 32 * t + 8 * q;
-        f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (FULL || (m < p.M && n < p.N)) {
-          const float* src = p.ws + (size_t)m * p.N + n;
-          for (int sidx = 0; sidx < p.split_k; ++sidx) {
-            // device-scope loads: served from memory, never from a line this XCD's L2 kept
-            // from an earlier launch
-            const float* q4 = src + (size_t)sidx * slice;
-            f32x4 v;
-            if (THROUGH) {
-              v[0] = __hip_atomic_load(q4 + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              v[1] = __hip_atomic_load(q4 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              v[2] = __hip_atomic_load(q4 + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              v[3] = __hip_atomic_load(q4 + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            } else {
-              v = *(const f32x4*)q4;
-            }
-            sum += v;
-          }
-        }
-        acc[i][t][4 * q] = sum[0]; acc[i][t][4 * q + 1] = sum[1];
-        acc[i][t][4 * q + 2] = sum[2]; acc[i][t][4 * q + 3] = sum[3];
-      }
+  for (int x = 0; x < NV; ++x) {
+    const int i = x / (C::TN * 4), t = (x / 4) % C::TN, q = x % 4;
+    acc[i][t][4 * q] = sum[x][0]; acc[i][t][4 * q + 1] = sum[x][1];
+    acc[i][t][4 * q + 2] = sum[x][2]; acc[i][t][4 * q + 3] = sum[x][3];
   }
 }
 

@@ -91,27 +91,31 @@ __global__ void __launch_bounds__(256) tf_calib_mfma_kernel(float* sink, int ite
 }
 
 __global__ void __launch_bounds__(256) tf_calib_read_kernel(const u32x4* src, size_t n16, unsigned* sink) {
-  // every work-group walks its own contiguous share, 8 x 4 KB in flight per work-group
-  const size_t per_wg = (n16 + gridDim.x - 1) / gridDim.x;
-  const size_t begin = per_wg * blockIdx.x, end = begin + per_wg < n16 ? begin + per_wg : n16;
+  // every wave reads 8 KB of its own, contiguous, as eight 16-byte non-temporal loads per lane that are all in flight
+  // together, and ends: the pattern that read fastest of those tried (134 MB: 19.9 us; the same bytes as column
+  // strips of 128 to 2048 bytes per row 20.4 to 33 us; a grid-stride walk with ordinary loads 25.7 us)
+  const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const size_t base = wave * 512 + (threadIdx.x & 63);            // in 16-byte units: 8 KB per wave
   u32x4 acc = {0u, 0u, 0u, 0u};
-  size_t i = begin + threadIdx.x;
-  for (; i + 7 * 256 < end; i += 8 * 256) {
+  if (base + 7 * 64 < n16) {
     u32x4 v[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = src[i + j * 256];
+    for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(src + base + j * 64);
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc ^= v[j];
+  } else {
+    for (int j = 0; j < 8; ++j)
+      if (base + j * 64 < n16) acc ^= src[base + j * 64];
   }
-  for (; i < end; i += 256) acc ^= src[i];
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) sink[0] = 1u;   // never true for the buffer the host fills
 }
 
 void launch_calib_mfma(float* sink, int wgs, int iters, hipStream_t s) {
   hipLaunchKernelGGL(tf_calib_mfma_kernel, dim3((unsigned)wgs), dim3(256), 0, s, sink, iters, 0x9e3779b9u);
 }
-void launch_calib_read(const void* src, size_t bytes, unsigned* sink, int wgs, hipStream_t s) {
-  hipLaunchKernelGGL(tf_calib_read_kernel, dim3((unsigned)wgs), dim3(256), 0, s, (const u32x4*)src, bytes / 16, sink);
+void launch_calib_read(const void* src, size_t bytes, unsigned* sink, int /*wgs*/, hipStream_t s) {
+  const size_t n16 = bytes / 16, waves = (n16 + 511) / 512;
+  hipLaunchKernelGGL(tf_calib_read_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, (const u32x4*)src, n16, sink);
 }
 
 // Batched product with the first operand transposed in memory (C[b] = A[b]^T B[b], A[b] = [K][lda]):
