@@ -339,11 +339,10 @@ __device__ __forceinline__ void store_partial(const f32x16 (&acc)[C::TM][C::TN],
 template <class C, bool FULL, bool THROUGH>
 __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const GemmParams& p, int wm0, int wn0) {
   const size_t slice = (size_t)p.M * p.N;
-  // 16-byte loads (device scope, or plain ones for slices that sit in this XCD's L2), a slice's worth in flight at a
-  // time: written slice by slice, because a loop over the slices per element is one long chain of dependent trips
-  // to memory (on a 16-row problem with two slices that chain was most of the 3.4 us the kernel spent behind its
-  // K loop). The accumulator registers are free by now: their contents have been published. Pieces outside M or N
-  // (ragged tiles) count as zero.
+  // 16-byte loads (device scope, or plain ones for slices that sit in this XCD's L2), whole slices in flight at a
+  // time: a loop over the slices per element is one long chain of dependent trips to memory, and everything behind
+  // the K loop of a memory-bound problem is time in which nothing is streamed. The accumulator registers are free
+  // by now: their contents have been published. Pieces outside M or N (ragged tiles) count as zero.
   constexpr int NV = C::TM_OUT * C::TN * 4;
   static_assert(NV % 4 == 0 && NV <= 16, "register budget of the exchange");
   f32x4 sum[NV];
@@ -354,25 +353,37 @@ __device__ __forceinline__ void sum_partials(f32x16 (&acc)[C::TM][C::TN], const 
     sum[x] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     ok[x] = FULL || (wm0 + 32 * i < p.M && wn0 + 32 * t + 8 * q < p.N);
   }
-  for (int sidx = 0; sidx < p.split_k; ++sidx) {
-    f32x4 v[NV];
+  // G slices are loaded together (as many as sixteen 16-byte vectors per lane allow: small tiles with two or four
+  // slices make one trip to memory in all), then added in slice order
+  constexpr int G = NV <= 4 ? 4 : (NV <= 8 ? 2 : 1);
+  for (int s0 = 0; s0 < p.split_k; s0 += G) {
+    f32x4 v[G][NV];
 #pragma unroll
-    for (int x = 0; x < NV; ++x) {
-      const int i = x / (C::TN * 4), t = (x / 4) % C::TN, q = x % 4;
-      // (a piece outside the matrix reads the slice's first 16 bytes instead: no branch round the load, whose
-      // result only counts after the wait below)
+    for (int g = 0; g < G; ++g) {
+      // (a slice past the last one reads the last one again and is not added)
+      const int sidx = s0 + g < p.split_k ? s0 + g : p.split_k - 1;
       const float* base = p.ws + (size_t)sidx * slice;
-      const float* src = ok[x] ? base + (size_t)(wm0 + 32 * i) * p.N + (wn0 + 32 * t + 8 * q) : base;
-      if constexpr (THROUGH) load_through_f32x4(v[x], src);
-      else v[x] = *(const f32x4*)src;
+#pragma unroll
+      for (int x = 0; x < NV; ++x) {
+        const int i = x / (C::TN * 4), t = (x / 4) % C::TN, q = x % 4;
+        // (a piece outside the matrix reads the slice's first 16 bytes instead: no branch round the load, whose
+        // result only counts after the wait below)
+        const float* src = ok[x] ? base + (size_t)(wm0 + 32 * i) * p.N + (wn0 + 32 * t + 8 * q) : base;
+        if constexpr (THROUGH) load_through_f32x4(v[g][x], src);
+        else v[g][x] = *(const f32x4*)src;
+      }
     }
     if constexpr (THROUGH) {
 #pragma unroll
-      for (int x = 0; x < NV; x += 4) wait_through(v[x], v[x + 1], v[x + 2], v[x + 3]);
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int x = 0; x < NV; x += 4) wait_through(v[g][x], v[g][x + 1], v[g][x + 2], v[g][x + 3]);
     }
 #pragma unroll
-    for (int x = 0; x < NV; ++x)
-      if (ok[x]) sum[x] += v[x];
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int x = 0; x < NV; ++x)
+        if (ok[x] && s0 + g < p.split_k) sum[x] += v[g][x];
   }
 #pragma unroll
   for (int x = 0; x < NV; ++x) {
