@@ -498,6 +498,10 @@ tf_status do_launch(tf_problem* p, int id, const void* A, const void* B, const v
   // count is a multiple of eight - what the L2-local reduction needs)
   g.slice_major = v.split_k > 1 && v.kind == TF_KIND_MFMA_LDS && (v.fused_reduce == 0 || !v.xcd_swizzle);
   g.k_rotate = v.k_rotate;
+  // where the tiles go round-robin over the XCDs (one row of tiles: a streaming problem), four or more slices also
+  // take the K tiles in turn (16 x 8192 x 8192, 32 x 128 tiles, four slices: 28.3 -> 26.7 us; with two slices and
+  // four buffers the two halves of K stream better: 26.6 against 27.9 us)
+  g.k_interleave = v.kind == TF_KIND_MFMA_LDS && !v.xcd_swizzle && v.split_k >= 4 && v.direct_to_lds && !v.stream_k;
   g.epi = d.epi; g.split_k = v.split_k; g.fused_reduce = v.fused_reduce; g.group_m = v.group_m > 0 ? v.group_m : 1; g.xcd_swizzle = v.xcd_swizzle;
   if (v.kind == TF_KIND_SIN) {
     if (im.lds_index < 0) {

@@ -191,7 +191,9 @@ __global__ void __launch_bounds__(C::THREADS) tf_gemm_stream_kernel(const GemmPa
     unsigned long long* ctr = (unsigned long long*)p.counters + tn;
     const unsigned xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 7u;      // HW_REG_XCC_ID
     const unsigned long long mine = 1ull + (1ull << (8 + 7 * xcc));
-    if (threadIdx.x == 0) ticket = atomicAdd(ctr, mine) + mine;
+    // (L2-local mode: the ticket is taken in this XCD's L2 too, with an atomic of narrower scope)
+    if (threadIdx.x == 0)
+      ticket = (local ? __hip_atomic_fetch_add(ctr, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : atomicAdd(ctr, mine)) + mine;
     __syncthreads();
     const unsigned long long tk = ticket;
     if ((unsigned)(tk & 255u) != (unsigned)p.split_k) return;

@@ -31,6 +31,7 @@ struct GemmParams {
   int stream_k;           // 1: work-groups from sk_first_wg on share the K steps of the last sk_tiles tiles evenly
   int sk_first_wg, sk_tiles, sk_wgs;   // (stream_k) first such work-group = number of tiles computed whole; tiles and work-groups of the shared part
   int k_rotate;           // 1: the K tiles of a work-group start a (blockIdx mod 8) / 8 of the way in and wrap round
+  int k_interleave;       // 1 (split-K, direct staging): slice s takes the K tiles s, s + split_k, ... instead of a contiguous range
   int batch_xcd;          // batched problems: 1 = all tiles of a batch item on one XCD (batch a multiple of 8)
   int ws_vec16;           // 1: the split-K workspace starts on a 16-byte boundary (its rows of N floats then do too)
   int y_vec16;            // 1: every row of Y (of every batch item) starts on a 16-byte boundary
