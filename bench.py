@@ -53,6 +53,7 @@ HBM_TRAFFIC_KIB = {
     ("C3", "lds_256x256x64_w4x2_s2_direct_tail192_sk1"): (305593.8, 89317.6),
     ("C2", "lds_128x128x64_w2x4_s3_direct_sk1x"): (24699.8, 8192.0),
     ("C4", "lds_32x64x64_w1x2_s4_direct_rr_sk2l"): (67329.2, 1292.0),
+    ("C4", "lds_32x128x64_w1x4_s3_direct_rr_sk4l"): (67907.3, 2314.0),
     ("C5", "lds_256x128x64_w4x2_s3_direct_sk8r"): (32862.6 + 16419.2, 32768.0 + 2048.0),     # main kernel + reduce kernel
     ("V2", "vecmat_r1_u4_w4_g0"): (525341.2, 1024.1),
     ("V2", "vecmat_r1_u8_w4_g0"): (525349.2, 1024.0),
