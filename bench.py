@@ -45,16 +45,16 @@ GEMM_WORKLOADS = ["C1", "C2", "C3", "C4", "C5"]
 FETCH_SCALE, WRITE_SCALE = 262144.0 / 131084.9, 1.0
 TRAFFIC_SOURCE = "recorded: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, see profiles/"
 HBM_TRAFFIC_KIB = {
-    ("C3", "lds_256x256x64_w2x4_s2_direct_tail192_sk1x"): (305585.0, 89131.7),
+    ("C3", "lds_256x256x64_w2x4_s2_direct_tail192_sk1x"): (305622.6, 89178.8),
     # the same compiled kernel with the plain K order, and the 4 x 2 wave arrangement (profiles/variant_loop_C3_...: the
     # FETCH_SIZE and WRITE_SIZE passes of the loop with --also-launch hold every large-tile kernel)
-    ("C3", "lds_256x256x64_w2x4_s2_direct_tail192_sk1"): (305580.4, 89412.7),
-    ("C3", "lds_256x256x64_w4x2_s2_direct_tail192_sk1x"): (305593.8, 89317.6),
-    ("C3", "lds_256x256x64_w4x2_s2_direct_tail192_sk1"): (305593.8, 89317.6),
-    ("C2", "lds_128x128x64_w2x4_s3_direct_sk1x"): (24699.8, 8192.0),
-    ("C4", "lds_32x64x64_w1x2_s4_direct_rr_sk2l"): (67329.2, 1292.0),
+    ("C3", "lds_256x256x64_w2x4_s2_direct_tail192_sk1"): (305625.4, 89372.0),
+    ("C3", "lds_256x256x64_w4x2_s2_direct_tail192_sk1x"): (305578.3, 89223.8),
+    ("C3", "lds_256x256x64_w4x2_s2_direct_tail192_sk1"): (305578.3, 89223.8),
+    ("C2", "lds_128x128x64_w2x4_s3_direct_sk1x"): (24691.8, 8192.0),
+    ("C4", "lds_32x64x64_w1x2_s4_direct_rr_sk2l"): (67342.1, 1292.0),
     ("C4", "lds_32x128x64_w1x4_s3_direct_rr_sk4l"): (67907.3, 2314.0),
-    ("C5", "lds_256x128x64_w4x2_s3_direct_sk8r"): (32862.6 + 16419.2, 32768.0 + 2048.0),     # main kernel + reduce kernel
+    ("C5", "lds_256x128x64_w4x2_s3_direct_sk8r"): (32872.2 + 16411.6, 32768.0 + 2048.0),     # main kernel + reduce kernel
     ("V2", "vecmat_r1_u4_w4_g0"): (525341.2, 1024.1),
     ("V2", "vecmat_r1_u8_w4_g0"): (525349.2, 1024.0),
     ("E2", "sin_b1024_t256_v4_g0_nt"): (131091.8, 262147.1),
