@@ -136,3 +136,23 @@ def test_l2_local_reduction_is_offered_for_whole_line_rows_only():
         ws = {v.workspace_bytes - (2 if v.stream_k else v.split_k) * M * N * 4 for v in vs if v.workspace_bytes > 0}
         assert len(ws) <= 1 and all(w >= 256 + 8 and w % 256 == 0 for w in ws)
     assert seen_l > 0
+
+
+def test_round_robin_placement_is_offered_for_one_row_of_tiles_only():
+    # tiles dealt round-robin over the XCDs (names with _rr, xcd_swizzle 0) suit problems whose every byte of B is read
+    # by one work-group; with several rows of tiles the work-groups of an XCD share panels and keep their contiguous run
+    with tf.Problem(16, 8192, 8192) as p:
+        vs = p.variants()
+        rr = [v for v in vs if v.xcd_swizzle == 0 and v.kind == tf.TF_KIND_MFMA_LDS]
+        assert rr and all(b"_rr_" in v.name for v in rr)
+        assert all(v.bm >= 16 and -(-16 // v.bm) == 1 for v in rr)
+        # each has its twin with the contiguous placement, and the L2-local reduction is still offered (64 or 128 tiles:
+        # a multiple of eight, so the slices of a tile stay on one XCD)
+        names = {v.name.decode() for v in vs}
+        assert all(v.name.decode().replace("_rr_", "_") in names for v in rr)
+        assert any(v.fused_reduce == 2 for v in rr)
+    with tf.Problem(2048, 2048, 2048) as p:
+        assert not [v for v in p.variants() if v.kind == tf.TF_KIND_MFMA_LDS and v.xcd_swizzle == 0]
+    with tf.Problem(64, 4096, 4096) as p:
+        rr = [v for v in p.variants() if v.kind == tf.TF_KIND_MFMA_LDS and v.xcd_swizzle == 0]
+        assert rr and all(v.bm >= 64 for v in rr)          # 64-row tiles: one row of tiles; 32-row tiles: two rows, no _rr
