@@ -50,3 +50,36 @@ def test_random_shape(case):
                 err = np.abs(got - want[epi])
                 bound = gu.preact_bound(z, s, K) if f32 else gu.strict_bound(want[epi], z, s, K)
                 assert np.all(err <= bound), "%s: worst excess %g" % (name, (err - bound).max())
+
+
+def skinny_shapes():
+    """One row of tiles (M <= 32) and a whole number of 64-column tiles: the shapes that are offered the round-robin
+    placement over the XCDs, the K tiles dealt to the slices in turn and the L2-local reduction."""
+    rng = np.random.default_rng(20251210)
+    out = []
+    for i in range(8):
+        out.append((int(rng.integers(1, 33)), 64 * int(rng.integers(1, 129)), 64 * int(rng.integers(1, 65)), i % 2))
+    return out
+
+
+@pytest.mark.parametrize("case", skinny_shapes())
+def test_random_skinny_shape_every_tile_variant(case):
+    M, N, K, b_as_nk = case
+    A, B, bias = wl.make_custom(M, N, K, seed=2000 + M + N + K)
+    y, z, s = orc.gemm_bias_gelu(A, B, bias)
+    dA, dbias = gu.to_dev(A), gu.to_dev(bias)
+    dB = gu.to_dev(np.ascontiguousarray(B.T)) if b_as_nk else gu.to_dev(B)
+    out = gu.OutBuf(M, N)
+    bound = gu.strict_bound(y, z, s, K)
+    with tf.Problem(M, N, K, trans_b=b_as_nk) as prob:
+        tiles = [v for v in prob.variants() if v.kind in (tf.TF_KIND_MFMA_LDS, tf.TF_KIND_MFMA_STREAM)]
+        assert tiles
+        for v in tiles:
+            name = v.name.decode()
+            print("case", case, "variant", name, flush=True)
+            got, intact, _ = gu.run_variant(prob, v.id, dA, dB, dbias, out)
+            assert intact, "%s wrote outside Y" % name
+            assert not np.isnan(got).any(), "%s left elements unwritten" % name
+            err = np.abs(got - y)
+            assert np.all(err <= bound), "%s: worst excess %g" % (name, (err - bound).max())
+            prob.workspace_status()
