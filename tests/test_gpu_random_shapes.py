@@ -58,7 +58,9 @@ def skinny_shapes():
     rng = np.random.default_rng(20251210)
     out = []
     for i in range(8):
-        out.append((int(rng.integers(1, 33)), 64 * int(rng.integers(1, 129)), 64 * int(rng.integers(1, 65)), i % 2))
+        # every other N a multiple of 1024: tile counts that are multiples of eight (what the L2-local reduction needs)
+        N = 1024 * int(rng.integers(1, 9)) if i % 4 < 2 else 64 * int(rng.integers(1, 129))
+        out.append((int(rng.integers(1, 33)), N, 64 * int(rng.integers(1, 65)), i % 2))
     return out
 
 
